@@ -1,0 +1,143 @@
+/*
+ * ssv_nsa.h -- C ABI of the MI355X (gfx950) NSA speculative-verification attention library.
+ *
+ * One call scores a batch of speculative verifier queries (linear draft chains or draft
+ * trees) against a long KV cache with Native Sparse Attention: compressed attention over
+ * pooled KV blocks, per-GQA-group top-n block selection routed by the compressed
+ * probabilities, selected-block attention and sliding-window attention, combined by
+ * per-branch gates (paper Section 2.2).  Selected blocks are loaded once per group of
+ * verifier queries as the sorted, de-duplicated union of their index sets and masked per
+ * query (exact merged schedule, Section 4.2); queries are grouped C at a time so that the
+ * heads of a GQA group times C queries form the rows of the matrix tiles (Section 4.1).
+ * SSV_REFRESH computes and writes the selected indices (routing launch followed by the
+ * downstream launch, Section 5.1); SSV_REUSE reads them and skips index construction
+ * (Section 5.2).
+ *
+ * Conventions
+ *  - Every data pointer is DEVICE memory owned by the caller; `p`, return codes and
+ *    `kernel_ms` are HOST.  The library allocates nothing; scratch comes from `workspace`.
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*); ssv_nsa_verify never
+ *    synchronises.  Nothing is launched when an error code is returned.
+ *  - Per sequence b: L = seq_lens[b] committed tokens occupy KV slots 0..L-1 (slot =
+ *    position); draft token i (flattened order) occupies slot L+i.  parents[b*T+i] is -1
+ *    (child of the last committed token) or the index (< i) of the parent draft token.
+ *    Draft token i sees the L committed tokens, itself and its ancestors.
+ *  - Layout: q [B,T,H,d_k] and out [B,T,H,d_v] contiguous; k, v, k_cmp, v_cmp addressed as
+ *    base + b*stride[0] + kv_head*stride[1] + row*stride[2] (+ contiguous feature), strides
+ *    in elements; gates [B,T,H,3] float32 in the order (compressed, selected, window);
+ *    sel_idx [B,T,H_kv,n_sel] int32, ascending, padded with -1.
+ */
+#ifndef SSV_NSA_H
+#define SSV_NSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SSV_OK            0
+#define SSV_EINVAL       -1   /* null pointer, inconsistent or out-of-range parameter */
+#define SSV_EUNSUPPORTED -2   /* valid NSA problem, but a shape this build has no kernel for */
+#define SSV_EWORKSPACE   -3   /* workspace missing, misaligned or smaller than ssv_nsa_workspace_bytes */
+#define SSV_ELAUNCH      -4   /* the HIP runtime reported an error when enqueueing */
+
+#define SSV_F32  0
+#define SSV_BF16 1
+
+#define SSV_REFRESH 0
+#define SSV_REUSE   1
+
+#define SSV_MAX_T 64          /* verifier queries per sequence */
+
+/* kernels of one call, in launch order (indices into kernel_ms of ssv_nsa_verify_timed) */
+#define SSV_K_STREAM_A  0     /* refresh: compressed scan + window;  reuse: compressed + window + selected */
+#define SSV_K_IMPORTANCE 1    /* refresh only: normalised compressed probabilities summed over the group's heads */
+#define SSV_K_TOPN      2     /* refresh only: block importance + top-n selection */
+#define SSV_K_STREAM_B  3     /* refresh only: selected-block attention over the merged schedule */
+#define SSV_K_COMBINE   4     /* merge of split partial states + gated combination */
+#define SSV_NUM_KERNELS 5
+
+typedef struct ssv_nsa_params {
+    int32_t B;            /* sequences in the batch */
+    int32_t T;            /* verifier queries per sequence (row capacity), 1..SSV_MAX_T */
+    int32_t H, H_kv;      /* query heads, KV heads; H_g = H / H_kv in {1,2,4,8,16} */
+    int32_t d_k, d_v;     /* head dims of K and V; supported (dtype,d_k,d_v): see ssv_nsa_supported */
+    int32_t l, d;         /* compression block length and stride (l % d == 0) */
+    int32_t l_sel;        /* selection block size l' (this build: 64) */
+    int32_t n_sel;        /* selected blocks per query, forced ones included (<= 32) */
+    int32_t w;            /* sliding window, in positions, ending at and including the query */
+    int32_t n_init;       /* forced leading blocks */
+    int32_t n_local;      /* forced blocks ending at the block of the query's own slot */
+    int32_t dtype;        /* SSV_F32 or SSV_BF16: type of q, k, v, k_cmp, v_cmp, out */
+    int32_t mode;         /* SSV_REFRESH: sel_idx is written; SSV_REUSE: sel_idx is read */
+    int32_t group_size;   /* C: verifier queries per workgroup; 0 = as many as fit (C * H_g <= 128) */
+    float   scale;        /* softmax scale; 0 => 1/sqrt(d_k) */
+    int32_t max_seq_len;  /* host-side upper bound on seq_lens[b] (sizes grids and scratch) */
+    int32_t max_n_cmp;    /* host-side upper bound on n_cmp[b] */
+    int32_t reserved;     /* must be 0 */
+    int64_t k_stride[3], v_stride[3], kc_stride[3], vc_stride[3];  /* elements: batch, KV head, row */
+} ssv_nsa_params;
+
+/* How one call is cut into workgroups (host-side planning; filled by ssv_nsa_plan). */
+typedef struct ssv_nsa_plan {
+    int32_t C;                /* verifier queries per group */
+    int32_t n_qg;             /* query groups per (sequence, KV head) */
+    int32_t rows_per_wg;      /* C * H_g */
+    int32_t n_cmp_chunks;     /* workgroups splitting the compressed scan of one group */
+    int32_t tiles_per_chunk;  /* 64-row tiles of k_cmp/v_cmp per such workgroup */
+    int32_t n_win_splits;     /* workgroups splitting the window tiles of one group */
+    int32_t n_slc_splits;     /* workgroups splitting the merged selected-block schedule of one group */
+    int32_t min_tiles_per_split;
+    int32_t n_slots;          /* partial softmax states per output row = sum of the three above */
+    int32_t max_sched_entries;/* capacity of the merged schedule of one group */
+    int64_t workspace_bytes;
+} ssv_nsa_plan;
+
+/*
+ * NSA verification attention (Section 2.2 branches; Section 4.1-4.2 grouping and merged schedule;
+ * Section 5.1 refresh / Section 5.2 reuse).
+ *   q, k, v, k_cmp, v_cmp, gates, out: see layout above.
+ *   seq_lens [B], n_cmp [B] (compressed rows available per sequence), n_query [B] or NULL (= T each),
+ *   tree_parents [B,T] or NULL (= linear chain): device int32.
+ *   A compressed row c (covering slots [c*d, c*d+l)) is used by query i only if c < n_cmp[b] and all
+ *   its slots are visible to i as a contiguous run from slot 0.
+ *   sel_idx: written in SSV_REFRESH; read in SSV_REUSE, where negative, repeated or out-of-range
+ *   entries are ignored.  Rows of queries i >= n_query[b]: out = 0, sel_idx = -1 (refresh).
+ *   workspace: >= ssv_nsa_workspace_bytes(p) bytes, 256-byte aligned; contents need not be preserved
+ *   or initialised between calls; calls sharing a workspace must not overlap in time.
+ * Returns SSV_OK or a negative SSV_E* code.
+ */
+int ssv_nsa_verify(const void* q, const void* k, const void* v, const void* k_cmp, const void* v_cmp,
+                   const float* gates, const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query,
+                   const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Same computation, with a HIP event pair around every kernel; synchronises `stream` before returning and
+ * writes the duration of each kernel in milliseconds to kernel_ms[SSV_NUM_KERNELS] (host; 0 for kernels the
+ * mode does not launch).  Measurement aid for the roofline figures (Section 7 reports per-kernel breakdowns).
+ */
+int ssv_nsa_verify_timed(const void* q, const void* k, const void* v, const void* k_cmp, const void* v_cmp,
+                         const float* gates, const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query,
+                         const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx,
+                         void* workspace, size_t workspace_bytes, void* stream, float* kernel_ms);
+
+/* Validates p (host only, no GPU needed) and describes the launch plan.  Returns SSV_OK or an error code. */
+int ssv_nsa_plan_query(const ssv_nsa_params* p, ssv_nsa_plan* plan);
+
+/* Scratch bytes ssv_nsa_verify needs for p; 0 if p is invalid. */
+size_t ssv_nsa_workspace_bytes(const ssv_nsa_params* p);
+
+/* 1 if this build has kernels for (dtype, d_k, d_v), else 0. */
+int ssv_nsa_supported(int32_t dtype, int32_t d_k, int32_t d_v);
+
+const char* ssv_nsa_strerror(int code);
+const char* ssv_nsa_kernel_name(int kernel_index);
+int ssv_nsa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSV_NSA_H */

@@ -1,0 +1,144 @@
+"""Thin ctypes binding of libssv_nsa.so (include/ssv_nsa.h): argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI.  PyTorch appears here only as the
+owner of device memory and of the stream; nothing in this module computes on tensors.  There is
+no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libssv_nsa.so")
+
+SSV_OK, SSV_EINVAL, SSV_EUNSUPPORTED, SSV_EWORKSPACE, SSV_ELAUNCH = 0, -1, -2, -3, -4
+SSV_F32, SSV_BF16 = 0, 1
+SSV_REFRESH, SSV_REUSE = 0, 1
+SSV_MAX_T = 64
+SSV_NUM_KERNELS = 5
+
+EXPORTS = ("ssv_nsa_verify", "ssv_nsa_verify_timed", "ssv_nsa_plan_query", "ssv_nsa_workspace_bytes",
+           "ssv_nsa_supported", "ssv_nsa_strerror", "ssv_nsa_kernel_name", "ssv_nsa_version")
+
+
+class SsvNsaParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("B", "T", "H", "H_kv", "d_k", "d_v", "l", "d", "l_sel", "n_sel", "w", "n_init", "n_local",
+                 "dtype", "mode", "group_size")] + \
+               [("scale", ctypes.c_float), ("max_seq_len", ctypes.c_int32), ("max_n_cmp", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)] + \
+               [(n, ctypes.c_int64 * 3) for n in ("k_stride", "v_stride", "kc_stride", "vc_stride")]
+
+
+class SsvNsaPlan(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("C", "n_qg", "rows_per_wg", "n_cmp_chunks", "tiles_per_chunk", "n_win_splits", "n_slc_splits",
+                 "min_tiles_per_split", "n_slots", "max_sched_entries")] + [("workspace_bytes", ctypes.c_int64)]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class SsvError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} (code {code})")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built HIP library; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run __graft_entry__.build() (hipcc, gfx950) first")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32p = ctypes.c_void_p, ctypes.c_void_p
+        common = [vp] * 5 + [vp, i32p, i32p, i32p, i32p, ctypes.POINTER(SsvNsaParams), vp, i32p, vp, ctypes.c_size_t, vp]
+        lib.ssv_nsa_verify.restype = ctypes.c_int
+        lib.ssv_nsa_verify.argtypes = common
+        lib.ssv_nsa_verify_timed.restype = ctypes.c_int
+        lib.ssv_nsa_verify_timed.argtypes = common + [ctypes.POINTER(ctypes.c_float)]
+        lib.ssv_nsa_plan_query.restype = ctypes.c_int
+        lib.ssv_nsa_plan_query.argtypes = [ctypes.POINTER(SsvNsaParams), ctypes.POINTER(SsvNsaPlan)]
+        lib.ssv_nsa_workspace_bytes.restype = ctypes.c_size_t
+        lib.ssv_nsa_workspace_bytes.argtypes = [ctypes.POINTER(SsvNsaParams)]
+        lib.ssv_nsa_supported.restype = ctypes.c_int
+        lib.ssv_nsa_supported.argtypes = [ctypes.c_int32] * 3
+        lib.ssv_nsa_strerror.restype = ctypes.c_char_p
+        lib.ssv_nsa_strerror.argtypes = [ctypes.c_int]
+        lib.ssv_nsa_kernel_name.restype = ctypes.c_char_p
+        lib.ssv_nsa_kernel_name.argtypes = [ctypes.c_int]
+        lib.ssv_nsa_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return load_library().ssv_nsa_strerror(code).decode()
+
+
+def kernel_name(idx: int) -> str:
+    return load_library().ssv_nsa_kernel_name(idx).decode()
+
+
+def make_params(*, B, T, H, H_kv, d_k, d_v, l, d, l_sel, n_sel, w, n_init=1, n_local=2, dtype=SSV_BF16,
+                mode=SSV_REFRESH, group_size=0, scale=0.0, max_seq_len, max_n_cmp, k_stride, v_stride, kc_stride,
+                vc_stride) -> SsvNsaParams:
+    p = SsvNsaParams(B=B, T=T, H=H, H_kv=H_kv, d_k=d_k, d_v=d_v, l=l, d=d, l_sel=l_sel, n_sel=n_sel, w=w,
+                     n_init=n_init, n_local=n_local, dtype=dtype, mode=mode, group_size=group_size, scale=scale,
+                     max_seq_len=max_seq_len, max_n_cmp=max_n_cmp, reserved=0)
+    for name, st in (("k_stride", k_stride), ("v_stride", v_stride), ("kc_stride", kc_stride), ("vc_stride", vc_stride)):
+        setattr(p, name, (ctypes.c_int64 * 3)(*[int(x) for x in st]))
+    return p
+
+
+def ssv_nsa_plan_query(p: SsvNsaParams) -> SsvNsaPlan:
+    plan = SsvNsaPlan()
+    rc = load_library().ssv_nsa_plan_query(ctypes.byref(p), ctypes.byref(plan))
+    if rc != SSV_OK:
+        raise SsvError(rc, "ssv_nsa_plan_query")
+    return plan
+
+
+def ssv_nsa_workspace_bytes(p: SsvNsaParams) -> int:
+    return int(load_library().ssv_nsa_workspace_bytes(ctypes.byref(p)))
+
+
+def ssv_nsa_supported(dtype: int, d_k: int, d_v: int) -> bool:
+    return bool(load_library().ssv_nsa_supported(dtype, d_k, d_v))
+
+
+def _ptr(t) -> Optional[int]:
+    """Device pointer of a torch tensor (or a raw integer address, or None)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def ssv_nsa_verify(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_parents, p: SsvNsaParams, out, sel_idx,
+                   workspace, workspace_bytes: int, stream: int, kernel_ms=None) -> None:
+    """Enqueue one verification call on `stream` (a hipStream_t as an integer).
+
+    Tensors are device tensors (or integer device addresses); `p` describes shapes and strides.
+    With kernel_ms (a list), the timed entry point is used: it synchronises the stream and the
+    per-kernel durations in milliseconds are appended to the list.
+    """
+    lib = load_library()
+    args = [_ptr(q), _ptr(k), _ptr(v), _ptr(k_cmp), _ptr(v_cmp), _ptr(gates), _ptr(seq_lens), _ptr(n_cmp),
+            _ptr(n_query), _ptr(tree_parents), ctypes.byref(p), _ptr(out), _ptr(sel_idx), _ptr(workspace),
+            ctypes.c_size_t(int(workspace_bytes)), ctypes.c_void_p(int(stream))]
+    if kernel_ms is None:
+        rc = lib.ssv_nsa_verify(*args)
+    else:
+        ms = (ctypes.c_float * SSV_NUM_KERNELS)()
+        rc = lib.ssv_nsa_verify_timed(*args, ms)
+        kernel_ms.extend(float(x) for x in ms)
+    if rc != SSV_OK:
+        raise SsvError(rc, "ssv_nsa_verify")

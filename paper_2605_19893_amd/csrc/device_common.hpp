@@ -1,0 +1,175 @@
+// Device-side building blocks shared by the gfx950 kernels: MFMA fragment helpers, coalesced
+// global->LDS tile loaders, and the per-sequence draft-tree metadata (Section 2.1, Section 4.1).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ssv {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;   // 4 wavefronts of 64 lanes
+constexpr int kTile = 64;       // KV rows per streamed tile (= one selection block)
+constexpr int kMaxT = 64;
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// One "fragment" is 16 bytes of a row: 8 bf16 or 4 fp32 values of the contraction dimension.
+// A 64-byte chunk of every row is spread over the four 16-lane groups of a wavefront
+// (group G = lane / 16 holds bytes [16 G, 16 G + 16)), and both MFMA operands use the same
+// assignment, so the contraction runs over the whole chunk whatever order the hardware
+// enumerates it in.  Result layout of every 16x16 MFMA: lane (n = lane % 16, G) holds
+// D[4 G + r][n], r = 0..3.
+template <bool BF16>
+__device__ __forceinline__ f32x4 mma_frag(u32x4 a, u32x4 b, f32x4 c) {
+    if constexpr (BF16) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                       0, 0, 0);
+    } else {
+        f32x4 af = __builtin_bit_cast(f32x4, a), bf = __builtin_bit_cast(f32x4, b);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c = __builtin_amdgcn_mfma_f32_16x16x4f32(af[j], bf[j], c, 0, 0, 0);
+        return c;
+    }
+}
+
+__device__ __forceinline__ u32x4 lds_read16(const char* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ u32x2 lds_read8(const char* p) { return *reinterpret_cast<const u32x2*>(p); }
+
+// Row-major copy of up to 64 rows of ROW_BYTES bytes into LDS with row pitch PITCH.
+// Rows >= valid_rows are zero-filled (their memory may not exist or may hold non-finite values).
+template <int ROW_BYTES, int PITCH>
+__device__ __forceinline__ void load_rows_to_lds(char* lds, const char* g, uint32_t g_row_bytes, int valid_rows, int tid) {
+    constexpr int CPR = ROW_BYTES / 16;
+    constexpr int TOTAL = kTile * CPR;
+    constexpr int ITERS = (TOTAL + kThreads - 1) / kThreads;
+    u32x4 val[ITERS];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int f = it * kThreads + tid;
+        const int row = f / CPR, col = f % CPR;
+        val[it] = u32x4{0, 0, 0, 0};
+        const uint32_t off = (uint32_t)row * g_row_bytes + (uint32_t)col * 16u;   // 32-bit offset from a uniform base
+        if (f < TOTAL && row < valid_rows) val[it] = *reinterpret_cast<const u32x4*>(g + off);
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int f = it * kThreads + tid;
+        const int row = f / CPR, col = f % CPR;
+        if (f < TOTAL) *reinterpret_cast<u32x4*>(lds + row * PITCH + col * 16) = val[it];
+    }
+}
+
+// Transposing load: 64 rows x DV values (row-major in global memory) become LDS rows indexed by
+// the value column, each holding the 64 keys contiguously (pitch PITCH), which is the operand
+// layout the P.V MFMA needs (the contraction index, the key, must run along a lane's registers).
+// Each work item reads four consecutive key rows of one 16-byte column chunk and writes, per
+// value column, the four keys as one 8-byte (bf16) or 16-byte (fp32) LDS store.
+template <bool BF16, int DV, int PITCH>
+__device__ __forceinline__ void load_transposed_to_lds(char* lds, const char* g, uint32_t g_row_bytes, int valid_rows,
+                                                       int tid) {
+    constexpr int ES = BF16 ? 2 : 4;
+    constexpr int CPR = DV * ES / 16;           // 16-byte chunks per row
+    constexpr int ITEMS = (kTile / 4) * CPR;    // (key quad, chunk) pairs
+    constexpr int ITERS = (ITEMS + kThreads - 1) / kThreads;
+    u32x4 r[ITERS][4];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int item = it * kThreads + tid;
+        const int kq = item / CPR, ch = item % CPR;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = 4 * kq + j;
+            r[it][j] = u32x4{0, 0, 0, 0};
+            const uint32_t off = (uint32_t)row * g_row_bytes + (uint32_t)ch * 16u;
+            if (item < ITEMS && row < valid_rows) r[it][j] = *reinterpret_cast<const u32x4*>(g + off);
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int item = it * kThreads + tid;
+        const int kq = item / CPR, ch = item % CPR;
+        if (item >= ITEMS) continue;
+        if constexpr (BF16) {
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {    // 32-bit word e2 of the chunk holds columns 2 e2 and 2 e2 + 1
+                const uint32_t w0 = r[it][0][e2], w1 = r[it][1][e2], w2 = r[it][2][e2], w3 = r[it][3][e2];
+                u32x2 lo, hi;
+                lo[0] = (w0 & 0xFFFFu) | (w1 << 16);
+                lo[1] = (w2 & 0xFFFFu) | (w3 << 16);
+                hi[0] = (w0 >> 16) | (w1 & 0xFFFF0000u);
+                hi[1] = (w2 >> 16) | (w3 & 0xFFFF0000u);
+                const int col = ch * 8 + 2 * e2;
+                *reinterpret_cast<u32x2*>(lds + col * PITCH + kq * 8) = lo;
+                *reinterpret_cast<u32x2*>(lds + (col + 1) * PITCH + kq * 8) = hi;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const u32x4 o = {r[it][0][e], r[it][1][e], r[it][2][e], r[it][3][e]};
+                *reinterpret_cast<u32x4*>(lds + (ch * 4 + e) * PITCH + kq * 16) = o;
+            }
+        }
+    }
+}
+
+// Draft-tree metadata of one sequence, rebuilt by every workgroup from the parent indices:
+// ancestor bitmask (bit t set iff draft token t is the query itself or one of its ancestors)
+// and depth (position = L + depth).  parents == nullptr means a linear chain.
+struct SeqMeta {
+    int L, Tq, n_cmp;
+};
+
+__device__ __forceinline__ SeqMeta build_tree_meta(int tid, int b, int T, const int32_t* seq_lens, const int32_t* n_query,
+                                                   const int32_t* n_cmp, const int32_t* parents, int* s_par,
+                                                   int* s_depth, uint64_t* s_anc) {
+    SeqMeta sm;
+    sm.L = seq_lens[b];
+    sm.Tq = n_query ? min(max(n_query[b], 0), T) : T;
+    sm.n_cmp = max(n_cmp[b], 0);
+    if (tid < kMaxT) {
+        int par = tid - 1;
+        if (parents && tid < sm.Tq) {
+            par = parents[(int64_t)b * T + tid];
+            if (par >= tid || par < -1) par = -1;   // malformed entry: treat as a child of the prefix
+        }
+        s_par[tid] = par;
+    }
+    __syncthreads();
+    if (tid < kMaxT) {
+        uint64_t anc = 0;
+        int dep = 0;
+        if (tid < sm.Tq) {
+            if (!parents) {
+                anc = (tid == 63) ? ~0ull : ((2ull << tid) - 1ull);
+                dep = tid;
+            } else {
+                int t = tid;
+                while (t >= 0) {        // strictly decreasing: at most tid + 1 steps
+                    anc |= 1ull << t;
+                    const int pn = s_par[t];
+                    if (pn >= 0) ++dep;
+                    t = pn;
+                }
+            }
+        }
+        s_anc[tid] = anc;
+        s_depth[tid] = dep;
+    }
+    __syncthreads();
+    return sm;
+}
+
+// Number of compressed rows query i may use: complete windows inside the contiguous visible
+// extent E = L + (leading run of visible draft slots), capped by the rows that exist.
+__device__ __forceinline__ int visible_cmp_rows(uint64_t anc, int L, int n_cmp, int l, int d) {
+    const int lead = (~anc == 0ull) ? 64 : __builtin_ctzll(~anc);
+    const int E = L + lead;
+    const int full = E >= l ? (E - l) / d + 1 : 0;
+    return min(full, n_cmp);
+}
+
+}  // namespace ssv

@@ -1,0 +1,368 @@
+// Streaming attention kernel: one workgroup = one (sequence, KV head, group of C verifier queries)
+// and one slice of one branch's key tiles.  The three NSA branches (Section 2.2) are three mask
+// policies over the same tile loop:
+//   CMP  rows of k_cmp / v_cmp, visible while the compressed window is complete for the query;
+//   WIN  raw KV tiles covering the union of the group's sliding windows, masked per row by the
+//        query's own absolute position and tree ancestry (Section 4.1: shared window scan with
+//        per-query local masks);
+//   SLC  raw KV tiles of the merged schedule: the sorted, de-duplicated union of the group's
+//        selected block indices with a query->block ownership mask; every block is loaded once
+//        and logits of non-owning rows are masked to -inf (Section 4.2).
+// Each workgroup writes one partial softmax state (running max, sum, un-normalised P.V) per row;
+// the combine kernel merges the slices of a branch and applies the gates.
+//
+// Matrix tiles: S^T = K . Q^T with K rows as the MFMA M dimension, so that each lane ends up
+// with four consecutive keys of one query row; P^T then is directly the B operand of
+// O^T = V^T . P^T without a round trip through LDS.
+#pragma once
+#include "device_common.hpp"
+
+namespace ssv {
+
+struct StreamArgs {
+    const char *q, *k, *v, *kc, *vc;
+    const int32_t *seq_lens, *n_cmp, *n_query, *parents, *sel_idx;
+    float *part_stats, *part_acc;
+    int B, T, H, H_kv, H_g, C, n_qg;
+    int l, d, n_sel, w;
+    float scale_log2;
+    int n_cmp_chunks, n_win_splits, n_slc_splits, min_tiles;
+    int slot_lo, slot_cnt;   // partial-state slots computed by this launch
+    int n_wg;                // real workgroups (the grid is padded to a multiple of 8)
+    int max_sched, bitmap_words;
+    int64_t rows_total;
+    int64_t k_s[3], v_s[3], kc_s[3], vc_s[3];   // strides in bytes
+};
+
+template <bool BF16, int DK, int DV>
+struct StreamCfg {
+    static constexpr int ES = BF16 ? 2 : 4;
+    static constexpr int KROW = DK * ES;            // bytes per K row
+    static constexpr int KP = KROW + 16;            // LDS pitch of a K row (bank spread)
+    static constexpr int KCH = KROW / 64;           // 64-byte chunks per K row
+    static constexpr int VP = kTile * ES + (BF16 ? 8 : 16);   // LDS pitch of a V^T row (64 keys)
+    static constexpr int MT = DV / 16;              // 16-row tiles of O^T
+    static constexpr int LDS_K = kTile * KP;
+    static constexpr int LDS_VT = DV * VP;
+};
+
+__host__ __device__ inline size_t stream_lds_bytes(size_t lds_k, size_t lds_vt, int max_sched, int bitmap_words) {
+    size_t n = lds_k + lds_vt;
+    n += (size_t)max_sched * 8;          // ownership masks
+    n += (size_t)max_sched * 4;          // block ids
+    n += (size_t)bitmap_words * 4 * 2;   // bitmap + prefix
+    n += kMaxT * 8 + kMaxT * 4 * 2 + 16; // anc, par, depth, scalars
+    return (n + 15) & ~(size_t)15;
+}
+
+enum Role { ROLE_CMP = 0, ROLE_WIN = 1, ROLE_SLC = 2 };
+
+template <bool BF16, int DK, int DV, int NRT>
+__global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
+    using Cfg = StreamCfg<BF16, DK, DV>;
+    constexpr int ES = Cfg::ES, KP = Cfg::KP, KCH = Cfg::KCH, VP = Cfg::VP, MT = Cfg::MT;
+    extern __shared__ __align__(16) char smem[];
+    char* sK = smem;
+    char* sVT = sK + Cfg::LDS_K;
+    uint64_t* s_own = reinterpret_cast<uint64_t*>(sVT + Cfg::LDS_VT);
+    uint64_t* s_anc = s_own + a.max_sched;
+    int* s_id = reinterpret_cast<int*>(s_anc + kMaxT);
+    uint32_t* s_bitmap = reinterpret_cast<uint32_t*>(s_id + a.max_sched);
+    uint32_t* s_prefix = s_bitmap + a.bitmap_words;
+    int* s_par = reinterpret_cast<int*>(s_prefix + a.bitmap_words);
+    int* s_depth = s_par + kMaxT;
+    int* s_scalar = s_depth + kMaxT;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, G = lane >> 4;
+
+    // XCD-aware order: consecutive dispatch ids go round-robin over the 8 XCDs, so give every XCD a
+    // contiguous range of logical work items; the query groups of one (sequence, head, slice), which
+    // read the same tiles, are adjacent in logical order and therefore share an L2.
+    const int n_pad = gridDim.x;
+    const int wg = (blockIdx.x & 7) * (n_pad >> 3) + (blockIdx.x >> 3);
+    if (wg >= a.n_wg) return;
+    const int qg = wg % a.n_qg;
+    const int slot = a.slot_lo + (wg / a.n_qg) % a.slot_cnt;
+    const int bg = wg / (a.n_qg * a.slot_cnt);
+    const int b = bg / a.H_kv, g = bg % a.H_kv;
+
+    int role, part;
+    if (slot < a.n_cmp_chunks) { role = ROLE_CMP; part = slot; }
+    else if (slot < a.n_cmp_chunks + a.n_win_splits) { role = ROLE_WIN; part = slot - a.n_cmp_chunks; }
+    else { role = ROLE_SLC; part = slot - a.n_cmp_chunks - a.n_win_splits; }
+
+    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, s_par, s_depth, s_anc);
+    const int L = sm.L, Tq = sm.Tq;
+    const int nq_grp = min(a.C, Tq - qg * a.C);   // verifier queries of this group that exist
+    const int n_slots_kv = L + Tq;                // raw KV rows that exist for this sequence
+
+    // ---- per-lane row metadata
+    bool rvalid[NRT];
+    uint64_t anc[NRT];
+    int pos[NRT], cmax[NRT], iq[NRT];
+    int64_t grow[NRT];
+#pragma unroll
+    for (int t = 0; t < NRT; ++t) {
+        const int rr = (wave + 4 * t) * 16 + n;
+        iq[t] = rr / a.H_g;
+        const int qi = qg * a.C + iq[t];
+        rvalid[t] = iq[t] < nq_grp;
+        const int qs = rvalid[t] ? qi : 0;
+        anc[t] = rvalid[t] ? s_anc[qs] : 0ull;
+        pos[t] = L + s_depth[qs];
+        cmax[t] = rvalid[t] ? visible_cmp_rows(anc[t], L, sm.n_cmp, a.l, a.d) : 0;
+        grow[t] = ((int64_t)b * a.T + qs) * a.H + g * a.H_g + rr % a.H_g;
+    }
+
+    // ---- tile range of this workgroup
+    int t0 = 0, t1 = 0;           // CMP / WIN: tile indices; SLC: schedule entries
+    if (nq_grp > 0) {
+        if (role == ROLE_CMP) {
+            int cm = 0;
+            for (int j = 0; j < nq_grp; ++j) cm = max(cm, visible_cmp_rows(s_anc[qg * a.C + j], L, sm.n_cmp, a.l, a.d));
+            const int ntiles = (cm + kTile - 1) / kTile;
+            const int per = max(1, (ntiles + a.n_cmp_chunks - 1) / a.n_cmp_chunks);
+            t0 = part * per;
+            t1 = min(ntiles, t0 + per);
+        } else if (role == ROLE_WIN) {
+            int dmin = 1 << 30;
+            for (int j = 0; j < nq_grp; ++j) dmin = min(dmin, s_depth[qg * a.C + j]);
+            const int wlo = max(0, L + dmin - a.w + 1) / kTile;
+            const int whi = (n_slots_kv + kTile - 1) / kTile;
+            const int per = max(1, (whi - wlo + a.n_win_splits - 1) / a.n_win_splits);
+            t0 = wlo + part * per;
+            t1 = min(whi, t0 + per);
+        } else {
+            // merged schedule: bitmap over blocks -> ranks by prefix popcount -> sorted unique list + ownership
+            const int nblk = min((n_slots_kv + kTile - 1) / kTile, a.bitmap_words * 32);
+            const int nwords = (nblk + 31) >> 5;
+            for (int i = tid; i < nwords; i += kThreads) s_bitmap[i] = 0;
+            for (int i = tid; i < a.max_sched; i += kThreads) s_own[i] = 0ull;
+            __syncthreads();
+            const int n_ent = nq_grp * a.n_sel;
+            for (int i = tid; i < n_ent; i += kThreads) {
+                const int j = i / a.n_sel, e = i % a.n_sel;
+                const int id = a.sel_idx[(((int64_t)b * a.T + qg * a.C + j) * a.H_kv + g) * a.n_sel + e];
+                if (id >= 0 && id < nblk) atomicOr(&s_bitmap[id >> 5], 1u << (id & 31));
+            }
+            __syncthreads();
+            if (wave == 0) {
+                const int per = (nwords + 63) >> 6;
+                const int w0 = lane * per, w1 = min(nwords, w0 + per);
+                int cnt = 0;
+                for (int i = w0; i < w1; ++i) cnt += __popc(s_bitmap[i]);
+                int incl = cnt;
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    const int up = __shfl_up(incl, off);
+                    if (lane >= off) incl += up;
+                }
+                int run = incl - cnt;
+                for (int i = w0; i < w1; ++i) { s_prefix[i] = run; run += __popc(s_bitmap[i]); }
+                if (lane == 63) s_scalar[0] = incl;
+            }
+            __syncthreads();
+            for (int i = tid; i < n_ent; i += kThreads) {
+                const int j = i / a.n_sel, e = i % a.n_sel;
+                const int id = a.sel_idx[(((int64_t)b * a.T + qg * a.C + j) * a.H_kv + g) * a.n_sel + e];
+                if (id >= 0 && id < nblk) {
+                    const uint32_t wd = s_bitmap[id >> 5];
+                    const int rank = s_prefix[id >> 5] + __popc(wd & ((1u << (id & 31)) - 1u));
+                    s_id[rank] = id;
+                    atomicOr(reinterpret_cast<unsigned long long*>(&s_own[rank]), 1ull << j);
+                }
+            }
+            __syncthreads();
+            const int len = s_scalar[0];
+            const int per = max(a.min_tiles, (len + a.n_slc_splits - 1) / a.n_slc_splits);
+            t0 = min(len, part * per);
+            t1 = min(len, t0 + per);
+        }
+    }
+
+    // ---- query fragments (B operand of S^T = K Q^T), kept in registers for the whole slice
+    u32x4 qf[NRT][KCH];
+#pragma unroll
+    for (int t = 0; t < NRT; ++t)
+#pragma unroll
+        for (int kc = 0; kc < KCH; ++kc) {
+            qf[t][kc] = u32x4{0, 0, 0, 0};
+            if (rvalid[t] && t0 < t1)
+                qf[t][kc] = *reinterpret_cast<const u32x4*>(a.q + grow[t] * (DK * ES) + kc * 64 + G * 16);
+        }
+
+    f32x4 acc[NRT][MT];
+    float mrun[NRT], zrun[NRT];
+#pragma unroll
+    for (int t = 0; t < NRT; ++t) {
+        mrun[t] = -INFINITY;
+        zrun[t] = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[t][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const char* kbase;
+    const char* vbase;
+    int64_t krow, vrow;
+    if (role == ROLE_CMP) {
+        kbase = a.kc + b * a.kc_s[0] + g * a.kc_s[1];
+        vbase = a.vc + b * a.vc_s[0] + g * a.vc_s[1];
+        krow = a.kc_s[2];
+        vrow = a.vc_s[2];
+    } else {
+        kbase = a.k + b * a.k_s[0] + g * a.k_s[1];
+        vbase = a.v + b * a.v_s[0] + g * a.v_s[1];
+        krow = a.k_s[2];
+        vrow = a.v_s[2];
+    }
+    const int rows_exist = role == ROLE_CMP ? sm.n_cmp : n_slots_kv;
+
+    for (int it = t0; it < t1; ++it) {
+        int tile;
+        uint64_t own = ~0ull;
+        if (role == ROLE_SLC) { tile = s_id[it]; own = s_own[it]; }
+        else tile = it;
+        const int base = tile * kTile;
+        const int valid_rows = min(kTile, rows_exist - base);
+
+        __syncthreads();   // every wave has finished reading the previous tile
+        load_rows_to_lds<Cfg::KROW, KP>(sK, kbase + (int64_t)base * krow, (uint32_t)krow, valid_rows, tid);
+        load_transposed_to_lds<BF16, DV, VP>(sVT, vbase + (int64_t)base * vrow, (uint32_t)vrow, valid_rows, tid);
+        __syncthreads();
+
+#pragma unroll
+        for (int t = 0; t < NRT; ++t) {
+            // ---- validity of this lane's 16 keys (4 key tiles x 4 registers) for its query row
+            uint32_t vm = 0;
+            if (rvalid[t]) {
+                if (role == ROLE_CMP) {
+#pragma unroll
+                    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (base + 16 * kt + 4 * G + r < cmax[t]) vm |= 1u << (4 * kt + r);
+                } else {
+                    const bool is_owner = role == ROLE_WIN || ((own >> iq[t]) & 1ull);
+                    if (is_owner) {
+#pragma unroll
+                        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                const int s = base + 16 * kt + 4 * G + r;
+                                bool ok;
+                                int kpos;
+                                if (s < L) { ok = true; kpos = s; }
+                                else {
+                                    const int dt = s - L;
+                                    ok = dt < Tq && ((anc[t] >> dt) & 1ull);
+                                    kpos = L + s_depth[dt < kMaxT ? dt : 0];
+                                }
+                                if (role == ROLE_WIN) ok = ok && kpos > pos[t] - a.w && kpos <= pos[t];
+                                if (ok) vm |= 1u << (4 * kt + r);
+                            }
+                    }
+                }
+            }
+            if (__builtin_amdgcn_ballot_w64(vm != 0) == 0ull) continue;   // no row of this tile uses these keys
+
+            // ---- S^T = K Q^T
+            f32x4 s[4];
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kc = 0; kc < KCH; ++kc) {
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt) {
+                    const u32x4 kf = lds_read16(sK + (16 * kt + n) * KP + kc * 64 + G * 16);
+                    s[kt] = mma_frag<BF16>(kf, qf[t][kc], s[kt]);
+                }
+                if (kc & 1) __builtin_amdgcn_sched_barrier(0);   // bound the LDS reads in flight (register pressure)
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // ---- online softmax in the log2 domain
+            float mx = -INFINITY;
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float x = ((vm >> (4 * kt + r)) & 1u) ? s[kt][r] * a.scale_log2 : -INFINITY;
+                    s[kt][r] = x;
+                    mx = fmaxf(mx, x);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(mrun[t], mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = fast_exp2(mrun[t] - m_use);
+            float rs = 0.f;
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float pz = fast_exp2(s[kt][r] - m_use);
+                    s[kt][r] = pz;
+                    rs += pz;
+                }
+            rs += __shfl_xor(rs, 16);
+            rs += __shfl_xor(rs, 32);
+            __builtin_amdgcn_sched_barrier(0);
+            zrun[t] = zrun[t] * alpha + rs;
+            mrun[t] = m_new;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[t][mt] *= alpha;
+
+            // ---- O^T += V^T P^T
+            if constexpr (BF16) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    bf16x8 pk;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        pk[r] = (__bf16)s[2 * u][r];
+                        pk[4 + r] = (__bf16)s[2 * u + 1][r];
+                    }
+                    const u32x4 pb = __builtin_bit_cast(u32x4, pk);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const char* row = sVT + (16 * mt + n) * VP;
+                        const u32x2 lo = lds_read8(row + (32 * u + 4 * G) * 2);
+                        const u32x2 hi = lds_read8(row + (32 * u + 16 + 4 * G) * 2);
+                        acc[t][mt] = mma_frag<true>(u32x4{lo[0], lo[1], hi[0], hi[1]}, pb, acc[t][mt]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt) {
+                    const u32x4 pb = __builtin_bit_cast(u32x4, s[kt]);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const u32x4 vf = lds_read16(sVT + (16 * mt + n) * VP + (16 * kt + 4 * G) * 4);
+                        acc[t][mt] = mma_frag<false>(vf, pb, acc[t][mt]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);   // keep the row tiles of a wave from being interleaved
+        }
+    }
+
+    // ---- partial state of this slice: (m, Z) per row and the un-normalised accumulator
+#pragma unroll
+    for (int t = 0; t < NRT; ++t) {
+        if (!rvalid[t]) continue;
+        const int64_t pr = (int64_t)slot * a.rows_total + grow[t];
+        if (G == 0) {
+            a.part_stats[pr * 2 + 0] = mrun[t];
+            a.part_stats[pr * 2 + 1] = zrun[t];
+        }
+        if (zrun[t] > 0.f) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                *reinterpret_cast<f32x4*>(a.part_acc + pr * DV + 16 * mt + 4 * G) = acc[t][mt];
+        }
+    }
+}
+
+}  // namespace ssv

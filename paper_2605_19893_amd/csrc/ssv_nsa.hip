@@ -1,0 +1,319 @@
+// Host side of the C ABI declared in include/ssv_nsa.h: argument validation, launch planning,
+// and the launch sequences of the refresh (Section 5.1) and reuse (Section 5.2) paths.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "../../include/ssv_nsa.h"
+#include "k_combine.hpp"
+#include "k_importance.hpp"
+#include "k_stream.hpp"
+#include "k_topn.hpp"
+
+namespace {
+
+using namespace ssv;
+
+struct Shape { int dtype, d_k, d_v; };
+constexpr Shape kShapes[] = {{SSV_BF16, 192, 128}, {SSV_BF16, 128, 128}, {SSV_BF16, 64, 64}, {SSV_F32, 64, 64}};
+
+int env_int(const char* name, int dflt) {
+    const char* s = std::getenv(name);
+    if (!s || !*s) return dflt;
+    const int v = std::atoi(s);
+    return v > 0 ? v : dflt;
+}
+
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {
+    ssv_nsa_plan plan;
+    int H_g, nrt, es;
+    int nc_pitch, max_blocks, bitmap_words;
+    int64_t rows_total;
+    size_t off_stats, off_acc, off_colsum, total;
+};
+
+int make_layout(const ssv_nsa_params* p, Layout* lo) {
+    if (!p) return SSV_EINVAL;
+    if (p->B < 1 || p->T < 1 || p->H < 1 || p->H_kv < 1 || p->d_k < 1 || p->d_v < 1) return SSV_EINVAL;
+    if (p->H % p->H_kv) return SSV_EINVAL;
+    if (p->l < 1 || p->d < 1 || p->l % p->d || p->l_sel < 1 || p->l_sel % p->d) return SSV_EINVAL;
+    if (p->n_sel < 1 || p->n_init < 0 || p->n_local < 0 || p->n_sel < p->n_init + p->n_local) return SSV_EINVAL;
+    if (p->w < 1 || p->max_seq_len < 0 || p->max_n_cmp < 0 || p->reserved != 0) return SSV_EINVAL;
+    if (p->dtype != SSV_F32 && p->dtype != SSV_BF16) return SSV_EINVAL;
+    if (p->mode != SSV_REFRESH && p->mode != SSV_REUSE) return SSV_EINVAL;
+    if (p->group_size < 0 || !(p->scale >= 0.f) || std::isinf(p->scale)) return SSV_EINVAL;
+    const int H_g = p->H / p->H_kv;
+    if (p->T > SSV_MAX_T) return SSV_EUNSUPPORTED;
+    if (H_g != 1 && H_g != 2 && H_g != 4 && H_g != 8 && H_g != 16) return SSV_EUNSUPPORTED;
+    if (p->l_sel != kTile || p->n_sel > kMaxNSel) return SSV_EUNSUPPORTED;
+    if (!ssv_nsa_supported(p->dtype, p->d_k, p->d_v)) return SSV_EUNSUPPORTED;
+    const int es = p->dtype == SSV_BF16 ? 2 : 4;
+    const int64_t* strides[4] = {p->k_stride, p->v_stride, p->kc_stride, p->vc_stride};
+    const int dims[4] = {p->d_k, p->d_v, p->d_k, p->d_v};
+    for (int a = 0; a < 4; ++a)
+        for (int j = 0; j < 3; ++j) {
+            if (strides[a][j] < 0 || (strides[a][j] * es) % 16) return SSV_EINVAL;
+            if (j == 2 && strides[a][j] < dims[a]) return SSV_EINVAL;
+        }
+    const int c_max = std::min(p->T, 128 / H_g);
+    if (p->group_size > c_max) return SSV_EINVAL;
+    const int max_blocks = (p->max_seq_len + p->T) / p->l_sel + 1;
+    if (max_blocks > 16384) return SSV_EUNSUPPORTED;
+
+    std::memset(lo, 0, sizeof(*lo));
+    ssv_nsa_plan& pl = lo->plan;
+    pl.C = p->group_size ? p->group_size : c_max;
+    pl.n_qg = ceil_div(p->T, pl.C);
+    pl.rows_per_wg = pl.C * H_g;
+    const int units = p->B * p->H_kv * pl.n_qg;
+    const int target = env_int("SSV_TARGET_WG", 768);
+    const int ntiles = std::max(1, ceil_div(p->max_n_cmp, kTile));
+    pl.n_cmp_chunks = std::min(std::max(1, ceil_div(target, units)), std::max(1, ntiles / 2));
+    pl.n_cmp_chunks = env_int("SSV_CMP_CHUNKS", pl.n_cmp_chunks);
+    pl.tiles_per_chunk = ceil_div(ntiles, pl.n_cmp_chunks);
+    const int per = std::max(2, pl.tiles_per_chunk);
+    const int win_tiles = (p->w + p->T) / kTile + 2;
+    pl.n_win_splits = env_int("SSV_WIN_SPLITS", std::min(std::max(1, ceil_div(win_tiles, per)), 8));
+    pl.max_sched_entries = pl.C * p->n_sel;
+    pl.n_slc_splits = env_int("SSV_SLC_SPLITS", std::min(std::max(1, ceil_div(pl.max_sched_entries, per)), 32));
+    pl.min_tiles_per_split = env_int("SSV_MIN_TILES", 2);
+    pl.n_slots = pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits;
+
+    lo->H_g = H_g;
+    lo->nrt = pl.rows_per_wg > 64 ? 2 : 1;
+    lo->es = es;
+    lo->nc_pitch = (int)align_up((size_t)std::max(1, p->max_n_cmp), kTile);
+    lo->max_blocks = max_blocks;
+    lo->bitmap_words = ceil_div(max_blocks, 32);
+    lo->rows_total = (int64_t)p->B * p->T * p->H;
+    size_t off = 0;
+    lo->off_stats = off;
+    off = align_up(off + (size_t)pl.n_slots * lo->rows_total * 2 * sizeof(float), 256);
+    lo->off_acc = off;
+    off = align_up(off + (size_t)pl.n_slots * lo->rows_total * p->d_v * sizeof(float), 256);
+    lo->off_colsum = off;
+    off = align_up(off + (size_t)p->B * p->T * p->H_kv * lo->nc_pitch * sizeof(float), 256);
+    lo->total = off;
+    pl.workspace_bytes = (int64_t)off;
+    return SSV_OK;
+}
+
+struct Timer {
+    bool on = false;
+    hipStream_t stream = nullptr;
+    hipEvent_t ev[SSV_NUM_KERNELS][2] = {};
+    bool used[SSV_NUM_KERNELS] = {};
+    int begin(int k) {
+        if (!on) return 0;
+        if (hipEventCreate(&ev[k][0]) != hipSuccess || hipEventCreate(&ev[k][1]) != hipSuccess) return -1;
+        used[k] = true;
+        return hipEventRecord(ev[k][0], stream) == hipSuccess ? 0 : -1;
+    }
+    int end(int k) { return !on || hipEventRecord(ev[k][1], stream) == hipSuccess ? 0 : -1; }
+    int finish(float* ms) {
+        int rc = 0;
+        if (!on) return 0;
+        if (hipStreamSynchronize(stream) != hipSuccess) rc = -1;
+        for (int k = 0; k < SSV_NUM_KERNELS; ++k) {
+            ms[k] = 0.f;
+            if (used[k]) {
+                if (rc == 0 && hipEventElapsedTime(&ms[k], ev[k][0], ev[k][1]) != hipSuccess) rc = -1;
+                (void)hipEventDestroy(ev[k][0]);
+                (void)hipEventDestroy(ev[k][1]);
+            }
+        }
+        return rc;
+    }
+};
+
+template <bool BF16, int DK, int DV>
+int launch_all(const void* q, const void* k, const void* v, const void* kc, const void* vc, const float* gates,
+               const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query, const int32_t* parents,
+               const ssv_nsa_params* p, void* out, int32_t* sel_idx, char* ws, const Layout& lo, hipStream_t stream,
+               Timer& tm) {
+    using SC = StreamCfg<BF16, DK, DV>;
+    using IC = ImportanceCfg<BF16, DK>;
+    const ssv_nsa_plan& pl = lo.plan;
+    const int es = lo.es;
+    const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->d_k);
+    const float scale_log2 = scale * 1.4426950408889634f;
+    float* part_stats = reinterpret_cast<float*>(ws + lo.off_stats);
+    float* part_acc = reinterpret_cast<float*>(ws + lo.off_acc);
+    float* colsum = reinterpret_cast<float*>(ws + lo.off_colsum);
+
+    StreamArgs sa{};
+    sa.q = (const char*)q; sa.k = (const char*)k; sa.v = (const char*)v; sa.kc = (const char*)kc; sa.vc = (const char*)vc;
+    sa.seq_lens = seq_lens; sa.n_cmp = n_cmp; sa.n_query = n_query; sa.parents = parents; sa.sel_idx = sel_idx;
+    sa.part_stats = part_stats; sa.part_acc = part_acc;
+    sa.B = p->B; sa.T = p->T; sa.H = p->H; sa.H_kv = p->H_kv; sa.H_g = lo.H_g; sa.C = pl.C; sa.n_qg = pl.n_qg;
+    sa.l = p->l; sa.d = p->d; sa.n_sel = p->n_sel; sa.w = p->w; sa.scale_log2 = scale_log2;
+    sa.n_cmp_chunks = pl.n_cmp_chunks; sa.n_win_splits = pl.n_win_splits; sa.n_slc_splits = pl.n_slc_splits;
+    sa.min_tiles = pl.min_tiles_per_split;
+    sa.max_sched = pl.max_sched_entries; sa.bitmap_words = lo.bitmap_words; sa.rows_total = lo.rows_total;
+    for (int j = 0; j < 3; ++j) {
+        sa.k_s[j] = p->k_stride[j] * es; sa.v_s[j] = p->v_stride[j] * es;
+        sa.kc_s[j] = p->kc_stride[j] * es; sa.vc_s[j] = p->vc_stride[j] * es;
+    }
+    const size_t lds_stream = stream_lds_bytes(SC::LDS_K, SC::LDS_VT, sa.max_sched, sa.bitmap_words);
+    const int units = p->B * p->H_kv * pl.n_qg;
+
+    auto launch_stream = [&](int slot_lo, int slot_cnt) -> int {
+        sa.slot_lo = slot_lo; sa.slot_cnt = slot_cnt; sa.n_wg = units * slot_cnt;
+        const int grid = ceil_div(sa.n_wg, 8) * 8;
+        if (lo.nrt == 2) hipLaunchKernelGGL((k_stream<BF16, DK, DV, 2>), dim3(grid), dim3(kThreads), lds_stream, stream, sa);
+        else hipLaunchKernelGGL((k_stream<BF16, DK, DV, 1>), dim3(grid), dim3(kThreads), lds_stream, stream, sa);
+        return hipGetLastError() == hipSuccess ? 0 : -1;
+    };
+
+    if (p->mode == SSV_REUSE) {
+        if (tm.begin(SSV_K_STREAM_A) || launch_stream(0, pl.n_slots) || tm.end(SSV_K_STREAM_A)) return SSV_ELAUNCH;
+    } else {
+        if (tm.begin(SSV_K_STREAM_A) || launch_stream(0, pl.n_cmp_chunks + pl.n_win_splits) || tm.end(SSV_K_STREAM_A))
+            return SSV_ELAUNCH;
+
+        ImportanceArgs ia{};
+        ia.q = sa.q; ia.kc = sa.kc; ia.seq_lens = seq_lens; ia.n_cmp = n_cmp; ia.n_query = n_query; ia.parents = parents;
+        ia.part_stats = part_stats; ia.colsum = colsum;
+        ia.B = p->B; ia.T = p->T; ia.H = p->H; ia.H_kv = p->H_kv; ia.H_g = lo.H_g; ia.C = pl.C; ia.n_qg = pl.n_qg;
+        ia.l = p->l; ia.d = p->d; ia.scale_log2 = scale_log2; ia.n_cmp_chunks = pl.n_cmp_chunks;
+        ia.n_wg = units * pl.n_cmp_chunks; ia.nc_pitch = lo.nc_pitch; ia.rows_total = lo.rows_total;
+        for (int j = 0; j < 3; ++j) ia.kc_s[j] = sa.kc_s[j];
+        const int grid_i = ceil_div(ia.n_wg, 8) * 8;
+        if (tm.begin(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
+        if (lo.nrt == 2) hipLaunchKernelGGL((k_importance<BF16, DK, 2>), dim3(grid_i), dim3(kThreads), IC::LDS_TOTAL, stream, ia);
+        else hipLaunchKernelGGL((k_importance<BF16, DK, 1>), dim3(grid_i), dim3(kThreads), IC::LDS_TOTAL, stream, ia);
+        if (hipGetLastError() != hipSuccess || tm.end(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
+
+        TopnArgs ta{};
+        ta.colsum = colsum; ta.seq_lens = seq_lens; ta.n_cmp = n_cmp; ta.n_query = n_query; ta.parents = parents;
+        ta.sel_idx = sel_idx; ta.B = p->B; ta.T = p->T; ta.H_kv = p->H_kv;
+        ta.l = p->l; ta.d = p->d; ta.l_sel = p->l_sel; ta.n_sel = p->n_sel; ta.n_init = p->n_init; ta.n_local = p->n_local;
+        ta.nc_pitch = lo.nc_pitch; ta.max_blocks = lo.max_blocks;
+        const size_t lds_topn = (size_t)lo.max_blocks * 8 + 64 + kMaxNSel * 4 + kMaxT * 16 + 64;
+        if (lds_topn > 64 * 1024 &&
+            hipFuncSetAttribute((const void*)k_topn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_topn) != hipSuccess)
+            return SSV_ELAUNCH;
+        if (tm.begin(SSV_K_TOPN)) return SSV_ELAUNCH;
+        hipLaunchKernelGGL(k_topn, dim3(p->B * p->T * p->H_kv), dim3(kThreads), lds_topn, stream, ta);
+        if (hipGetLastError() != hipSuccess || tm.end(SSV_K_TOPN)) return SSV_ELAUNCH;
+
+        if (tm.begin(SSV_K_STREAM_B) || launch_stream(pl.n_cmp_chunks + pl.n_win_splits, pl.n_slc_splits) ||
+            tm.end(SSV_K_STREAM_B))
+            return SSV_ELAUNCH;
+    }
+
+    CombineArgs ca{};
+    ca.part_stats = part_stats; ca.part_acc = part_acc; ca.gates = gates; ca.n_query = n_query; ca.out = out;
+    ca.T = p->T; ca.H = p->H; ca.n_cmp_chunks = pl.n_cmp_chunks; ca.n_win_splits = pl.n_win_splits;
+    ca.n_slc_splits = pl.n_slc_splits; ca.rows_total = lo.rows_total;
+    constexpr int RPB = kThreads / (DV / 4);
+    const int grid_c = (int)((lo.rows_total + RPB - 1) / RPB);
+    if (tm.begin(SSV_K_COMBINE)) return SSV_ELAUNCH;
+    hipLaunchKernelGGL((k_combine<BF16, DV>), dim3(grid_c), dim3(kThreads), 0, stream, ca);
+    if (hipGetLastError() != hipSuccess || tm.end(SSV_K_COMBINE)) return SSV_ELAUNCH;
+    return SSV_OK;
+}
+
+int verify_impl(const void* q, const void* k, const void* v, const void* kc, const void* vc, const float* gates,
+                const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query, const int32_t* parents,
+                const ssv_nsa_params* p, void* out, int32_t* sel_idx, void* workspace, size_t workspace_bytes,
+                void* stream, float* kernel_ms, bool timed) {
+    if (!q || !k || !v || !kc || !vc || !gates || !seq_lens || !n_cmp || !p || !out || !sel_idx) return SSV_EINVAL;
+    if (timed && !kernel_ms) return SSV_EINVAL;
+    Layout lo;
+    const int rc = make_layout(p, &lo);
+    if (rc != SSV_OK) return rc;
+    const void* aligned16[] = {q, k, v, kc, vc, out};
+    for (const void* ptr : aligned16)
+        if (reinterpret_cast<uintptr_t>(ptr) % 16) return SSV_EINVAL;
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || workspace_bytes < lo.total) return SSV_EWORKSPACE;
+
+    Timer tm;
+    tm.on = timed;
+    tm.stream = (hipStream_t)stream;
+    int res = SSV_EUNSUPPORTED;
+#define SSV_DISPATCH(BF, DK, DV)                                                                                     \
+    if (p->dtype == ((BF) ? SSV_BF16 : SSV_F32) && p->d_k == (DK) && p->d_v == (DV))                                 \
+        res = launch_all<BF, DK, DV>(q, k, v, kc, vc, gates, seq_lens, n_cmp, n_query, parents, p, out, sel_idx,      \
+                                     (char*)workspace, lo, (hipStream_t)stream, tm);
+    SSV_DISPATCH(true, 192, 128)
+    SSV_DISPATCH(true, 128, 128)
+    SSV_DISPATCH(true, 64, 64)
+    SSV_DISPATCH(false, 64, 64)
+#undef SSV_DISPATCH
+    if (timed) {
+        const int frc = tm.finish(kernel_ms);
+        if (res == SSV_OK && frc) res = SSV_ELAUNCH;
+    }
+    return res;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ssv_nsa_supported(int32_t dtype, int32_t d_k, int32_t d_v) {
+    for (const Shape& s : kShapes)
+        if (s.dtype == dtype && s.d_k == d_k && s.d_v == d_v) return 1;
+    return 0;
+}
+
+int ssv_nsa_plan_query(const ssv_nsa_params* p, ssv_nsa_plan* plan) {
+    if (!plan) return SSV_EINVAL;
+    Layout lo;
+    const int rc = make_layout(p, &lo);
+    if (rc == SSV_OK) *plan = lo.plan;
+    return rc;
+}
+
+size_t ssv_nsa_workspace_bytes(const ssv_nsa_params* p) {
+    Layout lo;
+    return make_layout(p, &lo) == SSV_OK ? lo.total : 0;
+}
+
+int ssv_nsa_verify(const void* q, const void* k, const void* v, const void* k_cmp, const void* v_cmp,
+                   const float* gates, const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query,
+                   const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+    return verify_impl(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_parents, p, out, sel_idx, workspace,
+                       workspace_bytes, stream, nullptr, false);
+}
+
+int ssv_nsa_verify_timed(const void* q, const void* k, const void* v, const void* k_cmp, const void* v_cmp,
+                         const float* gates, const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query,
+                         const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx,
+                         void* workspace, size_t workspace_bytes, void* stream, float* kernel_ms) {
+    return verify_impl(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_parents, p, out, sel_idx, workspace,
+                       workspace_bytes, stream, kernel_ms, true);
+}
+
+const char* ssv_nsa_strerror(int code) {
+    switch (code) {
+        case SSV_OK: return "ok";
+        case SSV_EINVAL: return "invalid argument";
+        case SSV_EUNSUPPORTED: return "shape not supported by this build";
+        case SSV_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case SSV_ELAUNCH: return "HIP launch failed";
+        default: return "unknown error";
+    }
+}
+
+const char* ssv_nsa_kernel_name(int idx) {
+    switch (idx) {
+        case SSV_K_STREAM_A: return "k_stream (compressed scan + window; all branches in reuse mode)";
+        case SSV_K_IMPORTANCE: return "k_importance";
+        case SSV_K_TOPN: return "k_topn";
+        case SSV_K_STREAM_B: return "k_stream (selected blocks, merged schedule)";
+        case SSV_K_COMBINE: return "k_combine";
+        default: return "";
+    }
+}
+
+int ssv_nsa_version(void) { return 1; }
+
+}  // extern "C"

@@ -1,0 +1,111 @@
+"""Host-side checks of the C ABI (no GPU, no compute calls): the library loads, exports every symbol the
+header declares, validates its arguments before touching the device, and plans launches sensibly."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_19893_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def std_params(**over):
+    kw = dict(B=1, T=8, H=64, H_kv=4, d_k=192, d_v=128, l=32, d=16, l_sel=64, n_sel=16, w=512, dtype=B.SSV_BF16,
+              mode=B.SSV_REFRESH, max_seq_len=32768, max_n_cmp=2047,
+              k_stride=(4 * 32832 * 192, 32832 * 192, 192), v_stride=(4 * 32832 * 128, 32832 * 128, 128),
+              kc_stride=(4 * 2047 * 192, 2047 * 192, 192), vc_stride=(4 * 2047 * 128, 2047 * 128, 128))
+    kw.update(over)
+    return B.make_params(**kw)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    with open(os.path.join(ROOT, "include", "ssv_nsa.h")) as f:
+        header = f.read()
+    declared = set(re.findall(r"\b(ssv_nsa_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.ssv_nsa_version() >= 1
+
+
+def test_struct_layout_matches_header():
+    # 20 four-byte fields followed by 12 int64 strides; 10 ints + int64 in the plan
+    assert ctypes.sizeof(B.SsvNsaParams) == 20 * 4 + 12 * 8
+    assert ctypes.sizeof(B.SsvNsaPlan) == 10 * 4 + 8
+
+
+def test_error_strings():
+    assert B.strerror(B.SSV_OK) == "ok"
+    for code in (B.SSV_EINVAL, B.SSV_EUNSUPPORTED, B.SSV_EWORKSPACE, B.SSV_ELAUNCH):
+        assert B.strerror(code) and B.strerror(code) != "unknown error"
+    assert B.kernel_name(0).startswith("k_stream") and B.kernel_name(99) == ""
+
+
+def test_supported_shapes():
+    assert B.ssv_nsa_supported(B.SSV_BF16, 192, 128)
+    assert B.ssv_nsa_supported(B.SSV_F32, 64, 64)
+    assert B.ssv_nsa_supported(B.SSV_BF16, 64, 64)
+    assert not B.ssv_nsa_supported(B.SSV_F32, 192, 128)
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(B=0), B.SSV_EINVAL), (dict(H=63), B.SSV_EINVAL), (dict(l=32, d=12), B.SSV_EINVAL),
+    (dict(n_sel=2), B.SSV_EINVAL), (dict(dtype=7), B.SSV_EINVAL), (dict(mode=3), B.SSV_EINVAL),
+    (dict(w=0), B.SSV_EINVAL), (dict(group_size=9), B.SSV_EINVAL), (dict(scale=-1.0), B.SSV_EINVAL),
+    (dict(k_stride=(1, 1, 100)), B.SSV_EINVAL), (dict(k_stride=(4 * 32832 * 192, 32832 * 192, 196)), B.SSV_EINVAL),
+    (dict(T=65), B.SSV_EUNSUPPORTED), (dict(H=96, H_kv=4), B.SSV_EUNSUPPORTED), (dict(l_sel=128), B.SSV_EUNSUPPORTED),
+    (dict(d_k=96), B.SSV_EUNSUPPORTED), (dict(n_sel=40), B.SSV_EUNSUPPORTED),
+    (dict(max_seq_len=2 ** 21), B.SSV_EUNSUPPORTED),
+])
+def test_bad_parameters_are_rejected_without_a_launch(over, code):
+    p = std_params(**over)
+    with pytest.raises(B.SsvError) as e:
+        B.ssv_nsa_plan_query(p)
+    assert e.value.code == code
+    assert B.ssv_nsa_workspace_bytes(p) == 0
+    fake = 4096   # non-null, aligned: validation of p happens before any pointer is used
+    with pytest.raises(B.SsvError) as e:
+        B.ssv_nsa_verify(fake, fake, fake, fake, fake, fake, fake, fake, None, None, p, fake, fake, fake, 1 << 40, 0)
+    assert e.value.code == code
+
+
+def test_null_misaligned_and_workspace_errors():
+    p = std_params()
+    need = B.ssv_nsa_workspace_bytes(p)
+    assert need > 0
+    a = 4096
+    with pytest.raises(B.SsvError) as e:
+        B.ssv_nsa_verify(None, a, a, a, a, a, a, a, None, None, p, a, a, a, need, 0)
+    assert e.value.code == B.SSV_EINVAL
+    with pytest.raises(B.SsvError) as e:
+        B.ssv_nsa_verify(a, a + 2, a, a, a, a, a, a, None, None, p, a, a, a, need, 0)
+    assert e.value.code == B.SSV_EINVAL
+    for ws, nbytes in ((None, need), (a + 16, need), (a, need - 1)):
+        with pytest.raises(B.SsvError) as e:
+            B.ssv_nsa_verify(a, a, a, a, a, a, a, a, None, None, p, a, a, ws, nbytes, 0)
+        assert e.value.code == B.SSV_EWORKSPACE
+
+
+def test_plan_fills_the_chip_and_respects_limits():
+    cfgs = {
+        "cfg1": std_params(),
+        "cfg2": std_params(B=16, T=4, max_seq_len=65536, max_n_cmp=4095),
+        "cfg3": std_params(B=4, T=40, max_seq_len=131072, max_n_cmp=8191),
+        "cfg4": std_params(B=32, T=16, max_seq_len=131072, max_n_cmp=8191),
+    }
+    for name, p in cfgs.items():
+        pl = B.ssv_nsa_plan_query(p)
+        H_g = p.H // p.H_kv
+        assert pl.C * H_g == pl.rows_per_wg <= 128 and pl.C * pl.n_qg >= p.T
+        assert pl.n_slots == pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits
+        assert pl.n_cmp_chunks * pl.tiles_per_chunk * 64 >= p.max_n_cmp
+        assert pl.max_sched_entries == pl.C * p.n_sel
+        units = p.B * p.H_kv * pl.n_qg
+        assert units * pl.n_cmp_chunks >= min(256, units * ((p.max_n_cmp + 63) // 64) // 2), name
+        assert pl.workspace_bytes == B.ssv_nsa_workspace_bytes(p) and pl.workspace_bytes % 256 == 0
+    p = std_params(group_size=2)
+    pl = B.ssv_nsa_plan_query(p)
+    assert (pl.C, pl.n_qg, pl.rows_per_wg) == (2, 4, 32)

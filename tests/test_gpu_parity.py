@@ -1,0 +1,160 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle, element by element on
+the same seeded inputs.  Sizes here are ones the oracle finishes in seconds while still spanning
+several 64-row tiles, several splits and ragged tails."""
+import numpy as np
+import pytest
+
+import ssv_inputs as si
+from parity import check, compare
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev_mod():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (run with -m 'not gpu' elsewhere)")
+    from paper_2605_19893_amd import device_case
+    return device_case
+
+
+def run_refresh(dev_mod, oracle, case, group_size=0):
+    ref = oracle.nsa_verify(case)
+    dev = dev_mod.DeviceCase(case, group_size=group_size)
+    print(f"[run] {case.name} refresh C={dev.plan.C} plan={dev.plan.as_dict()}", flush=True)
+    dev.run()
+    out, sel = dev.results()
+    rep = compare(case, oracle, ref, out, sel)
+    check(case, rep)
+    return dev, ref, out, sel
+
+
+def run_reuse(dev_mod, oracle, case, sel, group_size=0, dev=None):
+    from paper_2605_19893_amd import SSV_REUSE
+    ref = oracle.nsa_verify(case, sel_idx=sel)
+    if dev is None:
+        dev = dev_mod.DeviceCase(case, group_size=group_size)
+    dev.set_mode(SSV_REUSE)
+    dev.set_sel_idx(sel)
+    print(f"[run] {case.name} reuse C={dev.plan.C}", flush=True)
+    dev.run()
+    out, _ = dev.results()
+    rep = compare(case, oracle, ref, out, sel, reuse_sel=sel)
+    check(case, rep)
+    return out
+
+
+def test_config0_fp32(dev_mod, oracle):
+    case = si.config0()
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
+    assert np.array_equal(sel, ref.sel_idx)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+
+
+@pytest.mark.parametrize("group_size", [0, 1, 3])
+def test_bf16_ragged_tiles_and_splits(dev_mod, oracle, group_size):
+    """Two sequences of different, non-aligned lengths; 5 queries (80 rows: two row tiles per wave)."""
+    case = si.make_case("bf16_ragged", "bf16", 2, 5, 32, 2, 192, 128, si.STD_NSA, [3001, 1237], 101, rho=0.5,
+                        poison_pad=True)
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case, group_size=group_size)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+
+
+def test_f32_chain_crossing_block_boundaries(dev_mod, oracle):
+    """L chosen so that the draft tokens cross a selection-block and a compression-window boundary."""
+    nsa = si.NsaParams(l=32, d=16, l_sel=64, n_sel=6, w=100)
+    case = si.make_case("f32_cross", "f32", 3, 7, 8, 2, 64, 64, nsa, [1021, 2045, 636], 103, rho=0.3, poison_pad=True)
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
+    assert np.array_equal(sel, ref.sel_idx)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+
+
+@pytest.mark.parametrize("order", ["bfs", "dfs"])
+def test_tree_masks(dev_mod, oracle, order):
+    par = si.tree_parents((3, 2, 2), order)   # 3 + 6 + 12 = 21 queries
+    case = si.make_case(f"tree_{order}", "bf16", 2, len(par), 32, 2, 192, 128, si.STD_NSA, [2048, 1500], 105,
+                        rho=0.6, parents=par)
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+
+
+def test_tree_compressed_over_drafts_and_explicit_chain_parents(dev_mod, oracle):
+    """A chain given by explicit parent indices equals the NULL-parents fast path; a tree whose
+    compressed cache covers draft slots exercises the contiguous-extent visibility rule."""
+    chain = si.make_case("chain_explicit", "bf16", 1, 6, 16, 1, 192, 128, si.STD_NSA, [1008], 107, rho=0.5,
+                         parents=si.chain_parents(6))
+    _, _, out_a, sel_a = run_refresh(dev_mod, oracle, chain)
+    chain.parents = None
+    _, _, out_b, sel_b = run_refresh(dev_mod, oracle, chain)
+    assert np.array_equal(out_a, out_b) and np.array_equal(sel_a, sel_b)
+    par = si.tree_parents((2, 2), "dfs")
+    tree = si.make_case("tree_cmp_drafts", "f32", 1, len(par), 4, 1, 64, 64,
+                        si.NsaParams(l=32, d=16, l_sel=64, n_sel=5, w=64), [1010], 109, rho=0.5, parents=par,
+                        cmp_over_drafts=True)
+    run_refresh(dev_mod, oracle, tree)
+
+
+@pytest.mark.parametrize("H,H_kv", [(32, 8), (16, 2), (4, 2), (3, 3)])
+def test_gqa_group_sizes_paper_kernel_shape(dev_mod, oracle, H, H_kv):
+    """Head dim 64 as in the paper's kernel benchmark (32 query heads / 8 KV heads there); H_g = 4, 8, 2, 1."""
+    case = si.make_case(f"hg{H // H_kv}", "bf16", 2, 9, H, H_kv, 64, 64, si.STD_NSA, [1500, 2111], 111, rho=0.5)
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+
+
+def test_short_contexts_and_ragged_query_counts(dev_mod, oracle):
+    """Contexts shorter than one compression window / fewer blocks than n; sequences with fewer queries."""
+    case = si.make_case("short", "f32", 4, 5, 4, 1, 64, 64, si.NsaParams(l=32, d=16, l_sel=64, n_sel=4, w=40),
+                        [3, 40, 130, 700], 113, rho=0.2, n_query=[5, 1, 3, 4], poison_pad=True)
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
+    assert np.array_equal(sel, ref.sel_idx)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+
+
+def test_reuse_ignores_bad_entries(dev_mod, oracle):
+    case = si.make_case("reuse_messy", "bf16", 1, 4, 16, 1, 192, 128, si.STD_NSA, [4000], 115, rho=0.5)
+    ref = oracle.nsa_verify(case)
+    messy = ref.sel_idx[..., ::-1].copy()
+    messy[0, 0, 0, 3] = messy[0, 0, 0, 4]     # duplicate
+    messy[0, 1, 0, 5] = 10 ** 6               # out of range
+    messy[0, 2, 0, 7] = -5                    # negative
+    messy[0, 3, 0, 2] = (4000 + 3) // 64      # the last block: legal, partially visible
+    run_reuse(dev_mod, oracle, case, messy)
+
+
+def test_planted_needles_are_selected_exactly(dev_mod, oracle):
+    """Well-separated importances: indices must be bit-exact and far from the ambiguity band."""
+    case = si.make_case("needles", "bf16", 1, 4, 16, 1, 192, 128, si.STD_NSA, [8192], 117, rho=0.95)
+    qdir = si.bf16_bits_to_f32(case.q[0, 0]).mean(axis=0)
+    qdir /= np.linalg.norm(qdir)
+    needles = [5, 17, 40, 41, 77, 90, 100, 101, 110, 111, 120, 121, 125]
+    kf = si.bf16_bits_to_f32(case.k)
+    for j in needles:
+        kf[0, 0, 64 * j:64 * j + 64] = 2.0 * qdir
+    case.k[...] = si.f32_to_bf16_bits(kf)
+    nc = int(case.n_cmp[0])
+    case.k_cmp[0, 0, :nc] = si.f32_to_bf16_bits(si._pool_slice(si.bf16_bits_to_f32(case.k[0, 0]), nc, 32, 16))
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
+    assert np.all(ref.gap > 1e-3)
+    assert np.array_equal(sel, ref.sel_idx)
+    assert sorted(sel[0, 0, 0].tolist()) == sorted([0] + needles + [127, 128])
+
+
+def test_gates_one_hot_isolate_each_branch(dev_mod, oracle):
+    case = si.make_case("gates", "bf16", 1, 3, 16, 1, 192, 128, si.STD_NSA, [2500], 119, rho=0.5)
+    for idx in range(3):
+        case.gates[...] = 0.0
+        case.gates[..., idx] = 1.0
+        run_refresh(dev_mod, oracle, case)
+
+
+def test_runs_are_bitwise_reproducible(dev_mod, oracle):
+    case = si.make_case("repro", "bf16", 2, 8, 64, 4, 192, 128, si.STD_NSA, [5000, 4100], 121, rho=0.5)
+    dev = dev_mod.DeviceCase(case)
+    dev.run()
+    out1, sel1 = dev.results()
+    dev.workspace.fill_(0x7F)      # stale scratch contents must not matter
+    dev.run()
+    out2, sel2 = dev.results()
+    assert np.array_equal(out1, out2) and np.array_equal(sel1, sel2)
