@@ -1,0 +1,245 @@
+#!/usr/bin/env python3
+"""Benchmark of the NSA speculative-verification hot path on one MI355X.
+
+A "step" is one ssv_nsa_verify call in refresh mode: the whole hot path (compressed scan, block
+importance, top-n selection, merged selected-block + sliding-window attention, gated combine) over
+one batch of seeded synthetic inputs that are already resident in HBM.  The headline workload is
+benchmark configuration 1 (B=1, 32K context, 8 verifier queries, 64/4 heads, d_k=192, d_v=128, bf16);
+configuration 2 (B=16, 64K, 4 queries), the bandwidth-bound one, is measured in the same run and
+reported under "other_workloads".  One JSON line is printed.
+
+Cold numbers rotate over several copies of the inputs so that every call reads memory the previous
+calls have pushed out of the 256 MB last-level cache; warm numbers reuse one copy.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(case, sel_idx, C):
+    """Bytes the method itself must move for one call (compressed rows once per KV head; raw KV tokens
+    of the union of selected blocks and windows once per group of C queries; q, out, gates, indices)."""
+    import ssv_inputs as si
+    es = 2 if case.dtype == "bf16" else 4
+    nsa = case.nsa
+    row_b = (case.d_k + case.d_v) * es
+    cmp_b = slc_b = win_b = union_b = 0
+    for b in range(case.B):
+        L, Tq = int(case.seq_lens[b]), int(case.n_query[b])
+        par = case.parents[b] if case.parents is not None else si.chain_parents(case.T)
+        depth = si.node_depths(par[:Tq])
+        anc = []
+        for i in range(Tq):
+            a, t = set(), i
+            while t >= 0:
+                a.add(t)
+                t = int(par[t])
+            anc.append(a)
+        ncv = 0
+        for i in range(Tq):
+            lead = 0
+            while lead < Tq and lead in anc[i]:
+                lead += 1
+            ncv = max(ncv, min(int(case.n_cmp[b]), si.n_cmp_blocks(L + lead, nsa.l, nsa.d)))
+        cmp_b += case.H_kv * ncv * row_b
+        for g in range(case.H_kv):
+            for q0 in range(0, Tq, C):
+                grp = range(q0, min(Tq, q0 + C))
+                slc = np.zeros(L + Tq, bool)
+                win = np.zeros(L + Tq, bool)
+                for i in grp:
+                    vis_draft = np.zeros(Tq, bool)
+                    vis_draft[list(anc[i])] = True
+                    for j in sel_idx[b, i, g]:
+                        if j < 0:
+                            continue
+                        lo, hi = j * nsa.l_sel, min((j + 1) * nsa.l_sel, L + Tq)
+                        slc[lo:min(hi, L)] = True
+                        if hi > L:
+                            s = np.arange(max(lo, L), hi)
+                            slc[s] |= vis_draft[s - L]
+                    pos = L + int(depth[i])
+                    win[max(0, pos - nsa.w + 1):L] = True
+                    for t in anc[i]:
+                        if pos - nsa.w < L + int(depth[t]) <= pos:
+                            win[L + t] = True
+                slc_b += int(slc.sum()) * row_b
+                win_b += int(win.sum()) * row_b
+                union_b += int((slc | win).sum()) * row_b
+    tq = int(case.n_query.sum())
+    io_b = tq * case.H * (case.d_k + case.d_v) * es + tq * case.H * 3 * 4 + tq * case.H_kv * nsa.n_sel * 4
+    return {"compressed": cmp_b, "selected_union": slc_b, "window_union": win_b, "raw_union": union_b,
+            "q_out_gates_idx": io_b, "total": cmp_b + union_b + io_b}
+
+
+def time_calls(torch, devs, steps, warmup):
+    """Warm up, then time exactly `steps` calls (rotating over devs) between synchronisations."""
+    n = len(devs)
+    for s in range(warmup):
+        devs[s % n].run()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for s in range(steps):
+        devs[s % n].run()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return ev0.elapsed_time(ev1) / steps, wall_ms / steps
+
+
+def kernel_breakdown(devs, reps):
+    from paper_2605_19893_amd import binding as B
+    acc = np.zeros(B.SSV_NUM_KERNELS)
+    for r in range(reps):
+        ms = []
+        devs[r % len(devs)].run(kernel_ms=ms)
+        acc += np.asarray(ms)
+    return acc / reps
+
+
+def measure_workload(torch, oracle, case, name, steps, warmup, n_copies, parity=True):
+    from paper_2605_19893_amd import binding as B
+    from paper_2605_19893_amd.device_case import DeviceCase
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    devs = [DeviceCase(case) for _ in range(n_copies)]
+    plan = devs[0].plan.as_dict()
+    res = {"workload": name, "plan": plan}
+    ref = oracle.nsa_verify(case)
+    devs[0].run()
+    out, sel = devs[0].results()
+    if parity:
+        from parity import compare
+        rep = compare(case, oracle, ref, out, sel)
+        res["parity"] = {"idx_mismatch": rep.n_mismatch, "idx_mismatch_outside_ambiguity": rep.n_mismatch_strict,
+                         "ambiguous_units": rep.n_ambiguous, "units": rep.n_units, "max_abs_err": rep.max_abs_err}
+    ab = algorithmic_bytes(case, ref.sel_idx, plan["C"])
+    res["algorithmic_bytes"] = ab
+    tokens = int(case.n_query.sum())
+    out_modes = {}
+    for mode, mname in ((B.SSV_REFRESH, "refresh"), (B.SSV_REUSE, "reuse")):
+        for d in devs:
+            d.set_mode(mode)
+            if mode == B.SSV_REUSE:
+                d.set_sel_idx(ref.sel_idx)
+        cold_ms, cold_wall = time_calls(torch, devs, steps, warmup)
+        warm_ms, _ = time_calls(torch, devs[:1], steps, warmup)
+        kms = kernel_breakdown(devs, max(10, min(steps, 50)))
+        out_modes[mname] = {
+            "us_per_call_cold": cold_ms * 1e3, "us_per_call_warm": warm_ms * 1e3, "us_per_call_cold_wallclock": cold_wall * 1e3,
+            "tokens_per_s_cold": tokens / (cold_ms * 1e-3), "tokens_per_s_warm": tokens / (warm_ms * 1e-3),
+            "algorithmic_GBs_cold": ab["total"] / (cold_ms * 1e-3) / 1e9,
+            "hbm_frac_whole_call_cold": ab["total"] / (cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "kernel_us_cold": {B.kernel_name(i): float(kms[i] * 1e3) for i in range(B.SSV_NUM_KERNELS) if kms[i] > 0},
+            "kernel_ms_raw": [float(x) for x in kms],
+        }
+    res["modes"] = out_modes
+    # roofline of the dominant kernel of the refresh path
+    kms = np.asarray(out_modes["refresh"]["kernel_ms_raw"])
+    dom = int(np.argmax(kms))
+    kbytes = {B.SSV_K_STREAM_A: ab["compressed"] + ab["window_union"],
+              B.SSV_K_IMPORTANCE: ab["compressed"] * case.d_k // (case.d_k + case.d_v),
+              B.SSV_K_STREAM_B: ab["selected_union"]}.get(dom, 0)
+    achieved = kbytes / (kms[dom] * 1e-3) / 1e9 if kms[dom] > 0 else 0.0
+    res["roofline"] = {"bound": "hbm", "kernel": B.kernel_name(dom), "achieved": achieved, "peak": HBM_PEAK_GBS,
+                       "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                       "algorithmic_bytes_per_launch": int(kbytes), "avg_launch_us": float(kms[dom] * 1e3)}
+    for m in out_modes.values():
+        del m["kernel_ms_raw"]
+    del devs
+    torch.cuda.empty_cache()
+    return res, ref
+
+
+def cpu_baseline(oracle, case, budget_s=8.0):
+    """The oracle as it stands, timed on this machine's host cores on the same workload."""
+    threads = oracle.default_threads()
+    tokens = int(case.n_query.sum())
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        oracle.nsa_verify(case)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or reps >= 200:
+            break
+    return {"value": tokens * reps / el, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"the full headline workload ({tokens} verifier queries x all heads), {reps} repetitions, "
+                      f"{el:.1f} s of wall time on {threads} OpenMP threads", "ms_per_call": el / reps * 1e3}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--rho", type=float, default=0.5)
+    ap.add_argument("--no-extra", action="store_true", help="skip the configuration-2 measurement")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default="", help="measure only this workload (cfg1 or cfg2); for profiling runs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path shards over sequences and KV heads without communication; see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: there is no CPU fallback for the product path", file=sys.stderr)
+        sys.exit(2)
+    import oracle
+    import ssv_inputs as si
+
+    torch.cuda.set_device(0)
+    others = []
+    main_res = None
+    if args.only in ("", "cfg1"):
+        case1 = si.config1(args.rho)
+        main_res, _ = measure_workload(torch, oracle, case1, f"cfg1: B=1 L=32768 T=8 chain rho={args.rho} H=64/4 d_k=192 d_v=128 "
+                                       "l=32 d=16 l'=64 n=16 w=512", args.steps, args.warmup, n_copies=8)
+    if args.only == "cfg2" or (not args.no_extra and args.only == ""):
+        case2 = si.config2()
+        r2, _ = measure_workload(torch, oracle, case2, "cfg2: B=16 L=65536 T=4 chain rho=0.7, 5% keys x4", max(20, args.steps // 4),
+                                 max(5, args.warmup // 4), n_copies=2)
+        del case2
+        if main_res is None:
+            main_res = r2
+        else:
+            others.append(r2)
+    base = None
+    if not args.no_cpu_baseline and args.only in ("", "cfg1"):
+        base = cpu_baseline(oracle, case1)
+
+    refresh = main_res["modes"]["refresh"]
+    tokens_per_s = refresh["tokens_per_s_cold"]
+    line = {
+        "metric": "verified query-tokens/s, NSA verify attention (refresh path: routing + selected/window/compressed + gates)",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": refresh["us_per_call_cold"] / 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": main_res["workload"], "mode": "refresh", "cache": "cold (8 rotating input copies)",
+                   "plan": main_res["plan"]},
+        "roofline": main_res["roofline"],
+        "cpu_baseline": base,
+        "us_per_call": refresh["us_per_call_cold"],
+        "hbm_frac_whole_call": refresh["hbm_frac_whole_call_cold"],
+        "algorithmic_bytes": main_res["algorithmic_bytes"],
+        "parity": main_res.get("parity"),
+        "modes": main_res["modes"],
+        "other_workloads": others,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
