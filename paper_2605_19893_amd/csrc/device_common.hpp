@@ -40,26 +40,29 @@ __device__ __forceinline__ u32x4 lds_read16(const char* p) { return *reinterpret
 __device__ __forceinline__ u32x2 lds_read8(const char* p) { return *reinterpret_cast<const u32x2*>(p); }
 
 // Row-major copy of up to 64 rows of ROW_BYTES bytes into LDS with row pitch PITCH.
-// Rows >= valid_rows are zero-filled (their memory may not exist or may hold non-finite values).
+// Rows >= valid_rows (>= 1) are zero-filled: their memory may not exist or may hold non-finite values.
+// All global loads are unconditional (the row index is clamped, the value is zeroed afterwards), so
+// they are issued back to back and wait once; a predicated load would serialise on its branch.
 template <int ROW_BYTES, int PITCH>
 __device__ __forceinline__ void load_rows_to_lds(char* lds, const char* g, uint32_t g_row_bytes, int valid_rows, int tid) {
     constexpr int CPR = ROW_BYTES / 16;
     constexpr int TOTAL = kTile * CPR;
-    constexpr int ITERS = (TOTAL + kThreads - 1) / kThreads;
+    static_assert(TOTAL % kThreads == 0, "tile must divide evenly over the workgroup");
+    constexpr int ITERS = TOTAL / kThreads;
     u32x4 val[ITERS];
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int f = it * kThreads + tid;
         const int row = f / CPR, col = f % CPR;
-        val[it] = u32x4{0, 0, 0, 0};
-        const uint32_t off = (uint32_t)row * g_row_bytes + (uint32_t)col * 16u;   // 32-bit offset from a uniform base
-        if (f < TOTAL && row < valid_rows) val[it] = *reinterpret_cast<const u32x4*>(g + off);
+        const uint32_t off = (uint32_t)min(row, valid_rows - 1) * g_row_bytes + (uint32_t)col * 16u;
+        val[it] = *reinterpret_cast<const u32x4*>(g + off);
     }
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int f = it * kThreads + tid;
         const int row = f / CPR, col = f % CPR;
-        if (f < TOTAL) *reinterpret_cast<u32x4*>(lds + row * PITCH + col * 16) = val[it];
+        if (row >= valid_rows) val[it] = u32x4{0, 0, 0, 0};
+        *reinterpret_cast<u32x4*>(lds + row * PITCH + col * 16) = val[it];
     }
 }
 
@@ -74,7 +77,9 @@ __device__ __forceinline__ void load_transposed_to_lds(char* lds, const char* g,
     constexpr int ES = BF16 ? 2 : 4;
     constexpr int CPR = DV * ES / 16;           // 16-byte chunks per row
     constexpr int ITEMS = (kTile / 4) * CPR;    // (key quad, chunk) pairs
+    static_assert(ITEMS % kThreads == 0 || kThreads % ITEMS == 0, "unsupported value width");
     constexpr int ITERS = (ITEMS + kThreads - 1) / kThreads;
+    if (ITEMS < kThreads && tid >= ITEMS) return;   // whole wavefronts drop out (ITEMS is a multiple of 64)
     u32x4 r[ITERS][4];
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
@@ -83,16 +88,17 @@ __device__ __forceinline__ void load_transposed_to_lds(char* lds, const char* g,
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int row = 4 * kq + j;
-            r[it][j] = u32x4{0, 0, 0, 0};
-            const uint32_t off = (uint32_t)row * g_row_bytes + (uint32_t)ch * 16u;
-            if (item < ITEMS && row < valid_rows) r[it][j] = *reinterpret_cast<const u32x4*>(g + off);
+            const uint32_t off = (uint32_t)min(row, valid_rows - 1) * g_row_bytes + (uint32_t)ch * 16u;
+            r[it][j] = *reinterpret_cast<const u32x4*>(g + off);
         }
     }
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int item = it * kThreads + tid;
         const int kq = item / CPR, ch = item % CPR;
-        if (item >= ITEMS) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (4 * kq + j >= valid_rows) r[it][j] = u32x4{0, 0, 0, 0};
         if constexpr (BF16) {
 #pragma unroll
             for (int e2 = 0; e2 < 4; ++e2) {    // 32-bit word e2 of the chunk holds columns 2 e2 and 2 e2 + 1
@@ -116,29 +122,41 @@ __device__ __forceinline__ void load_transposed_to_lds(char* lds, const char* g,
     }
 }
 
+// Number of compressed rows a query may use: complete windows inside the contiguous visible
+// extent E = L + (leading run of visible draft slots), capped by the rows that exist.
+__device__ __forceinline__ int visible_cmp_rows(uint64_t anc, int L, int n_cmp, int l, int d) {
+    const int lead = (~anc == 0ull) ? 64 : __builtin_ctzll(~anc);
+    const int E = L + lead;
+    const int full = E >= l ? (E - l) / d + 1 : 0;
+    return min(full, n_cmp);
+}
+
 // Draft-tree metadata of one sequence, rebuilt by every workgroup from the parent indices:
-// ancestor bitmask (bit t set iff draft token t is the query itself or one of its ancestors)
-// and depth (position = L + depth).  parents == nullptr means a linear chain.
+// ancestor bitmask (bit t set iff draft token t is the query itself or one of its ancestors),
+// depth (position = L + depth) and the number of compressed rows the query may use.
+// parents == nullptr means a linear chain.
 struct SeqMeta {
     int L, Tq, n_cmp;
 };
 
 __device__ __forceinline__ SeqMeta build_tree_meta(int tid, int b, int T, const int32_t* seq_lens, const int32_t* n_query,
-                                                   const int32_t* n_cmp, const int32_t* parents, int* s_par,
-                                                   int* s_depth, uint64_t* s_anc) {
+                                                   const int32_t* n_cmp, const int32_t* parents, int l, int d, int* s_par,
+                                                   int* s_depth, int* s_cmax, uint64_t* s_anc) {
     SeqMeta sm;
     sm.L = seq_lens[b];
     sm.Tq = n_query ? min(max(n_query[b], 0), T) : T;
     sm.n_cmp = max(n_cmp[b], 0);
-    if (tid < kMaxT) {
-        int par = tid - 1;
-        if (parents && tid < sm.Tq) {
-            par = parents[(int64_t)b * T + tid];
-            if (par >= tid || par < -1) par = -1;   // malformed entry: treat as a child of the prefix
+    if (parents) {
+        if (tid < kMaxT) {
+            int par = -1;
+            if (tid < sm.Tq) {
+                par = parents[(int64_t)b * T + tid];
+                if (par >= tid || par < -1) par = -1;   // malformed entry: treat as a child of the prefix
+            }
+            s_par[tid] = par;
         }
-        s_par[tid] = par;
+        __syncthreads();
     }
-    __syncthreads();
     if (tid < kMaxT) {
         uint64_t anc = 0;
         int dep = 0;
@@ -158,18 +176,10 @@ __device__ __forceinline__ SeqMeta build_tree_meta(int tid, int b, int T, const 
         }
         s_anc[tid] = anc;
         s_depth[tid] = dep;
+        s_cmax[tid] = tid < sm.Tq ? visible_cmp_rows(anc, sm.L, sm.n_cmp, l, d) : 0;
     }
     __syncthreads();
     return sm;
-}
-
-// Number of compressed rows query i may use: complete windows inside the contiguous visible
-// extent E = L + (leading run of visible draft slots), capped by the rows that exist.
-__device__ __forceinline__ int visible_cmp_rows(uint64_t anc, int L, int n_cmp, int l, int d) {
-    const int lead = (~anc == 0ull) ? 64 : __builtin_ctzll(~anc);
-    const int E = L + lead;
-    const int full = E >= l ? (E - l) / d + 1 : 0;
-    return min(full, n_cmp);
 }
 
 }  // namespace ssv

@@ -2,6 +2,11 @@
 // branch, normalise, and apply the per-branch gates; only the aggregated output is written, in the
 // input dtype (round-to-nearest-even for bf16).
 //   o_branch = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) Z_s,   out = g_cmp o_cmp + g_slc o_slc + g_win o_win
+//
+// One workgroup per output row.  Wavefronts 0..2 each take one branch: lane = slice, one load of the
+// (m, Z) pair, wave-wide max and sum, and the per-slice weight gate * 2^(m - M) / Z_total goes to LDS.
+// Then all 256 threads accumulate weight * partial accumulator, (256 / (d_v/4)) slices in parallel with
+// independent loads, and a small LDS reduction produces the row.
 #pragma once
 #include "device_common.hpp"
 
@@ -16,53 +21,82 @@ struct CombineArgs {
     int64_t rows_total;
 };
 
+constexpr int kMaxSlotsPerBranch = 64;
+
+__device__ __forceinline__ float wave_max_f32(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+    return v;
+}
+__device__ __forceinline__ float wave_sum_f32(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
 template <bool BF16, int DV>
 __global__ void __launch_bounds__(kThreads) k_combine(const CombineArgs a) {
-    constexpr int TPR = DV / 4;                 // threads per output row, 4 columns each
-    constexpr int RPB = kThreads / TPR;         // rows per workgroup
-    const int tid = threadIdx.x;
-    const int64_t row = (int64_t)blockIdx.x * RPB + tid / TPR;
-    const int c4 = (tid % TPR) * 4;
-    if (row >= a.rows_total) return;
+    constexpr int TPR = DV / 4;                 // threads across one row, 4 columns each
+    constexpr int SL = kThreads / TPR;          // slices accumulated in parallel
+    __shared__ float s_w[3 * kMaxSlotsPerBranch];
+    __shared__ f32x4 s_red[SL][TPR];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
     const int i = (int)((row / a.H) % a.T);
     const int b = (int)(row / ((int64_t)a.H * a.T));
     const int Tq = a.n_query ? min(max(a.n_query[b], 0), a.T) : a.T;
+    const int n_slots = a.n_cmp_chunks + a.n_win_splits + a.n_slc_splits;
+    const int c = tid % TPR, sl = tid / TPR;
 
-    f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (i < Tq) {
-        const int lo[3] = {0, a.n_cmp_chunks + a.n_win_splits, a.n_cmp_chunks};
-        const int cnt[3] = {a.n_cmp_chunks, a.n_slc_splits, a.n_win_splits};   // gate order: cmp, slc, win
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (i < Tq) {     // uniform per workgroup
+        if (wave < 3) {
+            // slot ranges: cmp [0, n_cmp), win [n_cmp, n_cmp + n_win), slc after; gate order: cmp, slc, win
+            const int lo = wave == 0 ? 0 : (wave == 1 ? a.n_cmp_chunks + a.n_win_splits : a.n_cmp_chunks);
+            const int cnt = wave == 0 ? a.n_cmp_chunks : (wave == 1 ? a.n_slc_splits : a.n_win_splits);
+            float m = -INFINITY, z = 0.f;
+            if (lane < cnt) {
+                const float2 st = *reinterpret_cast<const float2*>(a.part_stats + ((int64_t)(lo + lane) * a.rows_total + row) * 2);
+                if (st.y > 0.f) { m = st.x; z = st.y; }
+            }
+            const float M = wave_max_f32(m);
+            const float e = z > 0.f ? fast_exp2(m - M) : 0.f;
+            const float Zt = wave_sum_f32(e * z);
+            const float gate = a.gates[row * 3 + wave];
+            if (lane < cnt) s_w[lo + lane] = Zt > 0.f ? gate * e / Zt : 0.f;
+        }
+        __syncthreads();
+        for (int s0 = sl; s0 < n_slots; s0 += 4 * SL) {
+            float w[4];
+            f32x4 v[4];
 #pragma unroll
-        for (int br = 0; br < 3; ++br) {
-            float M = -INFINITY;
-            for (int s = 0; s < cnt[br]; ++s) {
-                const float* ps = a.part_stats + ((int64_t)(lo[br] + s) * a.rows_total + row) * 2;
-                if (ps[1] > 0.f) M = fmaxf(M, ps[0]);
+            for (int u = 0; u < 4; ++u) {
+                const int s = s0 + u * SL;
+                w[u] = s < n_slots ? s_w[s] : 0.f;
+                // slices that contributed nothing never wrote their accumulator: read slice 0's memory instead
+                // (always mapped) and discard it, so that the load stays unconditional
+                const int64_t pr = (int64_t)(w[u] != 0.f ? s : 0) * a.rows_total + row;
+                v[u] = *reinterpret_cast<const f32x4*>(a.part_acc + pr * DV + c * 4);
             }
-            if (M == -INFINITY) continue;          // empty branch contributes zero
-            float Z = 0.f;
-            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-            for (int s = 0; s < cnt[br]; ++s) {
-                const int64_t pr = (int64_t)(lo[br] + s) * a.rows_total + row;
-                const float* ps = a.part_stats + pr * 2;
-                if (ps[1] > 0.f) {
-                    const float wgt = fast_exp2(ps[0] - M);
-                    Z += wgt * ps[1];
-                    const f32x4 v = *reinterpret_cast<const f32x4*>(a.part_acc + pr * DV + c4);
-                    acc += wgt * v;
-                }
-            }
-            const float gate = a.gates[row * 3 + br];
-            o += (gate / Z) * acc;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (w[u] != 0.f) acc += w[u] * v[u];
         }
     }
-    if constexpr (BF16) {
-        __bf16 h[4];
+    s_red[sl][c] = acc;
+    __syncthreads();
+    if (sl == 0) {
+        f32x4 o = s_red[0][c];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) h[e] = (__bf16)o[e];
-        *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.out) + (row * DV + c4) * 2) = *reinterpret_cast<u32x2*>(h);
-    } else {
-        *reinterpret_cast<f32x4*>(reinterpret_cast<char*>(a.out) + (row * DV + c4) * 4) = o;
+        for (int k = 1; k < SL; ++k) o += s_red[k][c];
+        if constexpr (BF16) {
+            __bf16 h[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) h[e] = (__bf16)o[e];
+            *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.out) + (row * DV + c * 4) * 2) = *reinterpret_cast<u32x2*>(h);
+        } else {
+            *reinterpret_cast<f32x4*>(reinterpret_cast<char*>(a.out) + (row * DV + c * 4) * 4) = o;
+        }
     }
 }
 

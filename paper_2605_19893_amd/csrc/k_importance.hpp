@@ -35,7 +35,7 @@ struct ImportanceCfg {
     static constexpr int KP = KROW + 16;
     static constexpr int KCH = KROW / 64;
     static constexpr int LDS_K = kTile * KP;
-    static constexpr int LDS_TOTAL = LDS_K + 128 * 8 /*stats*/ + 64 * kTile * 4 /*colsum tile*/ + kMaxT * 16 + 64;
+    static constexpr int LDS_TOTAL = LDS_K + 256 * 8 /*stats*/ + 64 * kTile * 4 /*colsum tile*/ + kMaxT * 20 + 64;
 };
 
 template <bool BF16, int DK, int NRT>
@@ -45,10 +45,11 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     extern __shared__ __align__(16) char smem[];
     char* sK = smem;
     float2* s_stat = reinterpret_cast<float2*>(sK + Cfg::LDS_K);   // [128] (M, 1/Z) per workgroup row
-    float* s_cs = reinterpret_cast<float*>(s_stat + 128);          // [C <= 64][64] head-summed probabilities
+    float* s_cs = reinterpret_cast<float*>(s_stat + 256);          // [C <= 64][64] head-summed probabilities
     uint64_t* s_anc = reinterpret_cast<uint64_t*>(s_cs + 64 * kTile);
     int* s_par = reinterpret_cast<int*>(s_anc + kMaxT);
     int* s_depth = s_par + kMaxT;
+    int* s_cmax = s_depth + kMaxT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, G = lane >> 4;
@@ -61,36 +62,55 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     const int bg = wg / (a.n_qg * a.n_cmp_chunks);
     const int b = bg / a.H_kv, g = bg % a.H_kv;
 
-    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, s_par, s_depth, s_anc);
+    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, s_par, s_depth, s_cmax,
+                                       s_anc);
     const int L = sm.L, Tq = sm.Tq;
     const int nq_grp = min(a.C, Tq - qg * a.C);
     if (nq_grp <= 0) return;
 
     int cm = 0;
-    for (int j = 0; j < nq_grp; ++j) cm = max(cm, visible_cmp_rows(s_anc[qg * a.C + j], L, sm.n_cmp, a.l, a.d));
+    for (int j = 0; j < nq_grp; ++j) cm = max(cm, s_cmax[qg * a.C + j]);
     const int ntiles = (cm + kTile - 1) / kTile;
     const int per = max(1, (ntiles + a.n_cmp_chunks - 1) / a.n_cmp_chunks);
     const int t0 = chunk * per, t1 = min(ntiles, t0 + per);
     if (t0 >= t1) return;
 
-    // merged softmax statistics of every row of this workgroup: M = max_s m_s, Z = sum_s Z_s 2^(m_s - M)
+    // merged softmax statistics of every row of this workgroup: M = max_s m_s, Z = sum_s Z_s 2^(m_s - M).
+    // Two threads per row, each taking every other slice; the loads of a batch of eight slices are
+    // unconditional (clamped index) so that they are in flight together.
     const int rows_wg = nq_grp * a.H_g;
-    if (tid < 128) {
-        float2 st = make_float2(0.f, 0.f);
-        if (tid < rows_wg) {
-            const int j = tid / a.H_g;
-            const int64_t grow = ((int64_t)b * a.T + qg * a.C + j) * a.H + g * a.H_g + tid % a.H_g;
-            float M = -INFINITY;
-            for (int s = 0; s < a.n_cmp_chunks; ++s) M = fmaxf(M, a.part_stats[((int64_t)s * a.rows_total + grow) * 2]);
-            float Z = 0.f;
-            if (M > -INFINITY)
-                for (int s = 0; s < a.n_cmp_chunks; ++s) {
-                    const float* ps = a.part_stats + ((int64_t)s * a.rows_total + grow) * 2;
-                    if (ps[1] > 0.f) Z += ps[1] * fast_exp2(ps[0] - M);
+    {
+        const int rr = tid & 127, half = tid >> 7;
+        const bool ok = rr < rows_wg;
+        const int64_t grow = ((int64_t)b * a.T + qg * a.C + (ok ? rr / a.H_g : 0)) * a.H + g * a.H_g + rr % a.H_g;
+        float M = -INFINITY, Z = 0.f;
+        for (int s0 = half; s0 < a.n_cmp_chunks; s0 += 16) {
+            float2 st[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int sl = min(s0 + 2 * u, a.n_cmp_chunks - 1);
+                st[u] = *reinterpret_cast<const float2*>(a.part_stats + ((int64_t)sl * a.rows_total + grow) * 2);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (s0 + 2 * u < a.n_cmp_chunks && st[u].y > 0.f) {
+                    const float Mn = fmaxf(M, st[u].x);
+                    Z = Z * fast_exp2(M - Mn) + st[u].y * fast_exp2(st[u].x - Mn);
+                    M = Mn;
                 }
-            st = make_float2(M > -INFINITY ? M : 0.f, Z > 0.f ? 1.f / Z : 0.f);
+            }
         }
-        s_stat[tid] = st;
+        float2* s_half = s_stat + 128;     // second half of the pair, merged below
+        if (half) s_half[rr] = make_float2(M, Z);
+        __syncthreads();
+        if (!half) {
+            const float2 o = s_half[rr];
+            const float Mn = fmaxf(M, o.x);
+            float Zt = 0.f;
+            if (Z > 0.f) Zt += Z * fast_exp2(M - Mn);
+            if (o.y > 0.f) Zt += o.y * fast_exp2(o.x - Mn);
+            s_stat[rr] = make_float2(Zt > 0.f ? Mn : 0.f, (ok && Zt > 0.f) ? 1.f / Zt : 0.f);
+        }
     }
 
     // A operand: this lane's query rows (row n of each row tile), all 64-byte chunks
@@ -122,7 +142,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
             const float2 st = s_stat[ok ? rr : 0];
             rowM[t][r] = st.x;
             rowIZ[t][r] = ok ? st.y : 0.f;
-            rowC[t][r] = ok ? visible_cmp_rows(s_anc[qg * a.C + j], L, sm.n_cmp, a.l, a.d) : 0;
+            rowC[t][r] = ok ? s_cmax[qg * a.C + j] : 0;
         }
 
     const char* kbase = a.kc + b * a.kc_s[0] + g * a.kc_s[1];

@@ -51,11 +51,19 @@ __host__ __device__ inline size_t stream_lds_bytes(size_t lds_k, size_t lds_vt, 
     n += (size_t)max_sched * 8;          // ownership masks
     n += (size_t)max_sched * 4;          // block ids
     n += (size_t)bitmap_words * 4 * 2;   // bitmap + prefix
-    n += kMaxT * 8 + kMaxT * 4 * 2 + 16; // anc, par, depth, scalars
+    n += kMaxT * 8 + kMaxT * 4 * 3 + 16; // anc, par, depth, cmax, scalars
     return (n + 15) & ~(size_t)15;
 }
 
 enum Role { ROLE_CMP = 0, ROLE_WIN = 1, ROLE_SLC = 2 };
+
+// Optional in-kernel time stamps (development builds only, -DSSV_CLOCKS): 16 stamps per workgroup.
+#ifdef SSV_CLOCKS
+__device__ long long g_clk[4096 * 16];
+#define SSV_STAMP(i) do { if (threadIdx.x == 0 && wg < 4096) g_clk[wg * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define SSV_STAMP(i) do { } while (0)
+#endif
 
 template <bool BF16, int DK, int DV, int NRT>
 __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
@@ -71,7 +79,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     uint32_t* s_prefix = s_bitmap + a.bitmap_words;
     int* s_par = reinterpret_cast<int*>(s_prefix + a.bitmap_words);
     int* s_depth = s_par + kMaxT;
-    int* s_scalar = s_depth + kMaxT;
+    int* s_cmax = s_depth + kMaxT;
+    int* s_scalar = s_cmax + kMaxT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, G = lane >> 4;
@@ -86,14 +95,17 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     const int slot = a.slot_lo + (wg / a.n_qg) % a.slot_cnt;
     const int bg = wg / (a.n_qg * a.slot_cnt);
     const int b = bg / a.H_kv, g = bg % a.H_kv;
+    SSV_STAMP(0);
 
     int role, part;
     if (slot < a.n_cmp_chunks) { role = ROLE_CMP; part = slot; }
     else if (slot < a.n_cmp_chunks + a.n_win_splits) { role = ROLE_WIN; part = slot - a.n_cmp_chunks; }
     else { role = ROLE_SLC; part = slot - a.n_cmp_chunks - a.n_win_splits; }
 
-    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, s_par, s_depth, s_anc);
+    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, s_par, s_depth, s_cmax,
+                                       s_anc);
     const int L = sm.L, Tq = sm.Tq;
+    SSV_STAMP(1);
     const int nq_grp = min(a.C, Tq - qg * a.C);   // verifier queries of this group that exist
     const int n_slots_kv = L + Tq;                // raw KV rows that exist for this sequence
 
@@ -111,7 +123,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         const int qs = rvalid[t] ? qi : 0;
         anc[t] = rvalid[t] ? s_anc[qs] : 0ull;
         pos[t] = L + s_depth[qs];
-        cmax[t] = rvalid[t] ? visible_cmp_rows(anc[t], L, sm.n_cmp, a.l, a.d) : 0;
+        cmax[t] = rvalid[t] ? s_cmax[qs] : 0;
         grow[t] = ((int64_t)b * a.T + qs) * a.H + g * a.H_g + rr % a.H_g;
     }
 
@@ -120,7 +132,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     if (nq_grp > 0) {
         if (role == ROLE_CMP) {
             int cm = 0;
-            for (int j = 0; j < nq_grp; ++j) cm = max(cm, visible_cmp_rows(s_anc[qg * a.C + j], L, sm.n_cmp, a.l, a.d));
+            for (int j = 0; j < nq_grp; ++j) cm = max(cm, s_cmax[qg * a.C + j]);
             const int ntiles = (cm + kTile - 1) / kTile;
             const int per = max(1, (ntiles + a.n_cmp_chunks - 1) / a.n_cmp_chunks);
             t0 = part * per;
@@ -181,6 +193,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         }
     }
 
+    SSV_STAMP(2);
     // ---- query fragments (B operand of S^T = K Q^T), kept in registers for the whole slice
     u32x4 qf[NRT][KCH];
 #pragma unroll
@@ -217,6 +230,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         vrow = a.v_s[2];
     }
     const int rows_exist = role == ROLE_CMP ? sm.n_cmp : n_slots_kv;
+    SSV_STAMP(3);
 
     for (int it = t0; it < t1; ++it) {
         int tile;
@@ -230,21 +244,28 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         load_rows_to_lds<Cfg::KROW, KP>(sK, kbase + (int64_t)base * krow, (uint32_t)krow, valid_rows, tid);
         load_transposed_to_lds<BF16, DV, VP>(sVT, vbase + (int64_t)base * vrow, (uint32_t)vrow, valid_rows, tid);
         __syncthreads();
+        if (it - t0 < 5) SSV_STAMP(4 + 2 * (it - t0));
 
 #pragma unroll
         for (int t = 0; t < NRT; ++t) {
-            // ---- validity of this lane's 16 keys (4 key tiles x 4 registers) for its query row
+            // ---- validity of this lane's 16 keys (4 key tiles x 4 registers) for its query row;
+            //      bit 4 kt + r <-> key base + 16 kt + 4 G + r
             uint32_t vm = 0;
             if (rvalid[t]) {
                 if (role == ROLE_CMP) {
+                    const int lim = cmax[t] - base - 4 * G;          // keys with 16 kt + r < lim are visible
 #pragma unroll
-                    for (int kt = 0; kt < 4; ++kt)
+                    for (int kt = 0; kt < 4; ++kt) vm |= ((1u << min(max(lim - 16 * kt, 0), 4)) - 1u) << (4 * kt);
+                } else if (role == ROLE_WIN || ((own >> iq[t]) & 1ull)) {
+                    if (base + kTile <= L) {                         // uniform: every key is a committed token
+                        if (role == ROLE_SLC) vm = 0xFFFFu;
+                        else {
+                            const int lo = pos[t] - a.w + 1 - base - 4 * G;   // keys with 16 kt + r >= lo are in the window
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (base + 16 * kt + 4 * G + r < cmax[t]) vm |= 1u << (4 * kt + r);
-                } else {
-                    const bool is_owner = role == ROLE_WIN || ((own >> iq[t]) & 1ull);
-                    if (is_owner) {
+                            for (int kt = 0; kt < 4; ++kt)
+                                vm |= (0xFu & ~((1u << min(max(lo - 16 * kt, 0), 4)) - 1u)) << (4 * kt);
+                        }
+                    } else {                                         // tile holds draft slots: ancestry and positions
 #pragma unroll
                         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
@@ -346,7 +367,9 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
             }
             __builtin_amdgcn_sched_barrier(0);   // keep the row tiles of a wave from being interleaved
         }
+        if (it - t0 < 5) SSV_STAMP(5 + 2 * (it - t0));
     }
+    SSV_STAMP(14);
 
     // ---- partial state of this slice: (m, Z) per row and the un-normalised accumulator
 #pragma unroll
@@ -363,6 +386,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                 *reinterpret_cast<f32x4*>(a.part_acc + pr * DV + 16 * mt + 4 * G) = acc[t][mt];
         }
     }
+    SSV_STAMP(15);
 }
 
 }  // namespace ssv

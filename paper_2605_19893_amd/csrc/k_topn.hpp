@@ -25,15 +25,34 @@ struct TopnArgs {
 
 constexpr int kMaxNSel = 32;
 
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const uint32_t lo = __shfl_xor((uint32_t)v, off), hi = __shfl_xor((uint32_t)(v >> 32), off);
-        const uint64_t o = ((uint64_t)hi << 32) | lo;
-        v = o > v ? o : v;
-    }
-    return v;
+// 64-bit maximum over a wavefront: four DPP butterfly steps inside each row of 16 lanes
+// (quad swaps, then half-row and row mirrors, which pair groups that already agree), then the four
+// row results are read out as scalars.  The result is wave-uniform.
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_max_step(uint64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, CTRL, 0xF, 0xF, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), CTRL, 0xF, 0xF, false);
+    const uint64_t o = ((uint64_t)hi << 32) | lo;
+    return o > v ? o : v;
 }
+
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+    v = dpp_max_step<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_max_step<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_max_step<0x141>(v);   // row_half_mirror
+    v = dpp_max_step<0x140>(v);   // row_mirror
+    uint64_t best = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 16 * r);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), 16 * r);
+        const uint64_t o = ((uint64_t)hi << 32) | lo;
+        best = o > best ? o : best;
+    }
+    return best;
+}
+
+constexpr int kMaxImpTerms = 8;   // (l'/d) + (l/d) - 1 compressed columns feed one selection block
 
 __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     extern __shared__ __align__(16) char smem[];
@@ -43,6 +62,7 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     uint64_t* s_anc = reinterpret_cast<uint64_t*>(s_pick + kMaxNSel);
     int* s_par = reinterpret_cast<int*>(s_anc + kMaxT);
     int* s_depth = s_par + kMaxT;
+    int* s_cmax = s_depth + kMaxT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.x % a.H_kv;
@@ -50,24 +70,44 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     const int b = blockIdx.x / (a.H_kv * a.T);
     int32_t* out = a.sel_idx + (((int64_t)b * a.T + i) * a.H_kv + g) * a.n_sel;
 
-    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, s_par, s_depth, s_anc);
+    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, s_par, s_depth, s_cmax,
+                                       s_anc);
     if (i >= sm.Tq) {
         if (tid < a.n_sel) out[tid] = -1;
         return;
     }
-    const int ncv = min(visible_cmp_rows(s_anc[i], sm.L, sm.n_cmp, a.l, a.d), a.nc_pitch);
+    const int ncv = min(s_cmax[i], a.nc_pitch);
     const int J = min((sm.L + i) / a.l_sel, a.max_blocks - 1);
     const int a_ratio = a.l_sel / a.d, b_ratio = a.l / a.d;
     const float* cs = a.colsum + (((int64_t)b * a.T + i) * a.H_kv + g) * a.nc_pitch;
 
+    // imp[j] = sum_delta wt[delta] * colsum[a_ratio * j + delta], delta in [-(b_ratio-1), a_ratio-1], where
+    // wt counts the (m, n') pairs with m - n' = delta.  All loads of a block are unconditional (clamped
+    // column, zero weight) so that they are in flight together.
+    const int n_terms = a_ratio + b_ratio - 1;
     uint64_t best = 0;   // best key among the blocks owned by this thread (index % 256 == tid)
     for (int j = tid; j <= J; j += kThreads) {
         float imp = 0.f;
-        for (int m = 0; m < a_ratio; ++m)
-            for (int n2 = 0; n2 < b_ratio; ++n2) {
-                const int c = a_ratio * j + m - n2;
-                if (c >= 0 && c < ncv) imp += cs[c];
+        if (n_terms <= kMaxImpTerms) {
+            float x[kMaxImpTerms], wt[kMaxImpTerms];
+#pragma unroll
+            for (int u = 0; u < kMaxImpTerms; ++u) {
+                const int delta = u - (b_ratio - 1);
+                const int c = a_ratio * j + delta;
+                const bool ok = u < n_terms && c >= 0 && c < ncv;
+                const int pairs = min(min(a_ratio, b_ratio), min(delta + b_ratio, a_ratio - delta));
+                wt[u] = ok ? (float)pairs : 0.f;
+                x[u] = cs[ok ? c : 0];
             }
+#pragma unroll
+            for (int u = 0; u < kMaxImpTerms; ++u) imp += wt[u] != 0.f ? wt[u] * x[u] : 0.f;
+        } else {
+            for (int m = 0; m < a_ratio; ++m)
+                for (int n2 = 0; n2 < b_ratio; ++n2) {
+                    const int c = a_ratio * j + m - n2;
+                    if (c >= 0 && c < ncv) imp += cs[c];
+                }
+        }
         const bool forced = j < a.n_init || j > J - a.n_local;
         const uint32_t bits = forced ? 0x7F800000u : __float_as_uint(imp);
         const uint64_t key = ((uint64_t)bits << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);

@@ -82,6 +82,10 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     pl.max_sched_entries = pl.C * p->n_sel;
     pl.n_slc_splits = env_int("SSV_SLC_SPLITS", std::min(std::max(1, ceil_div(pl.max_sched_entries, per)), 32));
     pl.min_tiles_per_split = env_int("SSV_MIN_TILES", 2);
+    pl.n_cmp_chunks = std::min(pl.n_cmp_chunks, kMaxSlotsPerBranch);   // one lane per slice in the combine kernel
+    pl.n_win_splits = std::min(pl.n_win_splits, 32);
+    pl.n_slc_splits = std::min(pl.n_slc_splits, 32);
+    pl.tiles_per_chunk = ceil_div(ntiles, pl.n_cmp_chunks);
     pl.n_slots = pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits;
 
     lo->H_g = H_g;
@@ -194,7 +198,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         ta.sel_idx = sel_idx; ta.B = p->B; ta.T = p->T; ta.H_kv = p->H_kv;
         ta.l = p->l; ta.d = p->d; ta.l_sel = p->l_sel; ta.n_sel = p->n_sel; ta.n_init = p->n_init; ta.n_local = p->n_local;
         ta.nc_pitch = lo.nc_pitch; ta.max_blocks = lo.max_blocks;
-        const size_t lds_topn = (size_t)lo.max_blocks * 8 + 64 + kMaxNSel * 4 + kMaxT * 16 + 64;
+        const size_t lds_topn = (size_t)lo.max_blocks * 8 + 64 + kMaxNSel * 4 + kMaxT * 20 + 64;
         if (lds_topn > 64 * 1024 &&
             hipFuncSetAttribute((const void*)k_topn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_topn) != hipSuccess)
             return SSV_ELAUNCH;
@@ -211,8 +215,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     ca.part_stats = part_stats; ca.part_acc = part_acc; ca.gates = gates; ca.n_query = n_query; ca.out = out;
     ca.T = p->T; ca.H = p->H; ca.n_cmp_chunks = pl.n_cmp_chunks; ca.n_win_splits = pl.n_win_splits;
     ca.n_slc_splits = pl.n_slc_splits; ca.rows_total = lo.rows_total;
-    constexpr int RPB = kThreads / (DV / 4);
-    const int grid_c = (int)((lo.rows_total + RPB - 1) / RPB);
+    const int grid_c = (int)lo.rows_total;   // one workgroup per output row
     if (tm.begin(SSV_K_COMBINE)) return SSV_ELAUNCH;
     hipLaunchKernelGGL((k_combine<BF16, DV>), dim3(grid_c), dim3(kThreads), 0, stream, ca);
     if (hipGetLastError() != hipSuccess || tm.end(SSV_K_COMBINE)) return SSV_ELAUNCH;
@@ -315,5 +318,12 @@ const char* ssv_nsa_kernel_name(int idx) {
 }
 
 int ssv_nsa_version(void) { return 1; }
+
+#ifdef SSV_CLOCKS
+// development builds only: copy the in-kernel time stamps of the last k_stream launch to the host
+int ssv_debug_read_clocks(long long* host_out, int n) {
+    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ssv::g_clk), sizeof(long long) * n) == hipSuccess ? 0 : -1;
+}
+#endif
 
 }  // extern "C"
