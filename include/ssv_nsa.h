@@ -76,7 +76,7 @@ typedef struct ssv_nsa_params {
     float   scale;        /* softmax scale; 0 => 1/sqrt(d_k) */
     int32_t max_seq_len;  /* host-side upper bound on seq_lens[b] (sizes grids and scratch) */
     int32_t max_n_cmp;    /* host-side upper bound on n_cmp[b] */
-    int32_t reserved;     /* must be 0 */
+    int32_t avg_seq_len;  /* host-side hint: mean of seq_lens[b] (balances splits of mixed-length batches); 0 = max_seq_len */
     int64_t k_stride[3], v_stride[3], kc_stride[3], vc_stride[3];  /* elements: batch, KV head, row */
 } ssv_nsa_params;
 

@@ -29,7 +29,7 @@ class SsvNsaParams(ctypes.Structure):
                 ("B", "T", "H", "H_kv", "d_k", "d_v", "l", "d", "l_sel", "n_sel", "w", "n_init", "n_local",
                  "dtype", "mode", "group_size")] + \
                [("scale", ctypes.c_float), ("max_seq_len", ctypes.c_int32), ("max_n_cmp", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)] + \
+                ("avg_seq_len", ctypes.c_int32)] + \
                [(n, ctypes.c_int64 * 3) for n in ("k_stride", "v_stride", "kc_stride", "vc_stride")]
 
 
@@ -88,11 +88,11 @@ def kernel_name(idx: int) -> str:
 
 
 def make_params(*, B, T, H, H_kv, d_k, d_v, l, d, l_sel, n_sel, w, n_init=1, n_local=2, dtype=SSV_BF16,
-                mode=SSV_REFRESH, group_size=0, scale=0.0, max_seq_len, max_n_cmp, k_stride, v_stride, kc_stride,
+                mode=SSV_REFRESH, group_size=0, scale=0.0, max_seq_len, max_n_cmp, avg_seq_len=0, k_stride, v_stride, kc_stride,
                 vc_stride) -> SsvNsaParams:
     p = SsvNsaParams(B=B, T=T, H=H, H_kv=H_kv, d_k=d_k, d_v=d_v, l=l, d=d, l_sel=l_sel, n_sel=n_sel, w=w,
                      n_init=n_init, n_local=n_local, dtype=dtype, mode=mode, group_size=group_size, scale=scale,
-                     max_seq_len=max_seq_len, max_n_cmp=max_n_cmp, reserved=0)
+                     max_seq_len=max_seq_len, max_n_cmp=max_n_cmp, avg_seq_len=avg_seq_len)
     for name, st in (("k_stride", k_stride), ("v_stride", v_stride), ("kc_stride", kc_stride), ("vc_stride", vc_stride)):
         setattr(p, name, (ctypes.c_int64 * 3)(*[int(x) for x in st]))
     return p

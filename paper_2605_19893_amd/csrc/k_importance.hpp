@@ -9,7 +9,7 @@
 // holds four heads of one key, so the head sum is three in-register adds plus at most two
 // cross-lane exchanges.
 #pragma once
-#include "device_common.hpp"
+#include "k_stream.hpp"
 
 namespace ssv {
 
@@ -21,7 +21,8 @@ struct ImportanceArgs {
     int B, T, H, H_kv, H_g, C, n_qg;
     int l, d;
     float scale_log2;
-    int n_cmp_chunks;
+    int n_cmp_chunks;          // slices of the compressed scan (partial statistics to merge)
+    int n_imp_chunks;          // slices of this kernel's own pass over k_cmp
     int n_wg;
     int nc_pitch;
     int64_t rows_total;
@@ -58,8 +59,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     const int wg = (blockIdx.x & 7) * (n_pad >> 3) + (blockIdx.x >> 3);
     if (wg >= a.n_wg) return;
     const int qg = wg % a.n_qg;
-    const int chunk = (wg / a.n_qg) % a.n_cmp_chunks;
-    const int bg = wg / (a.n_qg * a.n_cmp_chunks);
+    const int chunk = (wg / a.n_qg) % a.n_imp_chunks;
+    const int bg = wg / (a.n_qg * a.n_imp_chunks);
     const int b = bg / a.H_kv, g = bg % a.H_kv;
 
     const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, s_par, s_depth, s_cmax,
@@ -71,8 +72,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     int cm = 0;
     for (int j = 0; j < nq_grp; ++j) cm = max(cm, s_cmax[qg * a.C + j]);
     const int ntiles = (cm + kTile - 1) / kTile;
-    const int per = max(1, (ntiles + a.n_cmp_chunks - 1) / a.n_cmp_chunks);
-    const int t0 = chunk * per, t1 = min(ntiles, t0 + per);
+    int t0, t1;
+    even_slice(ntiles, a.n_imp_chunks, 1, chunk, t0, t1);
     if (t0 >= t1) return;
 
     // merged softmax statistics of every row of this workgroup: M = max_s m_s, Z = sum_s Z_s 2^(m_s - M).

@@ -51,11 +51,20 @@ __host__ __device__ inline size_t stream_lds_bytes(size_t lds_k, size_t lds_vt, 
     n += (size_t)max_sched * 8;          // ownership masks
     n += (size_t)max_sched * 4;          // block ids
     n += (size_t)bitmap_words * 4 * 2;   // bitmap + prefix
-    n += kMaxT * 8 + kMaxT * 4 * 3 + 16; // anc, par, depth, cmax, scalars
+    n += kMaxT * 8 + kMaxT * 4 * 3 + kTile * 4 + 16; // anc, par, depth, cmax, key positions, scalars
     return (n + 15) & ~(size_t)15;
 }
 
 enum Role { ROLE_CMP = 0, ROLE_WIN = 1, ROLE_SLC = 2 };
+
+// Slice `part` of `parts` over n items, sizes differing by at most one; fewer slices are used when
+// they would fall below min_items each (the surplus slices are empty).
+__device__ __forceinline__ void even_slice(int n, int parts, int min_items, int part, int& lo, int& hi) {
+    const int used = max(1, min(parts, n / max(1, min_items)));
+    if (part >= used) { lo = hi = 0; return; }
+    lo = part * n / used;          // part <= 64 and n <= 2^14 tiles: no overflow
+    hi = (part + 1) * n / used;
+}
 
 // Optional in-kernel time stamps (development builds only, -DSSV_CLOCKS): 16 stamps per workgroup.
 #ifdef SSV_CLOCKS
@@ -80,7 +89,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     int* s_par = reinterpret_cast<int*>(s_prefix + a.bitmap_words);
     int* s_depth = s_par + kMaxT;
     int* s_cmax = s_depth + kMaxT;
-    int* s_scalar = s_cmax + kMaxT;
+    int* s_kpos = s_cmax + kMaxT;      // [64] key positions of the current tile (16-byte aligned)
+    int* s_scalar = s_kpos + kTile;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, G = lane >> 4;
@@ -134,17 +144,15 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
             int cm = 0;
             for (int j = 0; j < nq_grp; ++j) cm = max(cm, s_cmax[qg * a.C + j]);
             const int ntiles = (cm + kTile - 1) / kTile;
-            const int per = max(1, (ntiles + a.n_cmp_chunks - 1) / a.n_cmp_chunks);
-            t0 = part * per;
-            t1 = min(ntiles, t0 + per);
+            even_slice(ntiles, a.n_cmp_chunks, a.min_tiles, part, t0, t1);
         } else if (role == ROLE_WIN) {
             int dmin = 1 << 30;
             for (int j = 0; j < nq_grp; ++j) dmin = min(dmin, s_depth[qg * a.C + j]);
             const int wlo = max(0, L + dmin - a.w + 1) / kTile;
             const int whi = (n_slots_kv + kTile - 1) / kTile;
-            const int per = max(1, (whi - wlo + a.n_win_splits - 1) / a.n_win_splits);
-            t0 = wlo + part * per;
-            t1 = min(whi, t0 + per);
+            even_slice(whi - wlo, a.n_win_splits, a.min_tiles, part, t0, t1);
+            t0 += wlo;
+            t1 += wlo;
         } else {
             // merged schedule: bitmap over blocks -> ranks by prefix popcount -> sorted unique list + ownership
             const int nblk = min((n_slots_kv + kTile - 1) / kTile, a.bitmap_words * 32);
@@ -187,9 +195,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
             }
             __syncthreads();
             const int len = s_scalar[0];
-            const int per = max(a.min_tiles, (len + a.n_slc_splits - 1) / a.n_slc_splits);
-            t0 = min(len, part * per);
-            t1 = min(len, t0 + per);
+            even_slice(len, a.n_slc_splits, a.min_tiles, part, t0, t1);
         }
     }
 
@@ -239,133 +245,152 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         else tile = it;
         const int base = tile * kTile;
         const int valid_rows = min(kTile, rows_exist - base);
+        const bool has_drafts = role != ROLE_CMP && base + kTile > L;   // uniform: the tile holds draft slots
 
         __syncthreads();   // every wave has finished reading the previous tile
         load_rows_to_lds<Cfg::KROW, KP>(sK, kbase + (int64_t)base * krow, (uint32_t)krow, valid_rows, tid);
         load_transposed_to_lds<BF16, DV, VP>(sVT, vbase + (int64_t)base * vrow, (uint32_t)vrow, valid_rows, tid);
+        if (has_drafts && tid < kTile) {   // absolute position of every key of the tile (tree drafts: L + depth)
+            const int s = base + tid;
+            s_kpos[tid] = s < L ? s : (s - L < Tq ? L + s_depth[s - L] : 0x7fffffff);
+        }
         __syncthreads();
         if (it - t0 < 5) SSV_STAMP(4 + 2 * (it - t0));
 
+        // ---- validity of this lane's 16 keys (4 key tiles x 4 registers) for each of its query rows;
+        //      bit 4 kt + r <-> key base + 16 kt + 4 G + r
+        uint32_t vm[NRT];
 #pragma unroll
         for (int t = 0; t < NRT; ++t) {
-            // ---- validity of this lane's 16 keys (4 key tiles x 4 registers) for its query row;
-            //      bit 4 kt + r <-> key base + 16 kt + 4 G + r
-            uint32_t vm = 0;
-            if (rvalid[t]) {
-                if (role == ROLE_CMP) {
-                    const int lim = cmax[t] - base - 4 * G;          // keys with 16 kt + r < lim are visible
+            vm[t] = 0;
+            if (!rvalid[t]) continue;
+            if (role == ROLE_CMP) {
+                const int lim = cmax[t] - base - 4 * G;          // keys with 16 kt + r < lim are visible
 #pragma unroll
-                    for (int kt = 0; kt < 4; ++kt) vm |= ((1u << min(max(lim - 16 * kt, 0), 4)) - 1u) << (4 * kt);
-                } else if (role == ROLE_WIN || ((own >> iq[t]) & 1ull)) {
-                    if (base + kTile <= L) {                         // uniform: every key is a committed token
-                        if (role == ROLE_SLC) vm = 0xFFFFu;
-                        else {
-                            const int lo = pos[t] - a.w + 1 - base - 4 * G;   // keys with 16 kt + r >= lo are in the window
-#pragma unroll
-                            for (int kt = 0; kt < 4; ++kt)
-                                vm |= (0xFu & ~((1u << min(max(lo - 16 * kt, 0), 4)) - 1u)) << (4 * kt);
-                        }
-                    } else {                                         // tile holds draft slots: ancestry and positions
+                for (int kt = 0; kt < 4; ++kt) vm[t] |= ((1u << min(max(lim - 16 * kt, 0), 4)) - 1u) << (4 * kt);
+            } else if (role == ROLE_WIN || ((own >> iq[t]) & 1ull)) {
+                if (!has_drafts) {                               // every key is a committed token
+                    if (role == ROLE_SLC) vm[t] = 0xFFFFu;
+                    else {
+                        const int lo = pos[t] - a.w + 1 - base - 4 * G;   // keys with 16 kt + r >= lo are in the window
 #pragma unroll
                         for (int kt = 0; kt < 4; ++kt)
+                            vm[t] |= (0xFu & ~((1u << min(max(lo - 16 * kt, 0), 4)) - 1u)) << (4 * kt);
+                    }
+                } else {
+                    // visibility of the tile's 64 slots as one bit mask: committed slots, then the ancestor bits
+                    const int cl = L - base;      // committed slots at the front of the tile (< 64 here; may be <= 0)
+                    const uint64_t vis = cl > 0 ? (((1ull << cl) - 1ull) | (anc[t] << cl))
+                                                : (-cl < 64 ? anc[t] >> (-cl) : 0ull);
 #pragma unroll
-                            for (int r = 0; r < 4; ++r) {
-                                const int s = base + 16 * kt + 4 * G + r;
-                                bool ok;
-                                int kpos;
-                                if (s < L) { ok = true; kpos = s; }
-                                else {
-                                    const int dt = s - L;
-                                    ok = dt < Tq && ((anc[t] >> dt) & 1ull);
-                                    kpos = L + s_depth[dt < kMaxT ? dt : 0];
-                                }
-                                if (role == ROLE_WIN) ok = ok && kpos > pos[t] - a.w && kpos <= pos[t];
-                                if (ok) vm |= 1u << (4 * kt + r);
-                            }
+                    for (int kt = 0; kt < 4; ++kt) vm[t] |= (uint32_t)((vis >> (16 * kt + 4 * G)) & 0xFull) << (4 * kt);
+                    if (role == ROLE_WIN) {
+#pragma unroll
+                        for (int kt = 0; kt < 4; ++kt) {
+                            const int4 kp = *reinterpret_cast<const int4*>(s_kpos + 16 * kt + 4 * G);
+                            const int kpv[4] = {kp.x, kp.y, kp.z, kp.w};
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                if (!(kpv[r] > pos[t] - a.w && kpv[r] <= pos[t])) vm[t] &= ~(1u << (4 * kt + r));
+                        }
                     }
                 }
             }
-            if (__builtin_amdgcn_ballot_w64(vm != 0) == 0ull) continue;   // no row of this tile uses these keys
-
-            // ---- S^T = K Q^T
-            f32x4 s[4];
+        }
+        uint32_t vm_any = vm[0];
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt) s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 1; t < NRT; ++t) vm_any |= vm[t];
+        if (__builtin_amdgcn_ballot_w64(vm_any != 0) != 0ull) {   // some row of this wave uses these keys
+            // ---- S^T = K Q^T; every K fragment read from LDS serves all row tiles of the wave
+            f32x4 s[NRT][4];
+#pragma unroll
+            for (int t = 0; t < NRT; ++t)
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt) s[t][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kc = 0; kc < KCH; ++kc) {
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt) {
                     const u32x4 kf = lds_read16(sK + (16 * kt + n) * KP + kc * 64 + G * 16);
-                    s[kt] = mma_frag<BF16>(kf, qf[t][kc], s[kt]);
+#pragma unroll
+                    for (int t = 0; t < NRT; ++t) s[t][kt] = mma_frag<BF16>(kf, qf[t][kc], s[t][kt]);
                 }
                 if (kc & 1) __builtin_amdgcn_sched_barrier(0);   // bound the LDS reads in flight (register pressure)
             }
             __builtin_amdgcn_sched_barrier(0);
-            // ---- online softmax in the log2 domain
-            float mx = -INFINITY;
+            // ---- online softmax in the log2 domain (rows without a valid key keep their state: alpha = 1)
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
+            for (int t = 0; t < NRT; ++t) {
+                float mx = -INFINITY;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float x = ((vm >> (4 * kt + r)) & 1u) ? s[kt][r] * a.scale_log2 : -INFINITY;
-                    s[kt][r] = x;
-                    mx = fmaxf(mx, x);
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(mrun[t], mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = fast_exp2(mrun[t] - m_use);
-            float rs = 0.f;
+                for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt)
+                    for (int r = 0; r < 4; ++r) {
+                        const float x = ((vm[t] >> (4 * kt + r)) & 1u) ? s[t][kt][r] * a.scale_log2 : -INFINITY;
+                        s[t][kt][r] = x;
+                        mx = fmaxf(mx, x);
+                    }
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(mrun[t], mx);
+                const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+                const float alpha = fast_exp2(mrun[t] - m_use);
+                float rs = 0.f;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float pz = fast_exp2(s[kt][r] - m_use);
-                    s[kt][r] = pz;
-                    rs += pz;
-                }
-            rs += __shfl_xor(rs, 16);
-            rs += __shfl_xor(rs, 32);
+                for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float pz = fast_exp2(s[t][kt][r] - m_use);
+                        s[t][kt][r] = pz;
+                        rs += pz;
+                    }
+                rs += __shfl_xor(rs, 16);
+                rs += __shfl_xor(rs, 32);
+                zrun[t] = zrun[t] * alpha + rs;
+                mrun[t] = m_new;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) acc[t][mt] *= alpha;
+            }
             __builtin_amdgcn_sched_barrier(0);
-            zrun[t] = zrun[t] * alpha + rs;
-            mrun[t] = m_new;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[t][mt] *= alpha;
-
-            // ---- O^T += V^T P^T
+            // ---- O^T += V^T P^T; every V^T fragment read from LDS serves all row tiles of the wave
             if constexpr (BF16) {
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
-                    bf16x8 pk;
+                    u32x4 pb[NRT];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        pk[r] = (__bf16)s[2 * u][r];
-                        pk[4 + r] = (__bf16)s[2 * u + 1][r];
+                    for (int t = 0; t < NRT; ++t) {
+                        bf16x8 pk;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            pk[r] = (__bf16)s[t][2 * u][r];
+                            pk[4 + r] = (__bf16)s[t][2 * u + 1][r];
+                        }
+                        pb[t] = __builtin_bit_cast(u32x4, pk);
                     }
-                    const u32x4 pb = __builtin_bit_cast(u32x4, pk);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
                         const char* row = sVT + (16 * mt + n) * VP;
                         const u32x2 lo = lds_read8(row + (32 * u + 4 * G) * 2);
                         const u32x2 hi = lds_read8(row + (32 * u + 16 + 4 * G) * 2);
-                        acc[t][mt] = mma_frag<true>(u32x4{lo[0], lo[1], hi[0], hi[1]}, pb, acc[t][mt]);
+                        const u32x4 vf = u32x4{lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+                        for (int t = 0; t < NRT; ++t) acc[t][mt] = mma_frag<true>(vf, pb[t], acc[t][mt]);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             } else {
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt) {
-                    const u32x4 pb = __builtin_bit_cast(u32x4, s[kt]);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
                         const u32x4 vf = lds_read16(sVT + (16 * mt + n) * VP + (16 * kt + 4 * G) * 4);
-                        acc[t][mt] = mma_frag<false>(vf, pb, acc[t][mt]);
+#pragma unroll
+                        for (int t = 0; t < NRT; ++t)
+                            acc[t][mt] = mma_frag<false>(vf, __builtin_bit_cast(u32x4, s[t][kt]), acc[t][mt]);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            __builtin_amdgcn_sched_barrier(0);   // keep the row tiles of a wave from being interleaved
         }
         if (it - t0 < 5) SSV_STAMP(5 + 2 * (it - t0));
     }

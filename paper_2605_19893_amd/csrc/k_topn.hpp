@@ -6,8 +6,14 @@
 //   the n_eff = min(n, J+1) best by (importance descending, index ascending) are written ascending.
 //
 // One workgroup per (b, i, g).  Keys are packed as (float bits << 32) | ~index so that a plain
-// unsigned 64-bit maximum implements "larger importance, then smaller index"; importances are sums
-// of probabilities, hence non-negative, and their IEEE bit patterns order like the values.
+// unsigned 64-bit comparison implements "larger importance, then smaller index"; importances are
+// sums of probabilities, hence non-negative, and their IEEE bit patterns order like the values.
+//
+// Selection without a serial argmax loop: every thread owns the blocks j = tid (mod 256) and keeps
+// its best key.  The n_eff-th largest of the 256 per-thread bests is a lower bound of the n_eff-th
+// largest key overall, so every winner is >= that threshold; the (few) keys at or above it are
+// compacted into a candidate list and ranked by counting.  If the list overflows (massive ties), a
+// plain serial argmax over LDS takes over.
 #pragma once
 #include "device_common.hpp"
 
@@ -24,41 +30,31 @@ struct TopnArgs {
 };
 
 constexpr int kMaxNSel = 32;
-
-// 64-bit maximum over a wavefront: four DPP butterfly steps inside each row of 16 lanes
-// (quad swaps, then half-row and row mirrors, which pair groups that already agree), then the four
-// row results are read out as scalars.  The result is wave-uniform.
-template <int CTRL>
-__device__ __forceinline__ uint64_t dpp_max_step(uint64_t v) {
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, CTRL, 0xF, 0xF, false);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), CTRL, 0xF, 0xF, false);
-    const uint64_t o = ((uint64_t)hi << 32) | lo;
-    return o > v ? o : v;
-}
+constexpr int kMaxImpTerms = 8;     // (l'/d) + (l/d) - 1 compressed columns feed one selection block
+constexpr int kBlocksPerBatch = 4;  // blocks whose column loads are issued together
+constexpr int kMaxCand = 512;
 
 __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-    v = dpp_max_step<0xB1>(v);    // quad_perm [1,0,3,2]
-    v = dpp_max_step<0x4E>(v);    // quad_perm [2,3,0,1]
-    v = dpp_max_step<0x141>(v);   // row_half_mirror
-    v = dpp_max_step<0x140>(v);   // row_mirror
-    uint64_t best = 0;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 16 * r);
-        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), 16 * r);
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)v, off), hi = __shfl_xor((uint32_t)(v >> 32), off);
         const uint64_t o = ((uint64_t)hi << 32) | lo;
-        best = o > best ? o : best;
+        v = o > v ? o : v;
     }
-    return best;
+    return v;
 }
 
-constexpr int kMaxImpTerms = 8;   // (l'/d) + (l/d) - 1 compressed columns feed one selection block
+__host__ __device__ inline size_t topn_lds_bytes(int max_blocks) {
+    return (size_t)max_blocks * 8 + kThreads * 8 + kMaxCand * 8 + 16 * 8 + kMaxNSel * 4 + kMaxT * 20 + 64;
+}
 
 __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     extern __shared__ __align__(16) char smem[];
     uint64_t* s_key = reinterpret_cast<uint64_t*>(smem);                  // [max_blocks]
-    uint64_t* s_red = s_key + a.max_blocks;                               // [2][4]
-    int* s_pick = reinterpret_cast<int*>(s_red + 8);                      // [kMaxNSel]
+    uint64_t* s_best = s_key + a.max_blocks;                              // [256] per-thread best keys
+    uint64_t* s_cand = s_best + kThreads;                                 // [kMaxCand]
+    uint64_t* s_red = s_cand + kMaxCand;                                  // [16]: threshold, counter, argmax scratch
+    int* s_pick = reinterpret_cast<int*>(s_red + 16);                     // [kMaxNSel]
     uint64_t* s_anc = reinterpret_cast<uint64_t*>(s_pick + kMaxNSel);
     int* s_par = reinterpret_cast<int*>(s_anc + kMaxT);
     int* s_depth = s_par + kMaxT;
@@ -80,64 +76,110 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     const int J = min((sm.L + i) / a.l_sel, a.max_blocks - 1);
     const int a_ratio = a.l_sel / a.d, b_ratio = a.l / a.d;
     const float* cs = a.colsum + (((int64_t)b * a.T + i) * a.H_kv + g) * a.nc_pitch;
+    const int n_eff = min(a.n_sel, J + 1);
+    if (tid == 0) s_red[1] = 0;     // candidate counter
 
-    // imp[j] = sum_delta wt[delta] * colsum[a_ratio * j + delta], delta in [-(b_ratio-1), a_ratio-1], where
-    // wt counts the (m, n') pairs with m - n' = delta.  All loads of a block are unconditional (clamped
-    // column, zero weight) so that they are in flight together.
+    // imp[j] = sum_delta wt[delta] * colsum[a_ratio * j + delta], delta in [-(b_ratio-1), a_ratio-1], where wt counts
+    // the (m, n') pairs with m - n' = delta.  Loads are unconditional (clamped column, zero weight) and issued
+    // for several blocks at once so that they are in flight together.
     const int n_terms = a_ratio + b_ratio - 1;
     uint64_t best = 0;   // best key among the blocks owned by this thread (index % 256 == tid)
-    for (int j = tid; j <= J; j += kThreads) {
-        float imp = 0.f;
+    for (int j0 = tid; j0 <= J; j0 += kThreads * kBlocksPerBatch) {
+        float imp[kBlocksPerBatch];
         if (n_terms <= kMaxImpTerms) {
-            float x[kMaxImpTerms], wt[kMaxImpTerms];
+            float x[kBlocksPerBatch][kMaxImpTerms];
 #pragma unroll
-            for (int u = 0; u < kMaxImpTerms; ++u) {
-                const int delta = u - (b_ratio - 1);
-                const int c = a_ratio * j + delta;
-                const bool ok = u < n_terms && c >= 0 && c < ncv;
-                const int pairs = min(min(a_ratio, b_ratio), min(delta + b_ratio, a_ratio - delta));
-                wt[u] = ok ? (float)pairs : 0.f;
-                x[u] = cs[ok ? c : 0];
-            }
+            for (int v = 0; v < kBlocksPerBatch; ++v)
 #pragma unroll
-            for (int u = 0; u < kMaxImpTerms; ++u) imp += wt[u] != 0.f ? wt[u] * x[u] : 0.f;
-        } else {
-            for (int m = 0; m < a_ratio; ++m)
-                for (int n2 = 0; n2 < b_ratio; ++n2) {
-                    const int c = a_ratio * j + m - n2;
-                    if (c >= 0 && c < ncv) imp += cs[c];
+                for (int u = 0; u < kMaxImpTerms; ++u) {
+                    const int c = a_ratio * (j0 + v * kThreads) + u - (b_ratio - 1);
+                    x[v][u] = cs[(u < n_terms && c >= 0 && c < ncv) ? c : 0];
                 }
+#pragma unroll
+            for (int v = 0; v < kBlocksPerBatch; ++v) {
+                imp[v] = 0.f;
+#pragma unroll
+                for (int u = 0; u < kMaxImpTerms; ++u) {
+                    const int delta = u - (b_ratio - 1);
+                    const int c = a_ratio * (j0 + v * kThreads) + delta;
+                    const int pairs = min(min(a_ratio, b_ratio), min(delta + b_ratio, a_ratio - delta));
+                    if (u < n_terms && c >= 0 && c < ncv) imp[v] += (float)pairs * x[v][u];
+                }
+            }
+        } else {
+            for (int v = 0; v < kBlocksPerBatch; ++v) {
+                imp[v] = 0.f;
+                const int j = j0 + v * kThreads;
+                for (int m = 0; m < a_ratio && j <= J; ++m)
+                    for (int n2 = 0; n2 < b_ratio; ++n2) {
+                        const int c = a_ratio * j + m - n2;
+                        if (c >= 0 && c < ncv) imp[v] += cs[c];
+                    }
+            }
         }
-        const bool forced = j < a.n_init || j > J - a.n_local;
-        const uint32_t bits = forced ? 0x7F800000u : __float_as_uint(imp);
-        const uint64_t key = ((uint64_t)bits << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
-        s_key[j] = key;
-        best = key > best ? key : best;
+#pragma unroll
+        for (int v = 0; v < kBlocksPerBatch; ++v) {
+            const int j = j0 + v * kThreads;
+            if (j <= J) {
+                const bool forced = j < a.n_init || j > J - a.n_local;
+                const uint32_t bits = forced ? 0x7F800000u : __float_as_uint(imp[v]);
+                const uint64_t key = ((uint64_t)bits << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
+                s_key[j] = key;
+                best = key > best ? key : best;
+            }
+        }
     }
-    const int n_eff = min(a.n_sel, J + 1);
+    s_best[tid] = best;
     __syncthreads();
 
-    for (int round = 0; round < n_eff; ++round) {
-        const uint64_t wbest = wave_max_u64(best);
-        uint64_t* red = s_red + (round & 1) * 4;
-        if (lane == 0) red[wave] = wbest;
-        __syncthreads();
-        uint64_t top = red[0];
+    // threshold: the n_eff-th largest per-thread best (keys are distinct; threads without blocks hold 0)
+    {
+        int rank = 0;
+        for (int k = 0; k < kThreads; ++k) rank += s_best[k] > best;
+        if (best != 0 && rank == n_eff - 1) s_red[0] = best;
+    }
+    __syncthreads();
+    const uint64_t thr = s_red[0];
+    for (int j = tid; j <= J; j += kThreads) {
+        const uint64_t key = s_key[j];
+        if (key >= thr) {
+            const unsigned slot = atomicAdd(reinterpret_cast<unsigned*>(&s_red[1]), 1u);
+            if (slot < kMaxCand) s_cand[slot] = key;
+        }
+    }
+    __syncthreads();
+    const int n_cand = (int)*reinterpret_cast<unsigned*>(&s_red[1]);
+    if (n_cand <= kMaxCand) {
+        // rank candidates by counting; ranks below n_eff are the selection
+        for (int e = tid; e < n_cand; e += kThreads) {
+            const uint64_t key = s_cand[e];
+            int rank = 0;
+            for (int f = 0; f < n_cand; ++f) rank += s_cand[f] > key;
+            if (rank < n_eff) s_pick[rank] = (int)(0xFFFFFFFFu - (uint32_t)key);
+        }
+    } else {
+        // fallback for massive ties: serial argmax, one winner per round
+        for (int round = 0; round < n_eff; ++round) {
+            const uint64_t wbest = wave_max_u64(best);
+            uint64_t* red = s_red + 4 + (round & 1) * 4;
+            if (lane == 0) red[wave] = wbest;
+            __syncthreads();
+            uint64_t top = red[0];
 #pragma unroll
-        for (int k = 1; k < 4; ++k) top = red[k] > top ? red[k] : top;
-        const int j_top = (int)(0xFFFFFFFFu - (uint32_t)top);
-        if (tid == 0) s_pick[round] = j_top;
-        if ((j_top % kThreads) == tid) {       // the owner retires the winner and rescans its blocks
-            s_key[j_top] = 0;
-            best = 0;
-            for (int j = tid; j <= J; j += kThreads) best = s_key[j] > best ? s_key[j] : best;
+            for (int k = 1; k < 4; ++k) top = red[k] > top ? red[k] : top;
+            const int j_top = (int)(0xFFFFFFFFu - (uint32_t)top);
+            if (tid == 0) s_pick[round] = j_top;
+            if ((j_top % kThreads) == tid) {       // the owner retires the winner and rescans its blocks
+                s_key[j_top] = 0;
+                best = 0;
+                for (int j = tid; j <= J; j += kThreads) best = s_key[j] > best ? s_key[j] : best;
+            }
         }
     }
     __syncthreads();
     if (tid < a.n_sel) {
         int val = -1;
         if (tid < n_eff) {      // ascending order by rank counting (picks are distinct)
-            // find the element whose rank equals tid
             for (int e = 0; e < n_eff; ++e) {
                 const int x = s_pick[e];
                 int rank = 0;

@@ -31,7 +31,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
     ssv_nsa_plan plan;
-    int H_g, nrt, es;
+    int H_g, nrt, es, n_imp_chunks;
     int nc_pitch, max_blocks, bitmap_words;
     int64_t rows_total;
     size_t off_stats, off_acc, off_colsum, total;
@@ -43,7 +43,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     if (p->H % p->H_kv) return SSV_EINVAL;
     if (p->l < 1 || p->d < 1 || p->l % p->d || p->l_sel < 1 || p->l_sel % p->d) return SSV_EINVAL;
     if (p->n_sel < 1 || p->n_init < 0 || p->n_local < 0 || p->n_sel < p->n_init + p->n_local) return SSV_EINVAL;
-    if (p->w < 1 || p->max_seq_len < 0 || p->max_n_cmp < 0 || p->reserved != 0) return SSV_EINVAL;
+    if (p->w < 1 || p->max_seq_len < 0 || p->max_n_cmp < 0 || p->avg_seq_len < 0 || p->avg_seq_len > p->max_seq_len) return SSV_EINVAL;
     if (p->dtype != SSV_F32 && p->dtype != SSV_BF16) return SSV_EINVAL;
     if (p->mode != SSV_REFRESH && p->mode != SSV_REUSE) return SSV_EINVAL;
     if (p->group_size < 0 || !(p->scale >= 0.f) || std::isinf(p->scale)) return SSV_EINVAL;
@@ -70,26 +70,37 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     pl.C = p->group_size ? p->group_size : c_max;
     pl.n_qg = ceil_div(p->T, pl.C);
     pl.rows_per_wg = pl.C * H_g;
+    // Split plan.  A launch should fill the chip once with resident workgroups (LDS and registers allow
+    // 3 per CU with one row tile per wave, 2 with two), so the key tiles of a (sequence, head, query group)
+    // are cut into about capacity / units slices, but never below min_tiles tiles per slice.
     const int units = p->B * p->H_kv * pl.n_qg;
-    const int target = env_int("SSV_TARGET_WG", 768);
-    const int ntiles = std::max(1, ceil_div(p->max_n_cmp, kTile));
-    pl.n_cmp_chunks = std::min(std::max(1, ceil_div(target, units)), std::max(1, ntiles / 2));
-    pl.n_cmp_chunks = env_int("SSV_CMP_CHUNKS", pl.n_cmp_chunks);
-    pl.tiles_per_chunk = ceil_div(ntiles, pl.n_cmp_chunks);
-    const int per = std::max(2, pl.tiles_per_chunk);
-    const int win_tiles = (p->w + p->T) / kTile + 2;
-    pl.n_win_splits = env_int("SSV_WIN_SPLITS", std::min(std::max(1, ceil_div(win_tiles, per)), 8));
+    const int nrt = pl.rows_per_wg > 64 ? 2 : 1;
+    const int capacity = env_int("SSV_CAPACITY", 256 * (nrt == 2 ? 2 : 3));
+    const int ntc = std::max(1, ceil_div(p->max_n_cmp, kTile));         // compressed tiles of the longest sequence
+    // an average sequence has fewer compressed tiles than the longest one: budget slices for the average, so
+    // that slices of long and short sequences come out at about the same length
+    const double avg_frac = (p->avg_seq_len > 0 && p->max_seq_len > 0) ? (double)p->avg_seq_len / p->max_seq_len : 1.0;
+    const int ntc_avg = std::max(1, (int)std::ceil(ntc * avg_frac));
+    const int ntw = (p->w + p->T) / kTile + 2;                          // window tiles
     pl.max_sched_entries = pl.C * p->n_sel;
-    pl.n_slc_splits = env_int("SSV_SLC_SPLITS", std::min(std::max(1, ceil_div(pl.max_sched_entries, per)), 32));
+    const int nts = pl.max_sched_entries;                               // selected tiles, at most
     pl.min_tiles_per_split = env_int("SSV_MIN_TILES", 2);
+    const int mt = pl.min_tiles_per_split;
+    int per_a, per_b;
+    if (p->mode == SSV_REUSE) per_a = per_b = std::max(mt, ceil_div((ntc_avg + ntw + nts) * units, capacity));
+    else { per_a = std::max(mt, ceil_div((ntc_avg + ntw) * units, capacity)); per_b = std::max(mt, ceil_div(nts * units, capacity)); }
+    pl.n_cmp_chunks = env_int("SSV_CMP_CHUNKS", std::max(1, ceil_div(ntc, per_a)));
+    pl.n_win_splits = env_int("SSV_WIN_SPLITS", std::max(1, ceil_div(ntw, per_a)));
+    pl.n_slc_splits = env_int("SSV_SLC_SPLITS", std::max(1, ceil_div(nts, per_b)));
     pl.n_cmp_chunks = std::min(pl.n_cmp_chunks, kMaxSlotsPerBranch);   // one lane per slice in the combine kernel
     pl.n_win_splits = std::min(pl.n_win_splits, 32);
     pl.n_slc_splits = std::min(pl.n_slc_splits, 32);
-    pl.tiles_per_chunk = ceil_div(ntiles, pl.n_cmp_chunks);
+    pl.tiles_per_chunk = ceil_div(ntc, pl.n_cmp_chunks);
     pl.n_slots = pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits;
 
     lo->H_g = H_g;
-    lo->nrt = pl.rows_per_wg > 64 ? 2 : 1;
+    lo->nrt = nrt;
+    lo->n_imp_chunks = std::max(1, std::min(ceil_div(ntc, 2), std::max(1, 1024 / units)));
     lo->es = es;
     lo->nc_pitch = (int)align_up((size_t)std::max(1, p->max_n_cmp), kTile);
     lo->max_blocks = max_blocks;
@@ -158,7 +169,8 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     sa.l = p->l; sa.d = p->d; sa.n_sel = p->n_sel; sa.w = p->w; sa.scale_log2 = scale_log2;
     sa.n_cmp_chunks = pl.n_cmp_chunks; sa.n_win_splits = pl.n_win_splits; sa.n_slc_splits = pl.n_slc_splits;
     sa.min_tiles = pl.min_tiles_per_split;
-    sa.max_sched = pl.max_sched_entries; sa.bitmap_words = lo.bitmap_words; sa.rows_total = lo.rows_total;
+    // rounded so that every LDS array behind them stays 16-byte aligned
+    sa.max_sched = (pl.max_sched_entries + 3) & ~3; sa.bitmap_words = (lo.bitmap_words + 1) & ~1; sa.rows_total = lo.rows_total;
     for (int j = 0; j < 3; ++j) {
         sa.k_s[j] = p->k_stride[j] * es; sa.v_s[j] = p->v_stride[j] * es;
         sa.kc_s[j] = p->kc_stride[j] * es; sa.vc_s[j] = p->vc_stride[j] * es;
@@ -184,8 +196,8 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         ia.q = sa.q; ia.kc = sa.kc; ia.seq_lens = seq_lens; ia.n_cmp = n_cmp; ia.n_query = n_query; ia.parents = parents;
         ia.part_stats = part_stats; ia.colsum = colsum;
         ia.B = p->B; ia.T = p->T; ia.H = p->H; ia.H_kv = p->H_kv; ia.H_g = lo.H_g; ia.C = pl.C; ia.n_qg = pl.n_qg;
-        ia.l = p->l; ia.d = p->d; ia.scale_log2 = scale_log2; ia.n_cmp_chunks = pl.n_cmp_chunks;
-        ia.n_wg = units * pl.n_cmp_chunks; ia.nc_pitch = lo.nc_pitch; ia.rows_total = lo.rows_total;
+        ia.l = p->l; ia.d = p->d; ia.scale_log2 = scale_log2; ia.n_cmp_chunks = pl.n_cmp_chunks; ia.n_imp_chunks = lo.n_imp_chunks;
+        ia.n_wg = units * lo.n_imp_chunks; ia.nc_pitch = lo.nc_pitch; ia.rows_total = lo.rows_total;
         for (int j = 0; j < 3; ++j) ia.kc_s[j] = sa.kc_s[j];
         const int grid_i = ceil_div(ia.n_wg, 8) * 8;
         if (tm.begin(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
@@ -198,7 +210,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         ta.sel_idx = sel_idx; ta.B = p->B; ta.T = p->T; ta.H_kv = p->H_kv;
         ta.l = p->l; ta.d = p->d; ta.l_sel = p->l_sel; ta.n_sel = p->n_sel; ta.n_init = p->n_init; ta.n_local = p->n_local;
         ta.nc_pitch = lo.nc_pitch; ta.max_blocks = lo.max_blocks;
-        const size_t lds_topn = (size_t)lo.max_blocks * 8 + 64 + kMaxNSel * 4 + kMaxT * 20 + 64;
+        const size_t lds_topn = topn_lds_bytes(lo.max_blocks);
         if (lds_topn > 64 * 1024 &&
             hipFuncSetAttribute((const void*)k_topn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_topn) != hipSuccess)
             return SSV_ELAUNCH;

@@ -44,14 +44,21 @@ class DeviceCase:
             l_sel=nsa.l_sel, n_sel=nsa.n_sel, w=nsa.w, n_init=nsa.n_init, n_local=nsa.n_local,
             dtype=B.SSV_BF16 if dt == "bf16" else B.SSV_F32, mode=mode, group_size=group_size, scale=scale,
             max_seq_len=int(case.seq_lens.max()), max_n_cmp=int(case.n_cmp.max()),
+            avg_seq_len=int(case.seq_lens.mean()),
             k_stride=self.k.stride()[:3], v_stride=self.v.stride()[:3],
             kc_stride=self.k_cmp.stride()[:3], vc_stride=self.v_cmp.stride()[:3])
-        self.plan = B.ssv_nsa_plan_query(self.params)
-        self.workspace_bytes = B.ssv_nsa_workspace_bytes(self.params)
+        # the split plan (and with it the scratch size) depends on the mode: size the workspace for both
+        need = 0
+        for m in (B.SSV_REFRESH, B.SSV_REUSE):
+            self.params.mode = m
+            need = max(need, B.ssv_nsa_workspace_bytes(self.params))
+        self.workspace_bytes = need
         self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=self.device)
+        self.set_mode(mode)
 
     def set_mode(self, mode: int) -> None:
         self.params.mode = mode
+        self.plan = B.ssv_nsa_plan_query(self.params)
 
     def set_sel_idx(self, sel: np.ndarray) -> None:
         self.sel_idx.copy_(torch.from_numpy(np.ascontiguousarray(sel, np.int32)).to(self.device))

@@ -54,7 +54,7 @@ def test_supported_shapes():
 @pytest.mark.parametrize("over,code", [
     (dict(B=0), B.SSV_EINVAL), (dict(H=63), B.SSV_EINVAL), (dict(l=32, d=12), B.SSV_EINVAL),
     (dict(n_sel=2), B.SSV_EINVAL), (dict(dtype=7), B.SSV_EINVAL), (dict(mode=3), B.SSV_EINVAL),
-    (dict(w=0), B.SSV_EINVAL), (dict(group_size=9), B.SSV_EINVAL), (dict(scale=-1.0), B.SSV_EINVAL),
+    (dict(w=0), B.SSV_EINVAL), (dict(avg_seq_len=40000), B.SSV_EINVAL), (dict(group_size=9), B.SSV_EINVAL), (dict(scale=-1.0), B.SSV_EINVAL),
     (dict(k_stride=(1, 1, 100)), B.SSV_EINVAL), (dict(k_stride=(4 * 32832 * 192, 32832 * 192, 196)), B.SSV_EINVAL),
     (dict(T=65), B.SSV_EUNSUPPORTED), (dict(H=96, H_kv=4), B.SSV_EUNSUPPORTED), (dict(l_sel=128), B.SSV_EUNSUPPORTED),
     (dict(d_k=96), B.SSV_EUNSUPPORTED), (dict(n_sel=40), B.SSV_EUNSUPPORTED),
@@ -104,7 +104,8 @@ def test_plan_fills_the_chip_and_respects_limits():
         assert pl.n_cmp_chunks * pl.tiles_per_chunk * 64 >= p.max_n_cmp
         assert pl.max_sched_entries == pl.C * p.n_sel
         units = p.B * p.H_kv * pl.n_qg
-        assert units * pl.n_cmp_chunks >= min(256, units * ((p.max_n_cmp + 63) // 64) // 2), name
+        wgs = units * (pl.n_cmp_chunks + pl.n_win_splits)
+        assert wgs >= min(256, units * ((p.max_n_cmp + 63) // 64) // 2) and wgs <= 1024, (name, wgs)
         assert pl.workspace_bytes == B.ssv_nsa_workspace_bytes(p) and pl.workspace_bytes % 256 == 0
     p = std_params(group_size=2)
     pl = B.ssv_nsa_plan_query(p)
