@@ -72,7 +72,7 @@ typedef struct ssv_nsa_params {
     int32_t n_local;      /* forced blocks ending at the block of the query's own slot */
     int32_t dtype;        /* SSV_F32 or SSV_BF16: type of q, k, v, k_cmp, v_cmp, out */
     int32_t mode;         /* SSV_REFRESH: sel_idx is written; SSV_REUSE: sel_idx is read */
-    int32_t group_size;   /* C: verifier queries per workgroup; 0 = as many as fit (C * H_g <= 128) */
+    int32_t group_size;   /* C: verifier queries per workgroup (C * H_g <= 128); 0 = auto (C * H_g <= 64) */
     float   scale;        /* softmax scale; 0 => 1/sqrt(d_k) */
     int32_t max_seq_len;  /* host-side upper bound on seq_lens[b] (sizes grids and scratch) */
     int32_t max_n_cmp;    /* host-side upper bound on n_cmp[b] */

@@ -39,31 +39,62 @@ __device__ __forceinline__ f32x4 mma_frag(u32x4 a, u32x4 b, f32x4 c) {
 __device__ __forceinline__ u32x4 lds_read16(const char* p) { return *reinterpret_cast<const u32x4*>(p); }
 __device__ __forceinline__ u32x2 lds_read8(const char* p) { return *reinterpret_cast<const u32x2*>(p); }
 
-// Row-major copy of up to 64 rows of ROW_BYTES bytes into LDS with row pitch PITCH.
+// Tile loaders come in two halves so that the global loads of the next tile can be in flight while the
+// current tile is being computed: *_issue reads into registers, *_commit writes the registers to LDS.
+// All global loads are unconditional (the row index is clamped, the value is zeroed at commit), so they
+// are issued back to back and wait once; a predicated load would serialise on its branch.
 // Rows >= valid_rows (>= 1) are zero-filled: their memory may not exist or may hold non-finite values.
-// All global loads are unconditional (the row index is clamped, the value is zeroed afterwards), so
-// they are issued back to back and wait once; a predicated load would serialise on its branch.
-template <int ROW_BYTES, int PITCH>
-__device__ __forceinline__ void load_rows_to_lds(char* lds, const char* g, uint32_t g_row_bytes, int valid_rows, int tid) {
-    constexpr int CPR = ROW_BYTES / 16;
-    constexpr int TOTAL = kTile * CPR;
+
+// Row-major copy of up to 64 rows of ROW_BYTES bytes into LDS with row pitch PITCH.
+template <int ROW_BYTES>
+struct RowTileRegs {
+    static constexpr int CPR = ROW_BYTES / 16;
+    static constexpr int TOTAL = kTile * CPR;
     static_assert(TOTAL % kThreads == 0, "tile must divide evenly over the workgroup");
-    constexpr int ITERS = TOTAL / kThreads;
+    static constexpr int ITERS = TOTAL / kThreads;
     u32x4 val[ITERS];
+
+    __device__ __forceinline__ void issue(const char* g, uint32_t g_row_bytes, int valid_rows, int tid) {
+        const int last = valid_rows - 1;     // == 63 for every tile but the last one of a sequence
 #pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        const int f = it * kThreads + tid;
-        const int row = f / CPR, col = f % CPR;
-        const uint32_t off = (uint32_t)min(row, valid_rows - 1) * g_row_bytes + (uint32_t)col * 16u;
-        val[it] = *reinterpret_cast<const u32x4*>(g + off);
+        for (int it = 0; it < ITERS; ++it) {
+            const int f = it * kThreads + tid;
+            const int row = f / CPR, col = f % CPR;
+            const uint32_t off = (uint32_t)min(row, last) * g_row_bytes + (uint32_t)col * 16u;
+            val[it] = *reinterpret_cast<const u32x4*>(g + off);
+        }
     }
+    template <int PITCH>
+    __device__ __forceinline__ void commit(char* lds, int valid_rows, int tid) {
+        if (valid_rows < kTile) {            // uniform; rare
 #pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        const int f = it * kThreads + tid;
-        const int row = f / CPR, col = f % CPR;
-        if (row >= valid_rows) val[it] = u32x4{0, 0, 0, 0};
-        *reinterpret_cast<u32x4*>(lds + row * PITCH + col * 16) = val[it];
+            for (int it = 0; it < ITERS; ++it)
+                if ((it * kThreads + tid) / CPR >= valid_rows) val[it] = u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int f = it * kThreads + tid;
+            const int row = f / CPR, col = f % CPR;
+            *reinterpret_cast<u32x4*>(lds + row * PITCH + col * 16) = val[it];
+        }
     }
+};
+
+// Layout of the bf16 V^T tile: row = value column (128 bytes = 16 "key quads" of 4 keys x 2 bytes, no
+// padding); key quad q of column c sits at quad position q ^ sw(c), sw(c) = ((c >> 3) ^ c) & 15.  The XOR
+// swizzle spreads both access patterns over all banks: the transposing store (16 lanes = 16 columns that
+// are 8 apart, same quad) and the MFMA operand load (16 lanes = 16 consecutive columns, same quad).
+// Because XOR distributes, a lane needs only a base offset; every unrolled access is (base ^ constant) +
+// constant:
+//   store, lane (kq, ch), column 8 ch + cc:   (ch * 1024 + ((kq ^ ch ^ 8 (ch & 1)) & 15) * 8) ^ (cc * 8)  +  cc * 128
+//   load,  lane (n, G), column 16 mt + n, quad 8 u + 4 h + G:
+//                                             (n * 128 + ((G ^ n ^ (n >> 3)) & 15) * 8) ^ (16 * ((4 u + 2 h) ^ mt))  +  mt * 2048
+constexpr int kVtPitchBf16 = 128;
+__device__ __forceinline__ int vt_store_base_bf16(int kq, int ch) {
+    return ch * 8 * kVtPitchBf16 + ((kq ^ ch ^ (8 * (ch & 1))) & 15) * 8;
+}
+__device__ __forceinline__ int vt_load_base_bf16(int n, int G) {
+    return n * kVtPitchBf16 + ((G ^ n ^ (n >> 3)) & 15) * 8;
 }
 
 // Transposing load: 64 rows x DV values (row-major in global memory) become LDS rows indexed by
@@ -71,56 +102,65 @@ __device__ __forceinline__ void load_rows_to_lds(char* lds, const char* g, uint3
 // layout the P.V MFMA needs (the contraction index, the key, must run along a lane's registers).
 // Each work item reads four consecutive key rows of one 16-byte column chunk and writes, per
 // value column, the four keys as one 8-byte (bf16) or 16-byte (fp32) LDS store.
-template <bool BF16, int DV, int PITCH>
-__device__ __forceinline__ void load_transposed_to_lds(char* lds, const char* g, uint32_t g_row_bytes, int valid_rows,
-                                                       int tid) {
-    constexpr int ES = BF16 ? 2 : 4;
-    constexpr int CPR = DV * ES / 16;           // 16-byte chunks per row
-    constexpr int ITEMS = (kTile / 4) * CPR;    // (key quad, chunk) pairs
+template <bool BF16, int DV>
+struct TransposedTileRegs {
+    static constexpr int ES = BF16 ? 2 : 4;
+    static constexpr int CPR = DV * ES / 16;           // 16-byte chunks per row
+    static constexpr int ITEMS = (kTile / 4) * CPR;    // (key quad, chunk) pairs
     static_assert(ITEMS % kThreads == 0 || kThreads % ITEMS == 0, "unsupported value width");
-    constexpr int ITERS = (ITEMS + kThreads - 1) / kThreads;
-    if (ITEMS < kThreads && tid >= ITEMS) return;   // whole wavefronts drop out (ITEMS is a multiple of 64)
+    static constexpr int ITERS = (ITEMS + kThreads - 1) / kThreads;
     u32x4 r[ITERS][4];
+
+    __device__ __forceinline__ void issue(const char* g, uint32_t g_row_bytes, int valid_rows, int tid) {
+        if (ITEMS < kThreads && tid >= ITEMS) return;   // whole wavefronts drop out (ITEMS is a multiple of 64)
 #pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        const int item = it * kThreads + tid;
-        const int kq = item / CPR, ch = item % CPR;
+        for (int it = 0; it < ITERS; ++it) {
+            const int item = it * kThreads + tid;
+            const int kq = item / CPR, ch = item % CPR;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int row = 4 * kq + j;
-            const uint32_t off = (uint32_t)min(row, valid_rows - 1) * g_row_bytes + (uint32_t)ch * 16u;
-            r[it][j] = *reinterpret_cast<const u32x4*>(g + off);
-        }
-    }
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        const int item = it * kThreads + tid;
-        const int kq = item / CPR, ch = item % CPR;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (4 * kq + j >= valid_rows) r[it][j] = u32x4{0, 0, 0, 0};
-        if constexpr (BF16) {
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {    // 32-bit word e2 of the chunk holds columns 2 e2 and 2 e2 + 1
-                const uint32_t w0 = r[it][0][e2], w1 = r[it][1][e2], w2 = r[it][2][e2], w3 = r[it][3][e2];
-                u32x2 lo, hi;
-                lo[0] = (w0 & 0xFFFFu) | (w1 << 16);
-                lo[1] = (w2 & 0xFFFFu) | (w3 << 16);
-                hi[0] = (w0 >> 16) | (w1 & 0xFFFF0000u);
-                hi[1] = (w2 >> 16) | (w3 & 0xFFFF0000u);
-                const int col = ch * 8 + 2 * e2;
-                *reinterpret_cast<u32x2*>(lds + col * PITCH + kq * 8) = lo;
-                *reinterpret_cast<u32x2*>(lds + (col + 1) * PITCH + kq * 8) = hi;
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const u32x4 o = {r[it][0][e], r[it][1][e], r[it][2][e], r[it][3][e]};
-                *reinterpret_cast<u32x4*>(lds + (ch * 4 + e) * PITCH + kq * 16) = o;
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t off = (uint32_t)min(4 * kq + j, valid_rows - 1) * g_row_bytes + (uint32_t)ch * 16u;
+                r[it][j] = *reinterpret_cast<const u32x4*>(g + off);
             }
         }
     }
-}
+    template <int PITCH>
+    __device__ __forceinline__ void commit(char* lds, int valid_rows, int tid) {
+        if (ITEMS < kThreads && tid >= ITEMS) return;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int item = it * kThreads + tid;
+            const int kq = item / CPR, ch = item % CPR;
+            if (valid_rows < kTile) {        // uniform; rare
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (4 * kq + j >= valid_rows) r[it][j] = u32x4{0, 0, 0, 0};
+            }
+            if constexpr (BF16) {
+                static_assert(PITCH == kVtPitchBf16, "the swizzled bf16 V^T tile has no padding");
+                const int wb = vt_store_base_bf16(kq, ch);
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {    // 32-bit word e2 of the chunk holds columns 2 e2 and 2 e2 + 1
+                    const uint32_t w0 = r[it][0][e2], w1 = r[it][1][e2], w2 = r[it][2][e2], w3 = r[it][3][e2];
+                    u32x2 lo, hi;
+                    lo[0] = (w0 & 0xFFFFu) | (w1 << 16);
+                    lo[1] = (w2 & 0xFFFFu) | (w3 << 16);
+                    hi[0] = (w0 >> 16) | (w1 & 0xFFFF0000u);
+                    hi[1] = (w2 >> 16) | (w3 & 0xFFFF0000u);
+                    const int cc = 2 * e2;
+                    *reinterpret_cast<u32x2*>(lds + (wb ^ (cc * 8)) + cc * PITCH) = lo;
+                    *reinterpret_cast<u32x2*>(lds + (wb ^ ((cc + 1) * 8)) + (cc + 1) * PITCH) = hi;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const u32x4 o = {r[it][0][e], r[it][1][e], r[it][2][e], r[it][3][e]};
+                    *reinterpret_cast<u32x4*>(lds + (ch * 4 + e) * PITCH + kq * 16) = o;
+                }
+            }
+        }
+    }
+};
 
 // Number of compressed rows a query may use: complete windows inside the contiguous visible
 // extent E = L + (leading run of visible draft slots), capped by the rows that exist.

@@ -147,11 +147,15 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
         }
 
     const char* kbase = a.kc + b * a.kc_s[0] + g * a.kc_s[1];
+    RowTileRegs<Cfg::KROW> kregs;     // the loads of the next tile are in flight while this one is computed
+    kregs.issue(kbase + (int64_t)t0 * kTile * a.kc_s[2], (uint32_t)a.kc_s[2], min(kTile, sm.n_cmp - t0 * kTile), tid);
     for (int tile = t0; tile < t1; ++tile) {
         const int base = tile * kTile;
         __syncthreads();
-        load_rows_to_lds<Cfg::KROW, KP>(sK, kbase + (int64_t)base * a.kc_s[2], (uint32_t)a.kc_s[2], min(kTile, sm.n_cmp - base), tid);
+        kregs.template commit<KP>(sK, min(kTile, sm.n_cmp - base), tid);
         __syncthreads();
+        if (tile + 1 < t1)
+            kregs.issue(kbase + (int64_t)(base + kTile) * a.kc_s[2], (uint32_t)a.kc_s[2], min(kTile, sm.n_cmp - base - kTile), tid);
 #pragma unroll
         for (int t = 0; t < NRT; ++t) {
             const int rt = wave + 4 * t;

@@ -40,7 +40,7 @@ struct StreamCfg {
     static constexpr int KROW = DK * ES;            // bytes per K row
     static constexpr int KP = KROW + 16;            // LDS pitch of a K row (bank spread)
     static constexpr int KCH = KROW / 64;           // 64-byte chunks per K row
-    static constexpr int VP = kTile * ES + (BF16 ? 8 : 16);   // LDS pitch of a V^T row (64 keys)
+    static constexpr int VP = kTile * ES + (BF16 ? 0 : 16);   // LDS pitch of a V^T row (64 keys); bf16 rows are swizzled
     static constexpr int MT = DV / 16;              // 16-row tiles of O^T
     static constexpr int LDS_K = kTile * KP;
     static constexpr int LDS_VT = DV * VP;
@@ -236,25 +236,41 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         vrow = a.v_s[2];
     }
     const int rows_exist = role == ROLE_CMP ? sm.n_cmp : n_slots_kv;
+    const int vt_rb = vt_load_base_bf16(n, G);   // this lane's base offset into the swizzled bf16 V^T tile
     SSV_STAMP(3);
 
+    // Software pipeline: the global loads of tile it+1 are issued before tile it is computed and are
+    // committed to LDS after it; two barriers per tile separate the LDS writes from the fragment reads.
+    RowTileRegs<Cfg::KROW> kregs;
+    TransposedTileRegs<BF16, DV> vregs;
+    auto tile_of = [&](int it) { return role == ROLE_SLC ? s_id[it] : it; };
+    if (t0 < t1) {
+        const int base0 = tile_of(t0) * kTile;
+        const int vr0 = min(kTile, rows_exist - base0);
+        kregs.issue(kbase + (int64_t)base0 * krow, (uint32_t)krow, vr0, tid);
+        vregs.issue(vbase + (int64_t)base0 * vrow, (uint32_t)vrow, vr0, tid);
+    }
     for (int it = t0; it < t1; ++it) {
-        int tile;
-        uint64_t own = ~0ull;
-        if (role == ROLE_SLC) { tile = s_id[it]; own = s_own[it]; }
-        else tile = it;
+        const int tile = tile_of(it);
+        const uint64_t own = role == ROLE_SLC ? s_own[it] : ~0ull;
         const int base = tile * kTile;
         const int valid_rows = min(kTile, rows_exist - base);
         const bool has_drafts = role != ROLE_CMP && base + kTile > L;   // uniform: the tile holds draft slots
 
-        __syncthreads();   // every wave has finished reading the previous tile
-        load_rows_to_lds<Cfg::KROW, KP>(sK, kbase + (int64_t)base * krow, (uint32_t)krow, valid_rows, tid);
-        load_transposed_to_lds<BF16, DV, VP>(sVT, vbase + (int64_t)base * vrow, (uint32_t)vrow, valid_rows, tid);
+        if (it > t0) __syncthreads();   // every wave has finished reading the previous tile
+        kregs.template commit<KP>(sK, valid_rows, tid);
+        vregs.template commit<VP>(sVT, valid_rows, tid);
         if (has_drafts && tid < kTile) {   // absolute position of every key of the tile (tree drafts: L + depth)
             const int s = base + tid;
             s_kpos[tid] = s < L ? s : (s - L < Tq ? L + s_depth[s - L] : 0x7fffffff);
         }
         __syncthreads();
+        if (it + 1 < t1) {
+            const int base1 = tile_of(it + 1) * kTile;
+            const int vr1 = min(kTile, rows_exist - base1);
+            kregs.issue(kbase + (int64_t)base1 * krow, (uint32_t)krow, vr1, tid);
+            vregs.issue(vbase + (int64_t)base1 * vrow, (uint32_t)vrow, vr1, tid);
+        }
         if (it - t0 < 5) SSV_STAMP(4 + 2 * (it - t0));
 
         // ---- validity of this lane's 16 keys (4 key tiles x 4 registers) for each of its query rows;
@@ -325,11 +341,18 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float x = ((vm[t] >> (4 * kt + r)) & 1u) ? s[t][kt][r] * a.scale_log2 : -INFINITY;
-                        s[t][kt][r] = x;
-                        mx = fmaxf(mx, x);
-                    }
+                    for (int r = 0; r < 4; ++r) s[t][kt][r] *= a.scale_log2;
+                if (__builtin_amdgcn_ballot_w64(vm[t] != 0xFFFFu) != 0ull) {   // uniform: some key is masked
+#pragma unroll
+                    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (!((vm[t] >> (4 * kt + r)) & 1u)) s[t][kt][r] = -INFINITY;
+                }
+#pragma unroll
+                for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[t][kt][r]);
                 mx = fmaxf(mx, __shfl_xor(mx, 16));
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
                 const float m_new = fmaxf(mrun[t], mx);
@@ -348,8 +371,10 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                 rs += __shfl_xor(rs, 32);
                 zrun[t] = zrun[t] * alpha + rs;
                 mrun[t] = m_new;
+                if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0ull) {      // uniform: some running max moved
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) acc[t][mt] *= alpha;
+                    for (int mt = 0; mt < MT; ++mt) acc[t][mt] *= alpha;
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
             // ---- O^T += V^T P^T; every V^T fragment read from LDS serves all row tiles of the wave
@@ -369,9 +394,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                     }
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
-                        const char* row = sVT + (16 * mt + n) * VP;
-                        const u32x2 lo = lds_read8(row + (32 * u + 4 * G) * 2);
-                        const u32x2 hi = lds_read8(row + (32 * u + 16 + 4 * G) * 2);
+                        const u32x2 lo = lds_read8(sVT + (vt_rb ^ (16 * ((4 * u) ^ mt))) + mt * 16 * VP);
+                        const u32x2 hi = lds_read8(sVT + (vt_rb ^ (16 * ((4 * u + 2) ^ mt))) + mt * 16 * VP);
                         const u32x4 vf = u32x4{lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
                         for (int t = 0; t < NRT; ++t) acc[t][mt] = mma_frag<true>(vf, pb[t], acc[t][mt]);

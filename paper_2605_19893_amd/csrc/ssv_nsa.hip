@@ -67,7 +67,9 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
 
     std::memset(lo, 0, sizeof(*lo));
     ssv_nsa_plan& pl = lo->plan;
-    pl.C = p->group_size ? p->group_size : c_max;
+    // default: 64 rows per workgroup (one 16-row tile per wave keeps the software pipeline in registers);
+    // up to 128 rows (two row tiles per wave) on request
+    pl.C = p->group_size ? p->group_size : std::max(1, std::min(p->T, 64 / H_g));
     pl.n_qg = ceil_div(p->T, pl.C);
     pl.rows_per_wg = pl.C * H_g;
     // Split plan.  A launch should fill the chip once with resident workgroups (LDS and registers allow
@@ -75,7 +77,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // are cut into about capacity / units slices, but never below min_tiles tiles per slice.
     const int units = p->B * p->H_kv * pl.n_qg;
     const int nrt = pl.rows_per_wg > 64 ? 2 : 1;
-    const int capacity = env_int("SSV_CAPACITY", 256 * (nrt == 2 ? 2 : 3));
+    const int capacity = env_int("SSV_CAPACITY", 256 * 2);
     const int ntc = std::max(1, ceil_div(p->max_n_cmp, kTile));         // compressed tiles of the longest sequence
     // an average sequence has fewer compressed tiles than the longest one: budget slices for the average, so
     // that slices of long and short sequences come out at about the same length
@@ -86,12 +88,36 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     const int nts = pl.max_sched_entries;                               // selected tiles, at most
     pl.min_tiles_per_split = env_int("SSV_MIN_TILES", 2);
     const int mt = pl.min_tiles_per_split;
+    // Tiles per slice.  If one round of resident workgroups can take the launch with slices of at most 24
+    // tiles, `per` is grown until the slices of an average unit fit the capacity (no partial second round).
+    // Otherwise slices are cut short (12 tiles): several rounds of workgroups, and the longest slice, the long
+    // pole of a mixed-length batch, stays short.
+    auto tiles_per_slice = [&](const int* tiles, int n_roles) {
+        const int spu = std::max(n_roles, capacity / units);      // slices per unit one round can hold
+        int total = 0;
+        for (int r = 0; r < n_roles; ++r) total += tiles[r];
+        int per = std::max(mt, ceil_div(total, spu));
+        if (per > 24) return 12;
+        for (;; ++per) {
+            int sum = 0;
+            for (int r = 0; r < n_roles; ++r) sum += std::max(1, ceil_div(tiles[r], per));
+            if (sum <= spu || per >= total) return per;
+        }
+    };
     int per_a, per_b;
-    if (p->mode == SSV_REUSE) per_a = per_b = std::max(mt, ceil_div((ntc_avg + ntw + nts) * units, capacity));
-    else { per_a = std::max(mt, ceil_div((ntc_avg + ntw) * units, capacity)); per_b = std::max(mt, ceil_div(nts * units, capacity)); }
-    pl.n_cmp_chunks = env_int("SSV_CMP_CHUNKS", std::max(1, ceil_div(ntc, per_a)));
-    pl.n_win_splits = env_int("SSV_WIN_SPLITS", std::max(1, ceil_div(ntw, per_a)));
-    pl.n_slc_splits = env_int("SSV_SLC_SPLITS", std::max(1, ceil_div(nts, per_b)));
+    if (p->mode == SSV_REUSE) {
+        const int tiles[3] = {ntc_avg, ntw, nts};
+        per_a = per_b = tiles_per_slice(tiles, 3);
+    } else {
+        const int tiles_a[2] = {ntc_avg, ntw};
+        per_a = tiles_per_slice(tiles_a, 2);
+        per_b = tiles_per_slice(&nts, 1);
+    }
+    const int n_c = std::max(1, ceil_div(ntc, per_a)), n_w = std::max(1, ceil_div(ntw, per_a));
+    const int n_s = std::max(1, ceil_div(nts, per_b));
+    pl.n_cmp_chunks = env_int("SSV_CMP_CHUNKS", n_c);
+    pl.n_win_splits = env_int("SSV_WIN_SPLITS", n_w);
+    pl.n_slc_splits = env_int("SSV_SLC_SPLITS", n_s);
     pl.n_cmp_chunks = std::min(pl.n_cmp_chunks, kMaxSlotsPerBranch);   // one lane per slice in the combine kernel
     pl.n_win_splits = std::min(pl.n_win_splits, 32);
     pl.n_slc_splits = std::min(pl.n_slc_splits, 32);

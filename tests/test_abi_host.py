@@ -99,14 +99,18 @@ def test_plan_fills_the_chip_and_respects_limits():
     for name, p in cfgs.items():
         pl = B.ssv_nsa_plan_query(p)
         H_g = p.H // p.H_kv
-        assert pl.C * H_g == pl.rows_per_wg <= 128 and pl.C * pl.n_qg >= p.T
+        assert pl.C * H_g == pl.rows_per_wg <= 64 and pl.C * pl.n_qg >= p.T
         assert pl.n_slots == pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits
         assert pl.n_cmp_chunks * pl.tiles_per_chunk * 64 >= p.max_n_cmp
         assert pl.max_sched_entries == pl.C * p.n_sel
         units = p.B * p.H_kv * pl.n_qg
         wgs = units * (pl.n_cmp_chunks + pl.n_win_splits)
-        assert wgs >= min(256, units * ((p.max_n_cmp + 63) // 64) // 2) and wgs <= 1024, (name, wgs)
+        # either one resident round (at most 2 workgroups per CU) or several rounds of short slices
+        assert wgs >= min(256, units * ((p.max_n_cmp + 63) // 64) // 2), (name, wgs)
+        assert wgs <= 512 or pl.tiles_per_chunk <= 12, (name, wgs)
         assert pl.workspace_bytes == B.ssv_nsa_workspace_bytes(p) and pl.workspace_bytes % 256 == 0
     p = std_params(group_size=2)
     pl = B.ssv_nsa_plan_query(p)
     assert (pl.C, pl.n_qg, pl.rows_per_wg) == (2, 4, 32)
+    pl = B.ssv_nsa_plan_query(std_params(group_size=8))
+    assert (pl.C, pl.n_qg, pl.rows_per_wg) == (8, 1, 128)

@@ -52,9 +52,10 @@ def test_config0_fp32(dev_mod, oracle):
     run_reuse(dev_mod, oracle, case, sel, dev=dev)
 
 
-@pytest.mark.parametrize("group_size", [0, 1, 3])
+@pytest.mark.parametrize("group_size", [0, 1, 3, 5])
 def test_bf16_ragged_tiles_and_splits(dev_mod, oracle, group_size):
-    """Two sequences of different, non-aligned lengths; 5 queries (80 rows: two row tiles per wave)."""
+    """Two sequences of different, non-aligned lengths; 5 queries: group sizes from 1 query per workgroup up
+    to all 5 (80 rows: two row tiles per wave)."""
     case = si.make_case("bf16_ragged", "bf16", 2, 5, 32, 2, 192, 128, si.STD_NSA, [3001, 1237], 101, rho=0.5,
                         poison_pad=True)
     dev, ref, out, sel = run_refresh(dev_mod, oracle, case, group_size=group_size)
