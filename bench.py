@@ -100,11 +100,13 @@ def time_calls(torch, devs, steps, warmup):
 
 
 def kernel_breakdown(devs, reps):
+    """Average launch duration of every kernel: HIP events (inside the library, on the call's stream) around
+    20 back-to-back launches of each kernel, averaged over the rotating input copies."""
     from paper_2605_19893_amd import binding as B
     acc = np.zeros(B.SSV_NUM_KERNELS)
     for r in range(reps):
         ms = []
-        devs[r % len(devs)].run(kernel_ms=ms)
+        devs[r % len(devs)].run(kernel_ms=ms, repeats=20)
         acc += np.asarray(ms)
     return acc / reps
 
@@ -135,7 +137,7 @@ def measure_workload(torch, oracle, case, name, steps, warmup, n_copies, parity=
                 d.set_sel_idx(ref.sel_idx)
         cold_ms, cold_wall = time_calls(torch, devs, steps, warmup)
         warm_ms, _ = time_calls(torch, devs[:1], steps, warmup)
-        kms = kernel_breakdown(devs, max(10, min(steps, 50)))
+        kms = kernel_breakdown(devs, 2 * len(devs))
         out_modes[mname] = {
             "us_per_call_cold": cold_ms * 1e3, "us_per_call_warm": warm_ms * 1e3, "us_per_call_cold_wallclock": cold_wall * 1e3,
             "tokens_per_s_cold": tokens / (cold_ms * 1e-3), "tokens_per_s_warm": tokens / (warm_ms * 1e-3),
@@ -188,6 +190,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the configuration-2 measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default="", help="measure only this workload (cfg1 or cfg2); for profiling runs")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -201,6 +205,14 @@ def main():
     import ssv_inputs as si
 
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)       # reads 1 GiB, writes 1 GiB per copy
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     others = []
     main_res = None
     if args.only in ("", "cfg1"):

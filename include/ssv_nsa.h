@@ -115,14 +115,16 @@ int ssv_nsa_verify(const void* q, const void* k, const void* v, const void* k_cm
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Same computation, with a HIP event pair around every kernel; synchronises `stream` before returning and
- * writes the duration of each kernel in milliseconds to kernel_ms[SSV_NUM_KERNELS] (host; 0 for kernels the
- * mode does not launch).  Measurement aid for the roofline figures (Section 7 reports per-kernel breakdowns).
+ * Same computation, timed per kernel: every kernel of the call is launched `repeats` (1..1000) times back to
+ * back between one pair of HIP events on `stream` (all kernels are idempotent, so the results are those of
+ * ssv_nsa_verify); the call synchronises `stream` before returning and writes the average duration of one launch
+ * of each kernel, in milliseconds, to kernel_ms[SSV_NUM_KERNELS] (host; 0 for kernels the mode does not launch).
+ * Measurement aid for the roofline figures (Section 7.3 reports such a per-kernel breakdown).
  */
 int ssv_nsa_verify_timed(const void* q, const void* k, const void* v, const void* k_cmp, const void* v_cmp,
                          const float* gates, const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query,
                          const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx,
-                         void* workspace, size_t workspace_bytes, void* stream, float* kernel_ms);
+                         void* workspace, size_t workspace_bytes, void* stream, int repeats, float* kernel_ms);
 
 /* Validates p (host only, no GPU needed) and describes the launch plan.  Returns SSV_OK or an error code. */
 int ssv_nsa_plan_query(const ssv_nsa_params* p, ssv_nsa_plan* plan);

@@ -63,7 +63,7 @@ def load_library() -> ctypes.CDLL:
         lib.ssv_nsa_verify.restype = ctypes.c_int
         lib.ssv_nsa_verify.argtypes = common
         lib.ssv_nsa_verify_timed.restype = ctypes.c_int
-        lib.ssv_nsa_verify_timed.argtypes = common + [ctypes.POINTER(ctypes.c_float)]
+        lib.ssv_nsa_verify_timed.argtypes = common + [ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
         lib.ssv_nsa_plan_query.restype = ctypes.c_int
         lib.ssv_nsa_plan_query.argtypes = [ctypes.POINTER(SsvNsaParams), ctypes.POINTER(SsvNsaPlan)]
         lib.ssv_nsa_workspace_bytes.restype = ctypes.c_size_t
@@ -124,12 +124,12 @@ def _ptr(t) -> Optional[int]:
 
 
 def ssv_nsa_verify(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_parents, p: SsvNsaParams, out, sel_idx,
-                   workspace, workspace_bytes: int, stream: int, kernel_ms=None) -> None:
+                   workspace, workspace_bytes: int, stream: int, kernel_ms=None, repeats: int = 1) -> None:
     """Enqueue one verification call on `stream` (a hipStream_t as an integer).
 
     Tensors are device tensors (or integer device addresses); `p` describes shapes and strides.
-    With kernel_ms (a list), the timed entry point is used: it synchronises the stream and the
-    per-kernel durations in milliseconds are appended to the list.
+    With kernel_ms (a list), the timed entry point is used: every kernel runs `repeats` times back to
+    back, the stream is synchronised, and the average per-kernel durations (ms) are appended to the list.
     """
     lib = load_library()
     args = [_ptr(q), _ptr(k), _ptr(v), _ptr(k_cmp), _ptr(v_cmp), _ptr(gates), _ptr(seq_lens), _ptr(n_cmp),
@@ -139,7 +139,7 @@ def ssv_nsa_verify(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_
         rc = lib.ssv_nsa_verify(*args)
     else:
         ms = (ctypes.c_float * SSV_NUM_KERNELS)()
-        rc = lib.ssv_nsa_verify_timed(*args, ms)
+        rc = lib.ssv_nsa_verify_timed(*args, int(repeats), ms)
         kernel_ms.extend(float(x) for x in ms)
     if rc != SSV_OK:
         raise SsvError(rc, "ssv_nsa_verify")

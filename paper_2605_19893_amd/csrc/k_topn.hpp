@@ -135,7 +135,8 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     // threshold: the n_eff-th largest per-thread best (keys are distinct; threads without blocks hold 0)
     {
         int rank = 0;
-        for (int k = 0; k < kThreads; ++k) rank += s_best[k] > best;
+#pragma unroll 16
+        for (int k = 0; k < kThreads; ++k) rank += s_best[k] > best;   // broadcast LDS reads, 16 in flight
         if (best != 0 && rank == n_eff - 1) s_red[0] = best;
     }
     __syncthreads();
@@ -154,7 +155,15 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
         for (int e = tid; e < n_cand; e += kThreads) {
             const uint64_t key = s_cand[e];
             int rank = 0;
-            for (int f = 0; f < n_cand; ++f) rank += s_cand[f] > key;
+            int f = 0;
+            for (; f + 8 <= n_cand; f += 8) {
+                uint64_t c[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) c[u] = s_cand[f + u];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) rank += c[u] > key;
+            }
+            for (; f < n_cand; ++f) rank += s_cand[f] > key;
             if (rank < n_eff) s_pick[rank] = (int)(0xFFFFFFFFu - (uint32_t)key);
         }
     } else {
@@ -177,17 +186,19 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
         }
     }
     __syncthreads();
+    // ascending order: pick e goes to position (number of smaller picks); picks are distinct
     if (tid < a.n_sel) {
-        int val = -1;
-        if (tid < n_eff) {      // ascending order by rank counting (picks are distinct)
-            for (int e = 0; e < n_eff; ++e) {
-                const int x = s_pick[e];
-                int rank = 0;
-                for (int f = 0; f < n_eff; ++f) rank += s_pick[f] < x;
-                if (rank == tid) val = x;
-            }
+        int x = 0x7fffffff, rank = tid;      // threads beyond n_eff write the -1 padding at their own position
+        if (tid < n_eff) {
+            x = s_pick[tid];
+            rank = 0;
+            int p[kMaxNSel];
+#pragma unroll
+            for (int f = 0; f < kMaxNSel; ++f) p[f] = s_pick[f < n_eff ? f : 0];
+#pragma unroll
+            for (int f = 0; f < kMaxNSel; ++f) rank += (f < n_eff && p[f] < x) ? 1 : 0;
         }
-        out[tid] = val;
+        out[rank] = tid < n_eff ? x : -1;
     }
 }
 

@@ -126,7 +126,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
 
     lo->H_g = H_g;
     lo->nrt = nrt;
-    lo->n_imp_chunks = std::max(1, std::min(ceil_div(ntc, 2), std::max(1, 1024 / units)));
+    lo->n_imp_chunks = std::max(1, std::min(ceil_div(ntc, env_int("SSV_IMP_MIN_TILES", 1)), std::max(1, 1024 / units)));
     lo->es = es;
     lo->nc_pitch = (int)align_up((size_t)std::max(1, p->max_n_cmp), kTile);
     lo->max_blocks = max_blocks;
@@ -146,6 +146,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
 
 struct Timer {
     bool on = false;
+    int repeats = 1;     // timed mode: every kernel is launched this many times back to back (all are idempotent)
     hipStream_t stream = nullptr;
     hipEvent_t ev[SSV_NUM_KERNELS][2] = {};
     bool used[SSV_NUM_KERNELS] = {};
@@ -164,6 +165,7 @@ struct Timer {
             ms[k] = 0.f;
             if (used[k]) {
                 if (rc == 0 && hipEventElapsedTime(&ms[k], ev[k][0], ev[k][1]) != hipSuccess) rc = -1;
+                ms[k] /= (float)repeats;
                 (void)hipEventDestroy(ev[k][0]);
                 (void)hipEventDestroy(ev[k][1]);
             }
@@ -204,11 +206,14 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     const size_t lds_stream = stream_lds_bytes(SC::LDS_K, SC::LDS_VT, sa.max_sched, sa.bitmap_words);
     const int units = p->B * p->H_kv * pl.n_qg;
 
+    const int reps = tm.on ? tm.repeats : 1;
     auto launch_stream = [&](int slot_lo, int slot_cnt) -> int {
         sa.slot_lo = slot_lo; sa.slot_cnt = slot_cnt; sa.n_wg = units * slot_cnt;
         const int grid = ceil_div(sa.n_wg, 8) * 8;
-        if (lo.nrt == 2) hipLaunchKernelGGL((k_stream<BF16, DK, DV, 2>), dim3(grid), dim3(kThreads), lds_stream, stream, sa);
-        else hipLaunchKernelGGL((k_stream<BF16, DK, DV, 1>), dim3(grid), dim3(kThreads), lds_stream, stream, sa);
+        for (int r = 0; r < reps; ++r) {
+            if (lo.nrt == 2) hipLaunchKernelGGL((k_stream<BF16, DK, DV, 2>), dim3(grid), dim3(kThreads), lds_stream, stream, sa);
+            else hipLaunchKernelGGL((k_stream<BF16, DK, DV, 1>), dim3(grid), dim3(kThreads), lds_stream, stream, sa);
+        }
         return hipGetLastError() == hipSuccess ? 0 : -1;
     };
 
@@ -227,8 +232,10 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         for (int j = 0; j < 3; ++j) ia.kc_s[j] = sa.kc_s[j];
         const int grid_i = ceil_div(ia.n_wg, 8) * 8;
         if (tm.begin(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
-        if (lo.nrt == 2) hipLaunchKernelGGL((k_importance<BF16, DK, 2>), dim3(grid_i), dim3(kThreads), IC::LDS_TOTAL, stream, ia);
-        else hipLaunchKernelGGL((k_importance<BF16, DK, 1>), dim3(grid_i), dim3(kThreads), IC::LDS_TOTAL, stream, ia);
+        for (int r = 0; r < reps; ++r) {
+            if (lo.nrt == 2) hipLaunchKernelGGL((k_importance<BF16, DK, 2>), dim3(grid_i), dim3(kThreads), IC::LDS_TOTAL, stream, ia);
+            else hipLaunchKernelGGL((k_importance<BF16, DK, 1>), dim3(grid_i), dim3(kThreads), IC::LDS_TOTAL, stream, ia);
+        }
         if (hipGetLastError() != hipSuccess || tm.end(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
 
         TopnArgs ta{};
@@ -241,7 +248,8 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
             hipFuncSetAttribute((const void*)k_topn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_topn) != hipSuccess)
             return SSV_ELAUNCH;
         if (tm.begin(SSV_K_TOPN)) return SSV_ELAUNCH;
-        hipLaunchKernelGGL(k_topn, dim3(p->B * p->T * p->H_kv), dim3(kThreads), lds_topn, stream, ta);
+        for (int r = 0; r < reps; ++r)
+            hipLaunchKernelGGL(k_topn, dim3(p->B * p->T * p->H_kv), dim3(kThreads), lds_topn, stream, ta);
         if (hipGetLastError() != hipSuccess || tm.end(SSV_K_TOPN)) return SSV_ELAUNCH;
 
         if (tm.begin(SSV_K_STREAM_B) || launch_stream(pl.n_cmp_chunks + pl.n_win_splits, pl.n_slc_splits) ||
@@ -255,7 +263,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     ca.n_slc_splits = pl.n_slc_splits; ca.rows_total = lo.rows_total;
     const int grid_c = (int)lo.rows_total;   // one workgroup per output row
     if (tm.begin(SSV_K_COMBINE)) return SSV_ELAUNCH;
-    hipLaunchKernelGGL((k_combine<BF16, DV>), dim3(grid_c), dim3(kThreads), 0, stream, ca);
+    for (int r = 0; r < reps; ++r) hipLaunchKernelGGL((k_combine<BF16, DV>), dim3(grid_c), dim3(kThreads), 0, stream, ca);
     if (hipGetLastError() != hipSuccess || tm.end(SSV_K_COMBINE)) return SSV_ELAUNCH;
     return SSV_OK;
 }
@@ -263,9 +271,9 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
 int verify_impl(const void* q, const void* k, const void* v, const void* kc, const void* vc, const float* gates,
                 const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query, const int32_t* parents,
                 const ssv_nsa_params* p, void* out, int32_t* sel_idx, void* workspace, size_t workspace_bytes,
-                void* stream, float* kernel_ms, bool timed) {
+                void* stream, float* kernel_ms, int repeats, bool timed) {
     if (!q || !k || !v || !kc || !vc || !gates || !seq_lens || !n_cmp || !p || !out || !sel_idx) return SSV_EINVAL;
-    if (timed && !kernel_ms) return SSV_EINVAL;
+    if (timed && (!kernel_ms || repeats < 1 || repeats > 1000)) return SSV_EINVAL;
     Layout lo;
     const int rc = make_layout(p, &lo);
     if (rc != SSV_OK) return rc;
@@ -276,6 +284,7 @@ int verify_impl(const void* q, const void* k, const void* v, const void* kc, con
 
     Timer tm;
     tm.on = timed;
+    tm.repeats = timed ? repeats : 1;
     tm.stream = (hipStream_t)stream;
     int res = SSV_EUNSUPPORTED;
 #define SSV_DISPATCH(BF, DK, DV)                                                                                     \
@@ -322,15 +331,15 @@ int ssv_nsa_verify(const void* q, const void* k, const void* v, const void* k_cm
                    const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx, void* workspace,
                    size_t workspace_bytes, void* stream) {
     return verify_impl(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_parents, p, out, sel_idx, workspace,
-                       workspace_bytes, stream, nullptr, false);
+                       workspace_bytes, stream, nullptr, 1, false);
 }
 
 int ssv_nsa_verify_timed(const void* q, const void* k, const void* v, const void* k_cmp, const void* v_cmp,
                          const float* gates, const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query,
                          const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx,
-                         void* workspace, size_t workspace_bytes, void* stream, float* kernel_ms) {
+                         void* workspace, size_t workspace_bytes, void* stream, int repeats, float* kernel_ms) {
     return verify_impl(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_parents, p, out, sel_idx, workspace,
-                       workspace_bytes, stream, kernel_ms, true);
+                       workspace_bytes, stream, kernel_ms, repeats, true);
 }
 
 const char* ssv_nsa_strerror(int code) {

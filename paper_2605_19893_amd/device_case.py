@@ -63,12 +63,12 @@ class DeviceCase:
     def set_sel_idx(self, sel: np.ndarray) -> None:
         self.sel_idx.copy_(torch.from_numpy(np.ascontiguousarray(sel, np.int32)).to(self.device))
 
-    def run(self, kernel_ms=None) -> None:
+    def run(self, kernel_ms=None, repeats: int = 1) -> None:
         """Enqueue one call on torch's current stream."""
         stream = torch.cuda.current_stream(self.device).cuda_stream
         B.ssv_nsa_verify(self.q, self.k, self.v, self.k_cmp, self.v_cmp, self.gates, self.seq_lens, self.n_cmp,
                          self.n_query, self.parents, self.params, self.out, self.sel_idx, self.workspace,
-                         self.workspace_bytes, stream, kernel_ms=kernel_ms)
+                         self.workspace_bytes, stream, kernel_ms=kernel_ms, repeats=repeats)
 
     def results(self):
         torch.cuda.synchronize(self.device)
