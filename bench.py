@@ -99,25 +99,42 @@ def time_calls(torch, devs, steps, warmup):
     return ev0.elapsed_time(ev1) / steps, wall_ms / steps
 
 
-def kernel_breakdown(devs, reps):
-    """Average launch duration of every kernel: HIP events (inside the library, on the call's stream) around
-    20 back-to-back launches of each kernel, averaged over the rotating input copies."""
+def kernel_breakdown(devs, rounds, repeats):
+    """Average launch duration (ms) of every kernel, measured with HIP events inside the library on the call's
+    stream.  repeats == 1: one launch per event pair, rotating over the input copies (cold caches); the
+    duration of an empty event pair, measured in the same call, is reported next to it.  repeats > 1: that
+    many back-to-back launches per pair on one copy (the event overhead amortises, but inputs of small
+    workloads stay cache-resident)."""
     from paper_2605_19893_amd import binding as B
-    acc = np.zeros(B.SSV_NUM_KERNELS)
-    for r in range(reps):
+    acc = np.zeros(B.SSV_NUM_TIMINGS)
+    n = rounds * len(devs)
+    for r in range(n):
         ms = []
-        devs[r % len(devs)].run(kernel_ms=ms, repeats=20)
+        devs[r % len(devs)].run(kernel_ms=ms, repeats=repeats)
         acc += np.asarray(ms)
-    return acc / reps
+    return acc / n
 
 
-def measure_workload(torch, oracle, case, name, steps, warmup, n_copies, parity=True):
+def read_traffic(tag):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (profiles/hbm_traffic_<tag>.txt):
+    lines 'kernel_index: fetch_bytes write_bytes', already scaled by the copy-kernel calibration."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{tag}.txt")
+    out = {}
+    if os.path.exists(path):
+        with open(path) as f:
+            for line in f:
+                if line.startswith("kernel_index"):
+                    parts = line.split()
+                    out[int(parts[1].rstrip(":"))] = int(parts[2]) + int(parts[3])
+    return out
+
+
+def measure_workload(torch, oracle, case, name, tag, steps, warmup, n_copies, parity=True):
     from paper_2605_19893_amd import binding as B
     from paper_2605_19893_amd.device_case import DeviceCase
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     devs = [DeviceCase(case) for _ in range(n_copies)]
-    plan = devs[0].plan.as_dict()
-    res = {"workload": name, "plan": plan}
+    res = {"workload": name}
     ref = oracle.nsa_verify(case)
     devs[0].run()
     out, sel = devs[0].results()
@@ -126,10 +143,11 @@ def measure_workload(torch, oracle, case, name, steps, warmup, n_copies, parity=
         rep = compare(case, oracle, ref, out, sel)
         res["parity"] = {"idx_mismatch": rep.n_mismatch, "idx_mismatch_outside_ambiguity": rep.n_mismatch_strict,
                          "ambiguous_units": rep.n_ambiguous, "units": rep.n_units, "max_abs_err": rep.max_abs_err}
-    ab = algorithmic_bytes(case, ref.sel_idx, plan["C"])
+    ab = algorithmic_bytes(case, ref.sel_idx, devs[0].plan.C)
     res["algorithmic_bytes"] = ab
     tokens = int(case.n_query.sum())
     out_modes = {}
+    raw = {}
     for mode, mname in ((B.SSV_REFRESH, "refresh"), (B.SSV_REUSE, "reuse")):
         for d in devs:
             d.set_mode(mode)
@@ -137,28 +155,34 @@ def measure_workload(torch, oracle, case, name, steps, warmup, n_copies, parity=
                 d.set_sel_idx(ref.sel_idx)
         cold_ms, cold_wall = time_calls(torch, devs, steps, warmup)
         warm_ms, _ = time_calls(torch, devs[:1], steps, warmup)
-        kms = kernel_breakdown(devs, 2 * len(devs))
+        kms = kernel_breakdown(devs, 8, 1)
+        kms_rep = kernel_breakdown(devs[:1], 2, 20)
+        raw[mname] = kms
+        nk = B.SSV_NUM_KERNELS
         out_modes[mname] = {
+            "plan": devs[0].plan.as_dict(),
             "us_per_call_cold": cold_ms * 1e3, "us_per_call_warm": warm_ms * 1e3, "us_per_call_cold_wallclock": cold_wall * 1e3,
             "tokens_per_s_cold": tokens / (cold_ms * 1e-3), "tokens_per_s_warm": tokens / (warm_ms * 1e-3),
             "algorithmic_GBs_cold": ab["total"] / (cold_ms * 1e-3) / 1e9,
             "hbm_frac_whole_call_cold": ab["total"] / (cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "kernel_us_cold": {B.kernel_name(i): float(kms[i] * 1e3) for i in range(B.SSV_NUM_KERNELS) if kms[i] > 0},
-            "kernel_ms_raw": [float(x) for x in kms],
+            "kernel_us_cold_single_launch": {B.kernel_name(i): float(kms[i] * 1e3) for i in range(nk) if kms[i] > 0},
+            "event_pair_overhead_us": float(kms[B.SSV_T_EVENT_PAIR] * 1e3),
+            "kernel_us_20_back_to_back_launches": {B.kernel_name(i): float(kms_rep[i] * 1e3) for i in range(nk) if kms_rep[i] > 0},
         }
     res["modes"] = out_modes
-    # roofline of the dominant kernel of the refresh path
-    kms = np.asarray(out_modes["refresh"]["kernel_ms_raw"])
-    dom = int(np.argmax(kms))
+    # roofline of the dominant kernel of the refresh path: algorithmic bytes of that launch over its average
+    # duration (one launch per event pair, cold inputs, minus the duration of an empty event pair)
+    kms = raw["refresh"]
+    dom = int(np.argmax(kms[:B.SSV_NUM_KERNELS]))
     kbytes = {B.SSV_K_STREAM_A: ab["compressed"] + ab["window_union"],
               B.SSV_K_IMPORTANCE: ab["compressed"] * case.d_k // (case.d_k + case.d_v),
               B.SSV_K_STREAM_B: ab["selected_union"]}.get(dom, 0)
-    achieved = kbytes / (kms[dom] * 1e-3) / 1e9 if kms[dom] > 0 else 0.0
+    dur_ms = max(kms[dom] - kms[B.SSV_T_EVENT_PAIR], 1e-6)
+    achieved = kbytes / (dur_ms * 1e-3) / 1e9
     res["roofline"] = {"bound": "hbm", "kernel": B.kernel_name(dom), "achieved": achieved, "peak": HBM_PEAK_GBS,
-                       "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                       "algorithmic_bytes_per_launch": int(kbytes), "avg_launch_us": float(kms[dom] * 1e3)}
-    for m in out_modes.values():
-        del m["kernel_ms_raw"]
+                       "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(tag).get(dom),
+                       "algorithmic_bytes_per_launch": int(kbytes), "avg_launch_us": float(dur_ms * 1e3),
+                       "avg_launch_us_including_event_pair": float(kms[dom] * 1e3)}
     del devs
     torch.cuda.empty_cache()
     return res, ref
@@ -218,11 +242,11 @@ def main():
     if args.only in ("", "cfg1"):
         case1 = si.config1(args.rho)
         main_res, _ = measure_workload(torch, oracle, case1, f"cfg1: B=1 L=32768 T=8 chain rho={args.rho} H=64/4 d_k=192 d_v=128 "
-                                       "l=32 d=16 l'=64 n=16 w=512", args.steps, args.warmup, n_copies=8)
+                                       "l=32 d=16 l'=64 n=16 w=512", "cfg1", args.steps, args.warmup, n_copies=8)
     if args.only == "cfg2" or (not args.no_extra and args.only == ""):
         case2 = si.config2()
-        r2, _ = measure_workload(torch, oracle, case2, "cfg2: B=16 L=65536 T=4 chain rho=0.7, 5% keys x4", max(20, args.steps // 4),
-                                 max(5, args.warmup // 4), n_copies=2)
+        r2, _ = measure_workload(torch, oracle, case2, "cfg2: B=16 L=65536 T=4 chain rho=0.7, 5% keys x4", "cfg2",
+                                 max(20, args.steps // 4), max(5, args.warmup // 4), n_copies=2)
         del case2
         if main_res is None:
             main_res = r2
@@ -239,8 +263,8 @@ def main():
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": refresh["us_per_call_cold"] / 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": main_res["workload"], "mode": "refresh", "cache": "cold (8 rotating input copies)",
-                   "plan": main_res["plan"]},
+        "config": {"workload": main_res["workload"], "mode": "refresh", "cache": "cold (rotating input copies)",
+                   "plan": main_res["modes"]["refresh"]["plan"]},
         "roofline": main_res["roofline"],
         "cpu_baseline": base,
         "us_per_call": refresh["us_per_call_cold"],

@@ -58,6 +58,8 @@ extern "C" {
 #define SSV_K_STREAM_B  3     /* refresh only: selected-block attention over the merged schedule */
 #define SSV_K_COMBINE   4     /* merge of split partial states + gated combination */
 #define SSV_NUM_KERNELS 5
+#define SSV_T_EVENT_PAIR 5    /* ssv_nsa_verify_timed only: duration of an empty event pair (measurement overhead) */
+#define SSV_NUM_TIMINGS 6
 
 typedef struct ssv_nsa_params {
     int32_t B;            /* sequences in the batch */
@@ -118,7 +120,9 @@ int ssv_nsa_verify(const void* q, const void* k, const void* v, const void* k_cm
  * Same computation, timed per kernel: every kernel of the call is launched `repeats` (1..1000) times back to
  * back between one pair of HIP events on `stream` (all kernels are idempotent, so the results are those of
  * ssv_nsa_verify); the call synchronises `stream` before returning and writes the average duration of one launch
- * of each kernel, in milliseconds, to kernel_ms[SSV_NUM_KERNELS] (host; 0 for kernels the mode does not launch).
+ * of each kernel, in milliseconds, to kernel_ms[SSV_NUM_TIMINGS] (host; 0 for kernels the mode does not launch);
+ * kernel_ms[SSV_T_EVENT_PAIR] is the duration of an event pair with nothing in between, i.e. what the event
+ * mechanism itself adds to every measured interval.
  * Measurement aid for the roofline figures (Section 7.3 reports such a per-kernel breakdown).
  */
 int ssv_nsa_verify_timed(const void* q, const void* k, const void* v, const void* k_cmp, const void* v_cmp,

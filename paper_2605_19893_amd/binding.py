@@ -19,6 +19,7 @@ SSV_REFRESH, SSV_REUSE = 0, 1
 SSV_MAX_T = 64
 SSV_K_STREAM_A, SSV_K_IMPORTANCE, SSV_K_TOPN, SSV_K_STREAM_B, SSV_K_COMBINE = range(5)
 SSV_NUM_KERNELS = 5
+SSV_T_EVENT_PAIR, SSV_NUM_TIMINGS = 5, 6
 
 EXPORTS = ("ssv_nsa_verify", "ssv_nsa_verify_timed", "ssv_nsa_plan_query", "ssv_nsa_workspace_bytes",
            "ssv_nsa_supported", "ssv_nsa_strerror", "ssv_nsa_kernel_name", "ssv_nsa_version")
@@ -138,7 +139,7 @@ def ssv_nsa_verify(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_
     if kernel_ms is None:
         rc = lib.ssv_nsa_verify(*args)
     else:
-        ms = (ctypes.c_float * SSV_NUM_KERNELS)()
+        ms = (ctypes.c_float * SSV_NUM_TIMINGS)()
         rc = lib.ssv_nsa_verify_timed(*args, int(repeats), ms)
         kernel_ms.extend(float(x) for x in ms)
     if rc != SSV_OK:

@@ -74,7 +74,12 @@ __device__ long long g_clk[4096 * 16];
 #define SSV_STAMP(i) do { } while (0)
 #endif
 
-template <bool BF16, int DK, int DV, int NRT>
+// ROLES: which branches this instantiation can run (bit 0 CMP, bit 1 WIN, bit 2 SLC).  The refresh path
+// launches <CMP|WIN> and then <SLC>, the reuse path launches all three at once; code of absent roles is
+// compiled out.
+constexpr int kRolesCmpWin = 3, kRolesSlc = 4, kRolesAll = 7;
+
+template <bool BF16, int DK, int DV, int NRT, int ROLES>
 __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     using Cfg = StreamCfg<BF16, DK, DV>;
     constexpr int ES = Cfg::ES, KP = Cfg::KP, KCH = Cfg::KCH, VP = Cfg::VP, MT = Cfg::MT;
@@ -111,6 +116,9 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     if (slot < a.n_cmp_chunks) { role = ROLE_CMP; part = slot; }
     else if (slot < a.n_cmp_chunks + a.n_win_splits) { role = ROLE_WIN; part = slot - a.n_cmp_chunks; }
     else { role = ROLE_SLC; part = slot - a.n_cmp_chunks - a.n_win_splits; }
+    const bool r_cmp = (ROLES & 1) && role == ROLE_CMP;
+    const bool r_win = (ROLES & 2) && role == ROLE_WIN;
+    const bool r_slc = (ROLES & 4) && role == ROLE_SLC;
 
     const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, s_par, s_depth, s_cmax,
                                        s_anc);
@@ -140,12 +148,12 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     // ---- tile range of this workgroup
     int t0 = 0, t1 = 0;           // CMP / WIN: tile indices; SLC: schedule entries
     if (nq_grp > 0) {
-        if (role == ROLE_CMP) {
+        if (r_cmp) {
             int cm = 0;
             for (int j = 0; j < nq_grp; ++j) cm = max(cm, s_cmax[qg * a.C + j]);
             const int ntiles = (cm + kTile - 1) / kTile;
             even_slice(ntiles, a.n_cmp_chunks, a.min_tiles, part, t0, t1);
-        } else if (role == ROLE_WIN) {
+        } else if (r_win) {
             int dmin = 1 << 30;
             for (int j = 0; j < nq_grp; ++j) dmin = min(dmin, s_depth[qg * a.C + j]);
             const int wlo = max(0, L + dmin - a.w + 1) / kTile;
@@ -153,7 +161,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
             even_slice(whi - wlo, a.n_win_splits, a.min_tiles, part, t0, t1);
             t0 += wlo;
             t1 += wlo;
-        } else {
+        } else if (r_slc) {
             // merged schedule: bitmap over blocks -> ranks by prefix popcount -> sorted unique list + ownership
             const int nblk = min((n_slots_kv + kTile - 1) / kTile, a.bitmap_words * 32);
             const int nwords = (nblk + 31) >> 5;
@@ -224,7 +232,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     const char* kbase;
     const char* vbase;
     int64_t krow, vrow;
-    if (role == ROLE_CMP) {
+    if (r_cmp) {
         kbase = a.kc + b * a.kc_s[0] + g * a.kc_s[1];
         vbase = a.vc + b * a.vc_s[0] + g * a.vc_s[1];
         krow = a.kc_s[2];
@@ -235,7 +243,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         krow = a.k_s[2];
         vrow = a.v_s[2];
     }
-    const int rows_exist = role == ROLE_CMP ? sm.n_cmp : n_slots_kv;
+    const int rows_exist = r_cmp ? sm.n_cmp : n_slots_kv;
     const int vt_rb = vt_load_base_bf16(n, G);   // this lane's base offset into the swizzled bf16 V^T tile
     SSV_STAMP(3);
 
@@ -243,7 +251,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     // committed to LDS after it; two barriers per tile separate the LDS writes from the fragment reads.
     RowTileRegs<Cfg::KROW> kregs;
     TransposedTileRegs<BF16, DV> vregs;
-    auto tile_of = [&](int it) { return role == ROLE_SLC ? s_id[it] : it; };
+    auto tile_of = [&](int it) { return r_slc ? s_id[it] : it; };
     if (t0 < t1) {
         const int base0 = tile_of(t0) * kTile;
         const int vr0 = min(kTile, rows_exist - base0);
@@ -252,10 +260,10 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     }
     for (int it = t0; it < t1; ++it) {
         const int tile = tile_of(it);
-        const uint64_t own = role == ROLE_SLC ? s_own[it] : ~0ull;
+        const uint64_t own = r_slc ? s_own[it] : ~0ull;
         const int base = tile * kTile;
         const int valid_rows = min(kTile, rows_exist - base);
-        const bool has_drafts = role != ROLE_CMP && base + kTile > L;   // uniform: the tile holds draft slots
+        const bool has_drafts = !r_cmp && base + kTile > L;   // uniform: the tile holds draft slots
 
         if (it > t0) __syncthreads();   // every wave has finished reading the previous tile
         kregs.template commit<KP>(sK, valid_rows, tid);
@@ -280,13 +288,13 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         for (int t = 0; t < NRT; ++t) {
             vm[t] = 0;
             if (!rvalid[t]) continue;
-            if (role == ROLE_CMP) {
+            if (r_cmp) {
                 const int lim = cmax[t] - base - 4 * G;          // keys with 16 kt + r < lim are visible
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt) vm[t] |= ((1u << min(max(lim - 16 * kt, 0), 4)) - 1u) << (4 * kt);
-            } else if (role == ROLE_WIN || ((own >> iq[t]) & 1ull)) {
+            } else if (r_win || (r_slc && ((own >> iq[t]) & 1ull))) {
                 if (!has_drafts) {                               // every key is a committed token
-                    if (role == ROLE_SLC) vm[t] = 0xFFFFu;
+                    if (r_slc) vm[t] = 0xFFFFu;
                     else {
                         const int lo = pos[t] - a.w + 1 - base - 4 * G;   // keys with 16 kt + r >= lo are in the window
 #pragma unroll
@@ -300,7 +308,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                                                 : (-cl < 64 ? anc[t] >> (-cl) : 0ull);
 #pragma unroll
                     for (int kt = 0; kt < 4; ++kt) vm[t] |= (uint32_t)((vis >> (16 * kt + 4 * G)) & 0xFull) << (4 * kt);
-                    if (role == ROLE_WIN) {
+                    if (r_win) {
 #pragma unroll
                         for (int kt = 0; kt < 4; ++kt) {
                             const int4 kp = *reinterpret_cast<const int4*>(s_kpos + 16 * kt + 4 * G);

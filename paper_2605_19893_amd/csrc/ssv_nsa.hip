@@ -148,8 +148,8 @@ struct Timer {
     bool on = false;
     int repeats = 1;     // timed mode: every kernel is launched this many times back to back (all are idempotent)
     hipStream_t stream = nullptr;
-    hipEvent_t ev[SSV_NUM_KERNELS][2] = {};
-    bool used[SSV_NUM_KERNELS] = {};
+    hipEvent_t ev[SSV_NUM_TIMINGS][2] = {};
+    bool used[SSV_NUM_TIMINGS] = {};
     int begin(int k) {
         if (!on) return 0;
         if (hipEventCreate(&ev[k][0]) != hipSuccess || hipEventCreate(&ev[k][1]) != hipSuccess) return -1;
@@ -161,11 +161,11 @@ struct Timer {
         int rc = 0;
         if (!on) return 0;
         if (hipStreamSynchronize(stream) != hipSuccess) rc = -1;
-        for (int k = 0; k < SSV_NUM_KERNELS; ++k) {
+        for (int k = 0; k < SSV_NUM_TIMINGS; ++k) {
             ms[k] = 0.f;
             if (used[k]) {
                 if (rc == 0 && hipEventElapsedTime(&ms[k], ev[k][0], ev[k][1]) != hipSuccess) rc = -1;
-                ms[k] /= (float)repeats;
+                if (k < SSV_NUM_KERNELS) ms[k] /= (float)repeats;
                 (void)hipEventDestroy(ev[k][0]);
                 (void)hipEventDestroy(ev[k][1]);
             }
@@ -210,9 +210,20 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     auto launch_stream = [&](int slot_lo, int slot_cnt) -> int {
         sa.slot_lo = slot_lo; sa.slot_cnt = slot_cnt; sa.n_wg = units * slot_cnt;
         const int grid = ceil_div(sa.n_wg, 8) * 8;
+        const bool all = slot_cnt == pl.n_slots, only_slc = slot_lo > 0;
         for (int r = 0; r < reps; ++r) {
-            if (lo.nrt == 2) hipLaunchKernelGGL((k_stream<BF16, DK, DV, 2>), dim3(grid), dim3(kThreads), lds_stream, stream, sa);
-            else hipLaunchKernelGGL((k_stream<BF16, DK, DV, 1>), dim3(grid), dim3(kThreads), lds_stream, stream, sa);
+#define SSV_LAUNCH_STREAM(NRT_, ROLES_) \
+    hipLaunchKernelGGL((k_stream<BF16, DK, DV, NRT_, ROLES_>), dim3(grid), dim3(kThreads), lds_stream, stream, sa)
+            if (lo.nrt == 2) {
+                if (all) SSV_LAUNCH_STREAM(2, kRolesAll);
+                else if (only_slc) SSV_LAUNCH_STREAM(2, kRolesSlc);
+                else SSV_LAUNCH_STREAM(2, kRolesCmpWin);
+            } else {
+                if (all) SSV_LAUNCH_STREAM(1, kRolesAll);
+                else if (only_slc) SSV_LAUNCH_STREAM(1, kRolesSlc);
+                else SSV_LAUNCH_STREAM(1, kRolesCmpWin);
+            }
+#undef SSV_LAUNCH_STREAM
         }
         return hipGetLastError() == hipSuccess ? 0 : -1;
     };
@@ -262,6 +273,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     ca.T = p->T; ca.H = p->H; ca.n_cmp_chunks = pl.n_cmp_chunks; ca.n_win_splits = pl.n_win_splits;
     ca.n_slc_splits = pl.n_slc_splits; ca.rows_total = lo.rows_total;
     const int grid_c = (int)lo.rows_total;   // one workgroup per output row
+    if (tm.begin(SSV_T_EVENT_PAIR) || tm.end(SSV_T_EVENT_PAIR)) return SSV_ELAUNCH;   // empty pair: the overhead itself
     if (tm.begin(SSV_K_COMBINE)) return SSV_ELAUNCH;
     for (int r = 0; r < reps; ++r) hipLaunchKernelGGL((k_combine<BF16, DV>), dim3(grid_c), dim3(kThreads), 0, stream, ca);
     if (hipGetLastError() != hipSuccess || tm.end(SSV_K_COMBINE)) return SSV_ELAUNCH;
