@@ -80,21 +80,24 @@ struct RowTileRegs {
     }
 };
 
-// Layout of the bf16 V^T tile: row = value column (128 bytes = 16 "key quads" of 4 keys x 2 bytes, no
-// padding); key quad q of column c sits at quad position q ^ sw(c), sw(c) = ((c >> 3) ^ c) & 15.  The XOR
-// swizzle spreads both access patterns over all banks: the transposing store (16 lanes = 16 columns that
-// are 8 apart, same quad) and the MFMA operand load (16 lanes = 16 consecutive columns, same quad).
-// Because XOR distributes, a lane needs only a base offset; every unrolled access is (base ^ constant) +
-// constant:
-//   store, lane (kq, ch), column 8 ch + cc:   (ch * 1024 + ((kq ^ ch ^ 8 (ch & 1)) & 15) * 8) ^ (cc * 8)  +  cc * 128
-//   load,  lane (n, G), column 16 mt + n, quad 8 u + 4 h + G:
-//                                             (n * 128 + ((G ^ n ^ (n >> 3)) & 15) * 8) ^ (16 * ((4 u + 2 h) ^ mt))  +  mt * 2048
+// Layout of the bf16 V^T tile: row = value column (128 bytes, no padding) = 8 "pairs" of 16 bytes; pair
+// p = 4 u + G holds the two key quads (4 keys x 2 bytes each) 8 u + G and 8 u + 4 + G side by side, which
+// are exactly the eight keys lane group G feeds to one K=32 MFMA step u, so one 16-byte LDS read is a whole
+// MFMA operand.  The pair index is XOR-swizzled with sw(c) = (c ^ (c >> 3)) & 7 of the column so that both
+// access patterns spread over the banks: the operand load (8 lanes = 8 consecutive columns, same pair) and
+// the transposing store (16 lanes = 16 columns that are 8 apart, same pair: 2-way at worst).  Because XOR
+// distributes, a lane needs one base offset and every unrolled access is (base ^ constant) + constant:
+//   store, lane (key quad kq = 8 u + 4 h + G, chunk ch), column 8 ch + cc:
+//       (ch * 1024 + ((4 u ^ G ^ (ch & 7)) * 16) + 8 h) ^ (cc * 16)  +  cc * 128
+//   load,  lane (n, G), column 16 mt + n, pair 4 u + G:
+//       (n * 128 + ((G ^ (n & 7) ^ (n >> 3)) & 7) * 16) ^ (16 * ((4 u) ^ ((2 mt) & 7)))  +  mt * 2048
 constexpr int kVtPitchBf16 = 128;
 __device__ __forceinline__ int vt_store_base_bf16(int kq, int ch) {
-    return ch * 8 * kVtPitchBf16 + ((kq ^ ch ^ (8 * (ch & 1))) & 15) * 8;
+    const int u = kq >> 3, h = (kq >> 2) & 1, G = kq & 3;
+    return ch * 8 * kVtPitchBf16 + (((4 * u) ^ G ^ (ch & 7)) & 7) * 16 + 8 * h;
 }
 __device__ __forceinline__ int vt_load_base_bf16(int n, int G) {
-    return n * kVtPitchBf16 + ((G ^ n ^ (n >> 3)) & 15) * 8;
+    return n * kVtPitchBf16 + ((G ^ (n & 7) ^ (n >> 3)) & 7) * 16;
 }
 
 // Transposing load: 64 rows x DV values (row-major in global memory) become LDS rows indexed by
@@ -148,8 +151,8 @@ struct TransposedTileRegs {
                     hi[0] = (w0 >> 16) | (w1 & 0xFFFF0000u);
                     hi[1] = (w2 >> 16) | (w3 & 0xFFFF0000u);
                     const int cc = 2 * e2;
-                    *reinterpret_cast<u32x2*>(lds + (wb ^ (cc * 8)) + cc * PITCH) = lo;
-                    *reinterpret_cast<u32x2*>(lds + (wb ^ ((cc + 1) * 8)) + (cc + 1) * PITCH) = hi;
+                    *reinterpret_cast<u32x2*>(lds + (wb ^ (cc * 16)) + cc * PITCH) = lo;
+                    *reinterpret_cast<u32x2*>(lds + (wb ^ ((cc + 1) * 16)) + (cc + 1) * PITCH) = hi;
                 }
             } else {
 #pragma unroll

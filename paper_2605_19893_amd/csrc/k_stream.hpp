@@ -346,10 +346,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
 #pragma unroll
             for (int t = 0; t < NRT; ++t) {
                 float mx = -INFINITY;
-#pragma unroll
-                for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) s[t][kt][r] *= a.scale_log2;
+                // scores stay unscaled: the running maximum is kept in raw units and the scale (times log2 e)
+                // is applied inside the exponent, one fused multiply-add per key
                 if (__builtin_amdgcn_ballot_w64(vm[t] != 0xFFFFu) != 0ull) {   // uniform: some key is masked
 #pragma unroll
                     for (int kt = 0; kt < 4; ++kt)
@@ -365,13 +363,14 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
                 const float m_new = fmaxf(mrun[t], mx);
                 const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-                const float alpha = fast_exp2(mrun[t] - m_use);
+                const float alpha = fast_exp2((mrun[t] - m_use) * a.scale_log2);
+                const float neg_ms = -m_use * a.scale_log2;
                 float rs = 0.f;
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const float pz = fast_exp2(s[t][kt][r] - m_use);
+                        const float pz = fast_exp2(__builtin_fmaf(s[t][kt][r], a.scale_log2, neg_ms));
                         s[t][kt][r] = pz;
                         rs += pz;
                     }
@@ -402,9 +401,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                     }
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
-                        const u32x2 lo = lds_read8(sVT + (vt_rb ^ (16 * ((4 * u) ^ mt))) + mt * 16 * VP);
-                        const u32x2 hi = lds_read8(sVT + (vt_rb ^ (16 * ((4 * u + 2) ^ mt))) + mt * 16 * VP);
-                        const u32x4 vf = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                        const u32x4 vf = lds_read16(sVT + (vt_rb ^ (16 * ((4 * u) ^ ((2 * mt) & 7)))) + mt * 16 * VP);
 #pragma unroll
                         for (int t = 0; t < NRT; ++t) acc[t][mt] = mma_frag<true>(vf, pb[t], acc[t][mt]);
                     }
@@ -434,7 +431,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         if (!rvalid[t]) continue;
         const int64_t pr = (int64_t)slot * a.rows_total + grow[t];
         if (G == 0) {
-            a.part_stats[pr * 2 + 0] = mrun[t];
+            a.part_stats[pr * 2 + 0] = mrun[t] * a.scale_log2;   // statistics leave the kernel in the log2 domain
             a.part_stats[pr * 2 + 1] = zrun[t];
         }
         if (zrun[t] > 0.f) {
