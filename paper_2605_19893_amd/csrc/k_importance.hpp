@@ -36,7 +36,8 @@ struct ImportanceCfg {
     static constexpr int KP = KROW + 16;
     static constexpr int KCH = KROW / 64;
     static constexpr int LDS_K = kTile * KP;
-    static constexpr int LDS_TOTAL = LDS_K + 256 * 8 /*stats*/ + 64 * kTile * 4 /*colsum tile*/ + kMaxT * 20 + 64;
+    // LDS bytes: K tile, merged row statistics, per-sequence tree metadata, then the head-summed tile [C][64]
+    static constexpr int lds_bytes(int C) { return LDS_K + 256 * 8 + kMaxT * 20 + 64 + C * kTile * 4; }
 };
 
 template <bool BF16, int DK, int NRT>
@@ -46,11 +47,11 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     extern __shared__ __align__(16) char smem[];
     char* sK = smem;
     float2* s_stat = reinterpret_cast<float2*>(sK + Cfg::LDS_K);   // [128] (M, 1/Z) per workgroup row
-    float* s_cs = reinterpret_cast<float*>(s_stat + 256);          // [C <= 64][64] head-summed probabilities
-    uint64_t* s_anc = reinterpret_cast<uint64_t*>(s_cs + 64 * kTile);
+    uint64_t* s_anc = reinterpret_cast<uint64_t*>(s_stat + 256);
     int* s_par = reinterpret_cast<int*>(s_anc + kMaxT);
     int* s_depth = s_par + kMaxT;
     int* s_cmax = s_depth + kMaxT;
+    float* s_cs = reinterpret_cast<float*>(s_cmax + kMaxT + 16);   // [C][64] head-summed probabilities
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, G = lane >> 4;

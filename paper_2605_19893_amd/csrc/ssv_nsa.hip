@@ -126,6 +126,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
 
     lo->H_g = H_g;
     lo->nrt = nrt;
+    // importance pass: 4 workgroups per CU are resident (120 VGPRs, about 30 KB LDS): one round of at most 1024
     lo->n_imp_chunks = std::max(1, std::min(ceil_div(ntc, env_int("SSV_IMP_MIN_TILES", 1)), std::max(1, 1024 / units)));
     lo->es = es;
     lo->nc_pitch = (int)align_up((size_t)std::max(1, p->max_n_cmp), kTile);
@@ -244,8 +245,8 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         const int grid_i = ceil_div(ia.n_wg, 8) * 8;
         if (tm.begin(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
         for (int r = 0; r < reps; ++r) {
-            if (lo.nrt == 2) hipLaunchKernelGGL((k_importance<BF16, DK, 2>), dim3(grid_i), dim3(kThreads), IC::LDS_TOTAL, stream, ia);
-            else hipLaunchKernelGGL((k_importance<BF16, DK, 1>), dim3(grid_i), dim3(kThreads), IC::LDS_TOTAL, stream, ia);
+            if (lo.nrt == 2) hipLaunchKernelGGL((k_importance<BF16, DK, 2>), dim3(grid_i), dim3(kThreads), IC::lds_bytes(pl.C), stream, ia);
+            else hipLaunchKernelGGL((k_importance<BF16, DK, 1>), dim3(grid_i), dim3(kThreads), IC::lds_bytes(pl.C), stream, ia);
         }
         if (hipGetLastError() != hipSuccess || tm.end(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
 
