@@ -70,7 +70,13 @@ __device__ __forceinline__ void even_slice(int n, int parts, int min_items, int 
 #ifdef SSV_CLOCKS
 __device__ long long g_clk[4096 * 16];
 #define SSV_STAMP(i) do { if (threadIdx.x == 0 && wg < 4096) g_clk[wg * 16 + (i)] = wall_clock64(); } while (0)
+#define SSV_PHASE_DECL long long ph_[6] = {0, 0, 0, 0, 0, 0}; long long pt_ = wall_clock64();
+#define SSV_PHASE(i) do { const long long n_ = wall_clock64(); ph_[i] += n_ - pt_; pt_ = n_; } while (0)
+#define SSV_PHASE_WRITE do { if (threadIdx.x == 0 && wg < 4096) { for (int i_ = 0; i_ < 6; ++i_) g_clk[wg * 16 + 8 + i_] = ph_[i_]; } } while (0)
 #else
+#define SSV_PHASE_DECL
+#define SSV_PHASE(i) do { } while (0)
+#define SSV_PHASE_WRITE do { } while (0)
 #define SSV_STAMP(i) do { } while (0)
 #endif
 
@@ -247,18 +253,28 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     const int vt_rb = vt_load_base_bf16(n, G);   // this lane's base offset into the swizzled bf16 V^T tile
     SSV_STAMP(3);
 
-    // Software pipeline: the global loads of tile it+1 are issued before tile it is computed and are
-    // committed to LDS after it; two barriers per tile separate the LDS writes from the fragment reads.
-    RowTileRegs<Cfg::KROW> kregs;
-    TransposedTileRegs<BF16, DV> vregs;
+    // Software pipeline: the global loads of tile it+AHEAD are issued before tile it is computed and are
+    // committed to LDS AHEAD tiles later (alternating register sets when AHEAD > 1); two barriers per tile
+    // separate the LDS writes from the fragment reads.  Measured with in-kernel clocks, the prefetched loads
+    // have always arrived by the time they are committed at one tile ahead (the tile loop is bound by its own
+    // instruction stream), and two tiles ahead bought nothing for 40 more registers, so AHEAD stays 1.
+    constexpr int AHEAD = 1;
+    RowTileRegs<Cfg::KROW> kregs[AHEAD];
+    TransposedTileRegs<BF16, DV> vregs[AHEAD];
     auto tile_of = [&](int it) { return r_slc ? s_id[it] : it; };
-    if (t0 < t1) {
-        const int base0 = tile_of(t0) * kTile;
-        const int vr0 = min(kTile, rows_exist - base0);
-        kregs.issue(kbase + (int64_t)base0 * krow, (uint32_t)krow, vr0, tid);
-        vregs.issue(vbase + (int64_t)base0 * vrow, (uint32_t)vrow, vr0, tid);
-    }
-    for (int it = t0; it < t1; ++it) {
+    auto issue_tile = [&](int it, RowTileRegs<Cfg::KROW>& kr, TransposedTileRegs<BF16, DV>& vr) {
+        const int base_n = tile_of(it) * kTile;
+        const int vr_n = min(kTile, rows_exist - base_n);
+        kr.issue(kbase + (int64_t)base_n * krow, (uint32_t)krow, vr_n, tid);
+        vr.issue(vbase + (int64_t)base_n * vrow, (uint32_t)vrow, vr_n, tid);
+    };
+#pragma unroll
+    for (int j = 0; j < AHEAD; ++j)
+        if (t0 + j < t1) issue_tile(t0 + j, kregs[j], vregs[j]);
+    SSV_PHASE_DECL
+    // One tile; (kcur, vcur) hold tile `it` and, once committed to LDS, take tile it + AHEAD.
+    auto tile_step = [&](const int it, RowTileRegs<Cfg::KROW>& kcur, TransposedTileRegs<BF16, DV>& vcur) {
+        SSV_PHASE(5);
         const int tile = tile_of(it);
         const uint64_t own = r_slc ? s_own[it] : ~0ull;
         const int base = tile * kTile;
@@ -266,20 +282,22 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         const bool has_drafts = !r_cmp && base + kTile > L;   // uniform: the tile holds draft slots
 
         if (it > t0) __syncthreads();   // every wave has finished reading the previous tile
-        kregs.template commit<KP>(sK, valid_rows, tid);
-        vregs.template commit<VP>(sVT, valid_rows, tid);
+        SSV_PHASE(0);
+#ifdef SSV_CLOCKS
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): separate the wait for the prefetched loads from the LDS stores
+        SSV_PHASE(1);
+#endif
+        kcur.template commit<KP>(sK, valid_rows, tid);
+        vcur.template commit<VP>(sVT, valid_rows, tid);
         if (has_drafts && tid < kTile) {   // absolute position of every key of the tile (tree drafts: L + depth)
             const int s = base + tid;
             s_kpos[tid] = s < L ? s : (s - L < Tq ? L + s_depth[s - L] : 0x7fffffff);
         }
+        SSV_PHASE(2);
         __syncthreads();
-        if (it + 1 < t1) {
-            const int base1 = tile_of(it + 1) * kTile;
-            const int vr1 = min(kTile, rows_exist - base1);
-            kregs.issue(kbase + (int64_t)base1 * krow, (uint32_t)krow, vr1, tid);
-            vregs.issue(vbase + (int64_t)base1 * vrow, (uint32_t)vrow, vr1, tid);
-        }
-        if (it - t0 < 5) SSV_STAMP(4 + 2 * (it - t0));
+        SSV_PHASE(3);
+        if (it + AHEAD < t1) issue_tile(it + AHEAD, kcur, vcur);
+        SSV_PHASE(4);
 
         // ---- validity of this lane's 16 keys (4 key tiles x 4 registers) for each of its query rows;
         //      bit 4 kt + r <-> key base + 16 kt + 4 G + r
@@ -421,9 +439,15 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                 }
             }
         }
-        if (it - t0 < 5) SSV_STAMP(5 + 2 * (it - t0));
+    };
+    for (int it = t0; it < t1; it += AHEAD) {
+#pragma unroll
+        for (int j = 0; j < AHEAD; ++j)
+            if (it + j < t1) tile_step(it + j, kregs[j], vregs[j]);
     }
-    SSV_STAMP(14);
+    SSV_PHASE(5);
+    SSV_PHASE_WRITE;
+    SSV_STAMP(4);
 
     // ---- partial state of this slice: (m, Z) per row and the un-normalised accumulator
 #pragma unroll
@@ -440,7 +464,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                 *reinterpret_cast<f32x4*>(a.part_acc + pr * DV + 16 * mt + 4 * G) = acc[t][mt];
         }
     }
-    SSV_STAMP(15);
+    SSV_STAMP(5);
 }
 
 }  // namespace ssv
