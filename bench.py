@@ -129,11 +129,11 @@ def read_traffic(tag):
     return out
 
 
-def measure_workload(torch, oracle, case, name, tag, steps, warmup, n_copies, parity=True):
+def measure_workload(torch, oracle, case, name, tag, steps, warmup, n_copies, parity=True, group_size=0):
     from paper_2605_19893_amd import binding as B
     from paper_2605_19893_amd.device_case import DeviceCase
     sys.path.insert(0, os.path.join(ROOT, "tests"))
-    devs = [DeviceCase(case) for _ in range(n_copies)]
+    devs = [DeviceCase(case, group_size=group_size) for _ in range(n_copies)]
     res = {"workload": name}
     ref = oracle.nsa_verify(case)
     devs[0].run()
@@ -213,7 +213,8 @@ def main():
     ap.add_argument("--rho", type=float, default=0.5)
     ap.add_argument("--no-extra", action="store_true", help="skip the configuration-2 measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", default="", help="measure only this workload (cfg1 or cfg2); for profiling runs")
+    ap.add_argument("--only", default="", help="measure only this workload (cfg1, cfg2, cfg3 or cfg4); for profiling runs")
+    ap.add_argument("--group-size", type=int, default=0, help="verifier queries per workgroup (0 = library default)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
@@ -243,6 +244,14 @@ def main():
         case1 = si.config1(args.rho)
         main_res, _ = measure_workload(torch, oracle, case1, f"cfg1: B=1 L=32768 T=8 chain rho={args.rho} H=64/4 d_k=192 d_v=128 "
                                        "l=32 d=16 l'=64 n=16 w=512", "cfg1", args.steps, args.warmup, n_copies=8)
+    for tag, make, label, copies in (
+            ("cfg3", lambda: si.config3("bfs"), "cfg3: B=4 L=131072 T=40 tree (4,3,2) BFS order", 1),
+            ("cfg4", lambda: si.config4(), "cfg4: B=32 L log-uniform 4K..128K T=16 chain rho=0.7", 1)):
+        if args.only == tag:
+            casex = make()
+            main_res, _ = measure_workload(torch, oracle, casex, label, tag, max(10, args.steps // 10), 3, n_copies=copies,
+                                           group_size=args.group_size)
+            del casex
     if args.only == "cfg2" or (not args.no_extra and args.only == ""):
         case2 = si.config2()
         r2, _ = measure_workload(torch, oracle, case2, "cfg2: B=16 L=65536 T=4 chain rho=0.7, 5% keys x4", "cfg2",

@@ -53,15 +53,27 @@ struct RowTileRegs {
     static_assert(TOTAL % kThreads == 0, "tile must divide evenly over the workgroup");
     static constexpr int ITERS = TOTAL / kThreads;
     u32x4 val[ITERS];
+    uint32_t off[ITERS];     // byte offsets of this thread's chunks inside a full tile (tile-invariant)
 
-    __device__ __forceinline__ void issue(const char* g, uint32_t g_row_bytes, int valid_rows, int tid) {
-        const int last = valid_rows - 1;     // == 63 for every tile but the last one of a sequence
+    __device__ __forceinline__ void init(uint32_t g_row_bytes, int tid) {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int f = it * kThreads + tid;
-            const int row = f / CPR, col = f % CPR;
-            const uint32_t off = (uint32_t)min(row, last) * g_row_bytes + (uint32_t)col * 16u;
-            val[it] = *reinterpret_cast<const u32x4*>(g + off);
+            off[it] = (uint32_t)(f / CPR) * g_row_bytes + (uint32_t)(f % CPR) * 16u;
+        }
+    }
+    __device__ __forceinline__ void issue(const char* g, uint32_t g_row_bytes, int valid_rows, int tid) {
+        if (valid_rows == kTile) {           // uniform; every tile but the last one of a sequence
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) val[it] = *reinterpret_cast<const u32x4*>(g + off[it]);
+        } else {
+            const int last = valid_rows - 1;
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                const int f = it * kThreads + tid;
+                const int row = f / CPR, col = f % CPR;
+                val[it] = *reinterpret_cast<const u32x4*>(g + (uint32_t)min(row, last) * g_row_bytes + (uint32_t)col * 16u);
+            }
         }
     }
     template <int PITCH>
@@ -113,17 +125,33 @@ struct TransposedTileRegs {
     static_assert(ITEMS % kThreads == 0 || kThreads % ITEMS == 0, "unsupported value width");
     static constexpr int ITERS = (ITEMS + kThreads - 1) / kThreads;
     u32x4 r[ITERS][4];
+    uint32_t off[ITERS];     // byte offset of the first of this thread's four rows inside a full tile
 
-    __device__ __forceinline__ void issue(const char* g, uint32_t g_row_bytes, int valid_rows, int tid) {
-        if (ITEMS < kThreads && tid >= ITEMS) return;   // whole wavefronts drop out (ITEMS is a multiple of 64)
+    __device__ __forceinline__ void init(uint32_t g_row_bytes, int tid) {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int item = it * kThreads + tid;
-            const int kq = item / CPR, ch = item % CPR;
+            off[it] = (uint32_t)(4 * (item / CPR)) * g_row_bytes + (uint32_t)(item % CPR) * 16u;
+        }
+    }
+    __device__ __forceinline__ void issue(const char* g, uint32_t g_row_bytes, int valid_rows, int tid) {
+        if (ITEMS < kThreads && tid >= ITEMS) return;   // whole wavefronts drop out (ITEMS is a multiple of 64)
+        if (valid_rows == kTile) {           // uniform; every tile but the last one of a sequence
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t off = (uint32_t)min(4 * kq + j, valid_rows - 1) * g_row_bytes + (uint32_t)ch * 16u;
-                r[it][j] = *reinterpret_cast<const u32x4*>(g + off);
+            for (int it = 0; it < ITERS; ++it)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    r[it][j] = *reinterpret_cast<const u32x4*>(g + off[it] + (uint32_t)j * g_row_bytes);
+        } else {
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                const int item = it * kThreads + tid;
+                const int kq = item / CPR, ch = item % CPR;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t o = (uint32_t)min(4 * kq + j, valid_rows - 1) * g_row_bytes + (uint32_t)ch * 16u;
+                    r[it][j] = *reinterpret_cast<const u32x4*>(g + o);
+                }
             }
         }
     }

@@ -149,6 +149,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
 
     const char* kbase = a.kc + b * a.kc_s[0] + g * a.kc_s[1];
     RowTileRegs<Cfg::KROW> kregs;     // the loads of the next tile are in flight while this one is computed
+    kregs.init((uint32_t)a.kc_s[2], tid);
     kregs.issue(kbase + (int64_t)t0 * kTile * a.kc_s[2], (uint32_t)a.kc_s[2], min(kTile, sm.n_cmp - t0 * kTile), tid);
     for (int tile = t0; tile < t1; ++tile) {
         const int base = tile * kTile;

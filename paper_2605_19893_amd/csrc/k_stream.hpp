@@ -269,8 +269,23 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         vr.issue(vbase + (int64_t)base_n * vrow, (uint32_t)vrow, vr_n, tid);
     };
 #pragma unroll
-    for (int j = 0; j < AHEAD; ++j)
+    for (int j = 0; j < AHEAD; ++j) {
+        kregs[j].init((uint32_t)krow, tid);
+        vregs[j].init((uint32_t)vrow, tid);
         if (t0 + j < t1) issue_tile(t0 + j, kregs[j], vregs[j]);
+    }
+    // wave-wide bounds for the "every key of the tile is valid for every row" fast path (rows that do not
+    // exist are don't-cares: nothing of theirs is ever written)
+    int full_cmax = 0x7fffffff, full_lo = -0x7fffffff;
+#pragma unroll
+    for (int t = 0; t < NRT; ++t) {
+        if (rvalid[t]) { full_cmax = min(full_cmax, cmax[t]); full_lo = max(full_lo, pos[t] - a.w + 1); }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        full_cmax = min(full_cmax, __shfl_xor(full_cmax, off));
+        full_lo = max(full_lo, __shfl_xor(full_lo, off));
+    }
     SSV_PHASE_DECL
     // One tile; (kcur, vcur) hold tile `it` and, once committed to LDS, take tile it + AHEAD.
     auto tile_step = [&](const int it, RowTileRegs<Cfg::KROW>& kcur, TransposedTileRegs<BF16, DV>& vcur) {
@@ -302,8 +317,11 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         // ---- validity of this lane's 16 keys (4 key tiles x 4 registers) for each of its query rows;
         //      bit 4 kt + r <-> key base + 16 kt + 4 G + r
         uint32_t vm[NRT];
+        const bool tile_full = (r_cmp && base + kTile <= full_cmax) || (r_win && !has_drafts && base >= full_lo);   // uniform
 #pragma unroll
         for (int t = 0; t < NRT; ++t) {
+            vm[t] = 0xFFFFu;
+            if (tile_full) continue;
             vm[t] = 0;
             if (!rvalid[t]) continue;
             if (r_cmp) {
@@ -357,7 +375,18 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
 #pragma unroll
                     for (int t = 0; t < NRT; ++t) s[t][kt] = mma_frag<BF16>(kf, qf[t][kc], s[t][kt]);
                 }
-                if (kc & 1) __builtin_amdgcn_sched_barrier(0);   // bound the LDS reads in flight (register pressure)
+            }
+            if constexpr (BF16) {
+                // issue order: 8 fragment reads ahead, then one read per MFMA group, so that the LDS latency of
+                // every fragment is covered by the MFMAs of the fragments before it
+                constexpr int N_RD = 4 * KCH, LEAD = 8;
+                __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0);
+#pragma unroll
+                for (int i = 0; i < N_RD - LEAD; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, NRT, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, LEAD * NRT, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
             // ---- online softmax in the log2 domain (rows without a valid key keep their state: alpha = 1)
@@ -422,6 +451,16 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                         const u32x4 vf = lds_read16(sVT + (vt_rb ^ (16 * ((4 * u) ^ ((2 * mt) & 7)))) + mt * 16 * VP);
 #pragma unroll
                         for (int t = 0; t < NRT; ++t) acc[t][mt] = mma_frag<true>(vf, pb[t], acc[t][mt]);
+                    }
+                    {
+                        constexpr int LEAD = 4;
+                        __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0);
+#pragma unroll
+                        for (int i = 0; i < MT - LEAD; ++i) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, NRT, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        }
+                        __builtin_amdgcn_sched_group_barrier(0x008, LEAD * NRT, 0);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
