@@ -105,3 +105,51 @@ def nsa_verify(case, *, sel_idx: Optional[np.ndarray] = None, scale: float = 0.0
     if rc != 0:
         raise ValueError(f"oracle rejected its arguments (code {rc})")
     return OracleResult(out=out, sel_idx=sel, gap=gap, o_cmp=oc, o_slc=os_, o_win=ow, imp=imp, p_cmp=pc)
+
+
+def group_representatives(case, C: int) -> np.ndarray:
+    """Representative verifier query of every group of C consecutive queries (flattened order), [B, T] int32.
+
+    Approximate shared-index variant (Section 4.3): the representative is the member with the longest
+    prefix, i.e. the largest position L + depth; among equally deep members (a tree) the last one in
+    flattened order.  In a linear chain that is the last query of the group.  Entry [b, i] is the
+    representative of i's group, -1 for i >= n_query[b].
+    """
+    B, T = case.B, case.T
+    rep = np.full((B, T), -1, np.int32)
+    for b in range(B):
+        Tq = int(case.n_query[b])
+        depth = np.zeros(Tq, np.int64)
+        for i in range(Tq):
+            par = i - 1 if case.parents is None else int(case.parents[b, i])
+            depth[i] = 0 if par < 0 else depth[par] + 1
+        for g0 in range(0, Tq, C):
+            members = range(g0, min(g0 + C, Tq))
+            best = max(members, key=lambda i: (depth[i], i))
+            rep[b, g0:min(g0 + C, Tq)] = best
+    return rep
+
+
+def nsa_verify_shared(case, C: int, *, scale: float = 0.0, branches: bool = False, n_threads: int = 0) -> OracleResult:
+    """Approximate shared-index variant (Section 4.3), as its three steps: (1) one representative per group of
+    C queries; (2) the selected block set is computed for the representative alone (exact selection of
+    that query); (3) every query of the group attends to that set, under its own visibility, position and
+    window (the compressed and window branches are those of the exact variant).  sel_idx and gap of the
+    result hold the representative's set and boundary gap in every member's row.
+    """
+    rep = group_representatives(case, C)
+    B, T = case.B, case.T
+    mask = np.zeros((B, T), np.uint8)
+    for b in range(B):
+        for i in range(int(case.n_query[b])):
+            mask[b, rep[b, i]] = 1
+    routed = nsa_verify(case, scale=scale, query_mask=mask, n_threads=n_threads)
+    sel = np.full_like(routed.sel_idx, -1)
+    gap = np.full_like(routed.gap, np.inf)
+    for b in range(B):
+        for i in range(int(case.n_query[b])):
+            sel[b, i] = routed.sel_idx[b, rep[b, i]]
+            gap[b, i] = routed.gap[b, rep[b, i]]
+    res = nsa_verify(case, sel_idx=sel, scale=scale, branches=branches, n_threads=n_threads)
+    res.gap = gap
+    return res
