@@ -11,7 +11,8 @@
  * heads of a GQA group times C queries form the rows of the matrix tiles (Section 4.1).
  * SSV_REFRESH computes and writes the selected indices (routing launch followed by the
  * downstream launch, Section 5.1); SSV_REUSE reads them and skips index construction
- * (Section 5.2).
+ * (Section 5.2).  SSV_REFRESH_SHARED is the approximate shared-index variant (Section 4.3):
+ * one representative query per group of C routes for the whole group.
  *
  * Conventions
  *  - Every data pointer is DEVICE memory owned by the caller; `p`, return codes and
@@ -48,6 +49,7 @@ extern "C" {
 
 #define SSV_REFRESH 0
 #define SSV_REUSE   1
+#define SSV_REFRESH_SHARED 2  /* approximate: every group of C queries uses its representative's indices */
 
 #define SSV_MAX_T 64          /* verifier queries per sequence */
 
@@ -73,8 +75,9 @@ typedef struct ssv_nsa_params {
     int32_t n_init;       /* forced leading blocks */
     int32_t n_local;      /* forced blocks ending at the block of the query's own slot */
     int32_t dtype;        /* SSV_F32 or SSV_BF16: type of q, k, v, k_cmp, v_cmp, out */
-    int32_t mode;         /* SSV_REFRESH: sel_idx is written; SSV_REUSE: sel_idx is read */
-    int32_t group_size;   /* C: verifier queries per workgroup (C * H_g <= 128); 0 = auto (C * H_g <= 64) */
+    int32_t mode;         /* SSV_REFRESH, SSV_REFRESH_SHARED: sel_idx is written; SSV_REUSE: sel_idx is read */
+    int32_t group_size;   /* C: verifier queries per workgroup (C * H_g <= 128); 0 = auto (C * H_g <= 64).  Never changes
+                             the result of SSV_REFRESH / SSV_REUSE; defines the groups of SSV_REFRESH_SHARED */
     float   scale;        /* softmax scale; 0 => 1/sqrt(d_k) */
     int32_t max_seq_len;  /* host-side upper bound on seq_lens[b] (sizes grids and scratch) */
     int32_t max_n_cmp;    /* host-side upper bound on n_cmp[b] */
@@ -107,6 +110,12 @@ typedef struct ssv_nsa_plan {
  *   its slots are visible to i as a contiguous run from slot 0.
  *   sel_idx: written in SSV_REFRESH; read in SSV_REUSE, where negative, repeated or out-of-range
  *   entries are ignored.  Rows of queries i >= n_query[b]: out = 0, sel_idx = -1 (refresh).
+ *   SSV_REFRESH_SHARED (Section 4.3): queries [m*C, (m+1)*C) of a sequence (flattened order, C = plan.C) form
+ *   a group; its representative is the member with the largest position L + depth, the last such member if
+ *   several are equally deep (the last query of the group in a chain).  Block importance and top-n run for the
+ *   representative only; its index set is written to the sel_idx row of every member and every member's
+ *   selected branch attends to it under the member's own visibility.  Compressed and window branches are
+ *   those of SSV_REFRESH.  The result equals SSV_REUSE on the sel_idx it writes.
  *   workspace: >= ssv_nsa_workspace_bytes(p) bytes, 256-byte aligned; contents need not be preserved
  *   or initialised between calls; calls sharing a workspace must not overlap in time.
  * Returns SSV_OK or a negative SSV_E* code.

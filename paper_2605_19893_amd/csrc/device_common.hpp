@@ -253,4 +253,13 @@ __device__ __forceinline__ SeqMeta build_tree_meta(int tid, int b, int T, const 
     return sm;
 }
 
+// Representative of the verifier queries [m0, m1) of one sequence for the approximate shared-index variant
+// (Section 4.3): the member with the longest prefix, i.e. the deepest one, the last of equally deep members.
+__device__ __forceinline__ int group_representative(const int* s_depth, int m0, int m1) {
+    int best = m0;
+    for (int m = m0 + 1; m < m1; ++m)
+        if (s_depth[m] >= s_depth[best]) best = m;
+    return best;
+}
+
 }  // namespace ssv

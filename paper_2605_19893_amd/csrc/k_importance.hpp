@@ -5,6 +5,9 @@
 // rows (k_cmp only, no v_cmp), forms p = exp2(s - M) / Z with the merged statistics, adds the heads
 // of each query, and writes colsum[b, i, g, c] = sum_{h in g} p_h[c].
 //
+// The kernel works on a list of routed queries: every verifier query in the exact variant, only the
+// representative of each group of `share` queries in the approximate shared-index variant (Section 4.3).
+//
 // The tile product is taken in the orientation D[query row][key] (Q as the A operand): a lane then
 // holds four heads of one key, so the head sum is three in-register adds plus at most two
 // cross-lane exchanges.
@@ -18,7 +21,9 @@ struct ImportanceArgs {
     const int32_t *seq_lens, *n_cmp, *n_query, *parents;
     const float* part_stats;   // slots [0, n_cmp_chunks) hold the compressed-scan partial statistics
     float* colsum;             // [B, T, H_kv, nc_pitch]
-    int B, T, H, H_kv, H_g, C, n_qg;
+    int B, T, H, H_kv, H_g;
+    int C, n_qg;               // routed queries per workgroup; workgroups over the routed queries of a sequence
+    int share;                 // 0: every query is routed; > 0: one representative per group of `share` queries
     int l, d;
     float scale_log2;
     int n_cmp_chunks;          // slices of the compressed scan (partial statistics to merge)
@@ -36,8 +41,9 @@ struct ImportanceCfg {
     static constexpr int KP = KROW + 16;
     static constexpr int KCH = KROW / 64;
     static constexpr int LDS_K = kTile * KP;
-    // LDS bytes: K tile, merged row statistics, per-sequence tree metadata, then the head-summed tile [C][64]
-    static constexpr int lds_bytes(int C) { return LDS_K + 256 * 8 + kMaxT * 20 + 64 + C * kTile * 4; }
+    // LDS bytes: K tile, merged row statistics, per-sequence tree metadata and routed-query list, then the
+    // head-summed tile [C][64]
+    static constexpr int lds_bytes(int C) { return LDS_K + 256 * 8 + kMaxT * 24 + 64 + C * kTile * 4; }
 };
 
 template <bool BF16, int DK, int NRT>
@@ -51,7 +57,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     int* s_par = reinterpret_cast<int*>(s_anc + kMaxT);
     int* s_depth = s_par + kMaxT;
     int* s_cmax = s_depth + kMaxT;
-    float* s_cs = reinterpret_cast<float*>(s_cmax + kMaxT + 16);   // [C][64] head-summed probabilities
+    int* s_qi = s_cmax + kMaxT;                                    // verifier query behind every routed query of this workgroup
+    float* s_cs = reinterpret_cast<float*>(s_qi + kMaxT + 16);     // [C][64] head-summed probabilities
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, G = lane >> 4;
@@ -67,11 +74,21 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, s_par, s_depth, s_cmax,
                                        s_anc);
     const int L = sm.L, Tq = sm.Tq;
-    const int nq_grp = min(a.C, Tq - qg * a.C);
+    const int n_routed = a.share ? (Tq + a.share - 1) / a.share : Tq;
+    const int nq_grp = min(a.C, n_routed - qg * a.C);
     if (nq_grp <= 0) return;
+    if (tid < a.C) {
+        int qi = 0;
+        if (tid < nq_grp) {
+            const int r = qg * a.C + tid;
+            qi = a.share ? group_representative(s_depth, r * a.share, min((r + 1) * a.share, Tq)) : r;
+        }
+        s_qi[tid] = qi;
+    }
+    __syncthreads();
 
     int cm = 0;
-    for (int j = 0; j < nq_grp; ++j) cm = max(cm, s_cmax[qg * a.C + j]);
+    for (int j = 0; j < nq_grp; ++j) cm = max(cm, s_cmax[s_qi[j]]);
     const int ntiles = (cm + kTile - 1) / kTile;
     int t0, t1;
     even_slice(ntiles, a.n_imp_chunks, 1, chunk, t0, t1);
@@ -84,7 +101,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     {
         const int rr = tid & 127, half = tid >> 7;
         const bool ok = rr < rows_wg;
-        const int64_t grow = ((int64_t)b * a.T + qg * a.C + (ok ? rr / a.H_g : 0)) * a.H + g * a.H_g + rr % a.H_g;
+        const int64_t grow = ((int64_t)b * a.T + s_qi[ok ? rr / a.H_g : 0]) * a.H + g * a.H_g + rr % a.H_g;
         float M = -INFINITY, Z = 0.f;
         for (int s0 = half; s0 < a.n_cmp_chunks; s0 += 16) {
             float2 st[8];
@@ -122,7 +139,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
         const int rr = (wave + 4 * t) * 16 + n;
         const int j = rr / a.H_g;
         const bool ok = j < nq_grp;
-        const int64_t grow = ((int64_t)b * a.T + qg * a.C + (ok ? j : 0)) * a.H + g * a.H_g + rr % a.H_g;
+        const int64_t grow = ((int64_t)b * a.T + s_qi[ok ? j : 0]) * a.H + g * a.H_g + rr % a.H_g;
 #pragma unroll
         for (int kc = 0; kc < KCH; ++kc) {
             qf[t][kc] = u32x4{0, 0, 0, 0};
@@ -144,7 +161,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
             const float2 st = s_stat[ok ? rr : 0];
             rowM[t][r] = st.x;
             rowIZ[t][r] = ok ? st.y : 0.f;
-            rowC[t][r] = ok ? s_cmax[qg * a.C + j] : 0;
+            rowC[t][r] = ok ? s_cmax[s_qi[j]] : 0;
         }
 
     const char* kbase = a.kc + b * a.kc_s[0] + g * a.kc_s[1];
@@ -203,7 +220,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
         for (int i = tid; i < nq_grp * kTile; i += kThreads) {
             const int j = i / kTile, key = i % kTile;
             if (base + key < a.nc_pitch)
-                a.colsum[(((int64_t)b * a.T + qg * a.C + j) * a.H_kv + g) * a.nc_pitch + base + key] = s_cs[i];
+                a.colsum[(((int64_t)b * a.T + s_qi[j]) * a.H_kv + g) * a.nc_pitch + base + key] = s_cs[i];
         }
     }
 }

@@ -5,7 +5,8 @@
 //   candidates j = 0..J, J = block of the query's own slot; forced blocks are ranked first;
 //   the n_eff = min(n, J+1) best by (importance descending, index ascending) are written ascending.
 //
-// One workgroup per (b, i, g).  Keys are packed as (float bits << 32) | ~index so that a plain
+// One workgroup per (b, i, g); in the approximate shared-index variant (Section 4.3) one per (b, group, g):
+// it selects for the group's representative and writes the set to the row of every member.  Keys are packed as (float bits << 32) | ~index so that a plain
 // unsigned 64-bit comparison implements "larger importance, then smaller index"; importances are
 // sums of probabilities, hence non-negative, and their IEEE bit patterns order like the values.
 //
@@ -27,6 +28,7 @@ struct TopnArgs {
     int l, d, l_sel, n_sel, n_init, n_local;
     int nc_pitch;
     int max_blocks;          // capacity of the key array in LDS
+    int share;               // 0: every query selects for itself; > 0: groups of `share` queries share a set
 };
 
 constexpr int kMaxNSel = 32;
@@ -62,15 +64,22 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.x % a.H_kv;
-    const int i = (blockIdx.x / a.H_kv) % a.T;
+    const int x = (blockIdx.x / a.H_kv) % a.T;
     const int b = blockIdx.x / (a.H_kv * a.T);
-    int32_t* out = a.sel_idx + (((int64_t)b * a.T + i) * a.H_kv + g) * a.n_sel;
 
     const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, s_par, s_depth, s_cmax,
                                        s_anc);
-    if (i >= sm.Tq) {
-        if (tid < a.n_sel) out[tid] = -1;
+    if (x >= sm.Tq) {
+        if (tid < a.n_sel) a.sel_idx[(((int64_t)b * a.T + x) * a.H_kv + g) * a.n_sel + tid] = -1;
         return;
+    }
+    // rows [m0, m1) receive the set selected for query i
+    int i = x, m0 = x, m1 = x + 1;
+    if (a.share) {
+        m0 = x * a.share;
+        if (m0 >= sm.Tq) return;
+        m1 = min(m0 + a.share, sm.Tq);
+        i = group_representative(s_depth, m0, m1);
     }
     const int ncv = min(s_cmax[i], a.nc_pitch);
     const int J = min((sm.L + i) / a.l_sel, a.max_blocks - 1);
@@ -188,17 +197,18 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     __syncthreads();
     // ascending order: pick e goes to position (number of smaller picks); picks are distinct
     if (tid < a.n_sel) {
-        int x = 0x7fffffff, rank = tid;      // threads beyond n_eff write the -1 padding at their own position
+        int pick = 0x7fffffff, rank = tid;   // threads beyond n_eff write the -1 padding at their own position
         if (tid < n_eff) {
-            x = s_pick[tid];
+            pick = s_pick[tid];
             rank = 0;
             int p[kMaxNSel];
 #pragma unroll
             for (int f = 0; f < kMaxNSel; ++f) p[f] = s_pick[f < n_eff ? f : 0];
 #pragma unroll
-            for (int f = 0; f < kMaxNSel; ++f) rank += (f < n_eff && p[f] < x) ? 1 : 0;
+            for (int f = 0; f < kMaxNSel; ++f) rank += (f < n_eff && p[f] < pick) ? 1 : 0;
         }
-        out[rank] = tid < n_eff ? x : -1;
+        for (int m = m0; m < m1; ++m)
+            a.sel_idx[(((int64_t)b * a.T + m) * a.H_kv + g) * a.n_sel + rank] = tid < n_eff ? pick : -1;
     }
 }
 

@@ -31,7 +31,8 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
     ssv_nsa_plan plan;
-    int H_g, nrt, es, n_imp_chunks;
+    int H_g, nrt, es;
+    int imp_C, imp_n_qg, n_imp_chunks;   // importance pass: routed queries per workgroup, such workgroups per sequence, slices
     int nc_pitch, max_blocks, bitmap_words;
     int64_t rows_total;
     size_t off_stats, off_acc, off_colsum, total;
@@ -45,7 +46,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     if (p->n_sel < 1 || p->n_init < 0 || p->n_local < 0 || p->n_sel < p->n_init + p->n_local) return SSV_EINVAL;
     if (p->w < 1 || p->max_seq_len < 0 || p->max_n_cmp < 0 || p->avg_seq_len < 0 || p->avg_seq_len > p->max_seq_len) return SSV_EINVAL;
     if (p->dtype != SSV_F32 && p->dtype != SSV_BF16) return SSV_EINVAL;
-    if (p->mode != SSV_REFRESH && p->mode != SSV_REUSE) return SSV_EINVAL;
+    if (p->mode != SSV_REFRESH && p->mode != SSV_REUSE && p->mode != SSV_REFRESH_SHARED) return SSV_EINVAL;
     if (p->group_size < 0 || !(p->scale >= 0.f) || std::isinf(p->scale)) return SSV_EINVAL;
     const int H_g = p->H / p->H_kv;
     if (p->T > SSV_MAX_T) return SSV_EUNSUPPORTED;
@@ -85,7 +86,8 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     const int ntc_avg = std::max(1, (int)std::ceil(ntc * avg_frac));
     const int ntw = (p->w + p->T) / kTile + 2;                          // window tiles
     pl.max_sched_entries = pl.C * p->n_sel;
-    const int nts = pl.max_sched_entries;                               // selected tiles, at most
+    // selected tiles, at most; with one shared index set per group the schedule is a single set
+    const int nts = p->mode == SSV_REFRESH_SHARED ? p->n_sel : pl.max_sched_entries;
     pl.min_tiles_per_split = env_int("SSV_MIN_TILES", 2);
     const int mt = pl.min_tiles_per_split;
     // Tiles per slice.  If one round of resident workgroups can take the launch with slices of at most 24
@@ -126,8 +128,19 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
 
     lo->H_g = H_g;
     lo->nrt = nrt;
-    // importance pass: 4 workgroups per CU are resident (120 VGPRs, about 30 KB LDS): one round of at most 1024
-    lo->n_imp_chunks = std::max(1, std::min(ceil_div(ntc, env_int("SSV_IMP_MIN_TILES", 1)), std::max(1, 1024 / units)));
+    // importance pass: every query is routed, or one representative per group of C (shared-index variant), then
+    // packed 64 rows to a workgroup; 4 workgroups per CU are resident (120 VGPRs, about 30 KB LDS): one round of
+    // at most 1024
+    if (p->mode == SSV_REFRESH_SHARED) {
+        const int routed = ceil_div(p->T, pl.C);
+        lo->imp_C = std::max(1, std::min(routed, 64 / H_g));
+        lo->imp_n_qg = ceil_div(routed, lo->imp_C);
+    } else {
+        lo->imp_C = pl.C;
+        lo->imp_n_qg = pl.n_qg;
+    }
+    const int imp_units = p->B * p->H_kv * lo->imp_n_qg;
+    lo->n_imp_chunks = std::max(1, std::min(ceil_div(ntc, env_int("SSV_IMP_MIN_TILES", 1)), std::max(1, 1024 / imp_units)));
     lo->es = es;
     lo->nc_pitch = (int)align_up((size_t)std::max(1, p->max_n_cmp), kTile);
     lo->max_blocks = max_blocks;
@@ -238,15 +251,16 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         ImportanceArgs ia{};
         ia.q = sa.q; ia.kc = sa.kc; ia.seq_lens = seq_lens; ia.n_cmp = n_cmp; ia.n_query = n_query; ia.parents = parents;
         ia.part_stats = part_stats; ia.colsum = colsum;
-        ia.B = p->B; ia.T = p->T; ia.H = p->H; ia.H_kv = p->H_kv; ia.H_g = lo.H_g; ia.C = pl.C; ia.n_qg = pl.n_qg;
+        ia.B = p->B; ia.T = p->T; ia.H = p->H; ia.H_kv = p->H_kv; ia.H_g = lo.H_g; ia.C = lo.imp_C; ia.n_qg = lo.imp_n_qg;
+        ia.share = p->mode == SSV_REFRESH_SHARED ? pl.C : 0;
         ia.l = p->l; ia.d = p->d; ia.scale_log2 = scale_log2; ia.n_cmp_chunks = pl.n_cmp_chunks; ia.n_imp_chunks = lo.n_imp_chunks;
-        ia.n_wg = units * lo.n_imp_chunks; ia.nc_pitch = lo.nc_pitch; ia.rows_total = lo.rows_total;
+        ia.n_wg = p->B * p->H_kv * lo.imp_n_qg * lo.n_imp_chunks; ia.nc_pitch = lo.nc_pitch; ia.rows_total = lo.rows_total;
         for (int j = 0; j < 3; ++j) ia.kc_s[j] = sa.kc_s[j];
         const int grid_i = ceil_div(ia.n_wg, 8) * 8;
         if (tm.begin(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
         for (int r = 0; r < reps; ++r) {
-            if (lo.nrt == 2) hipLaunchKernelGGL((k_importance<BF16, DK, 2>), dim3(grid_i), dim3(kThreads), IC::lds_bytes(pl.C), stream, ia);
-            else hipLaunchKernelGGL((k_importance<BF16, DK, 1>), dim3(grid_i), dim3(kThreads), IC::lds_bytes(pl.C), stream, ia);
+            if (ia.C * lo.H_g > 64) hipLaunchKernelGGL((k_importance<BF16, DK, 2>), dim3(grid_i), dim3(kThreads), IC::lds_bytes(ia.C), stream, ia);
+            else hipLaunchKernelGGL((k_importance<BF16, DK, 1>), dim3(grid_i), dim3(kThreads), IC::lds_bytes(ia.C), stream, ia);
         }
         if (hipGetLastError() != hipSuccess || tm.end(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
 
@@ -254,7 +268,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         ta.colsum = colsum; ta.seq_lens = seq_lens; ta.n_cmp = n_cmp; ta.n_query = n_query; ta.parents = parents;
         ta.sel_idx = sel_idx; ta.B = p->B; ta.T = p->T; ta.H_kv = p->H_kv;
         ta.l = p->l; ta.d = p->d; ta.l_sel = p->l_sel; ta.n_sel = p->n_sel; ta.n_init = p->n_init; ta.n_local = p->n_local;
-        ta.nc_pitch = lo.nc_pitch; ta.max_blocks = lo.max_blocks;
+        ta.nc_pitch = lo.nc_pitch; ta.max_blocks = lo.max_blocks; ta.share = ia.share;
         const size_t lds_topn = topn_lds_bytes(lo.max_blocks);
         if (lds_topn > 64 * 1024 &&
             hipFuncSetAttribute((const void*)k_topn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_topn) != hipSuccess)

@@ -49,7 +49,7 @@ class DeviceCase:
             kc_stride=self.k_cmp.stride()[:3], vc_stride=self.v_cmp.stride()[:3])
         # the split plan (and with it the scratch size) depends on the mode: size the workspace for both
         need = 0
-        for m in (B.SSV_REFRESH, B.SSV_REUSE):
+        for m in (B.SSV_REFRESH, B.SSV_REUSE, B.SSV_REFRESH_SHARED):
             self.params.mode = m
             need = max(need, B.ssv_nsa_workspace_bytes(self.params))
         self.workspace_bytes = need

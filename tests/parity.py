@@ -31,8 +31,9 @@ class ParityReport:
                 f"max_abs_err={self.max_abs_err:.3e}")
 
 
-def compare(case, oracle_mod, ref, gpu_out: np.ndarray, gpu_sel: np.ndarray, reuse_sel=None) -> ParityReport:
-    """ref: oracle result in the same mode; reuse_sel: indices given to both sides in reuse mode."""
+def compare(case, oracle_mod, ref, gpu_out: np.ndarray, gpu_sel: np.ndarray, reuse_sel=None, routed_by=None) -> ParityReport:
+    """ref: oracle result in the same mode; reuse_sel: indices given to both sides in reuse mode;
+    routed_by [B, T]: in the shared-index variant, the query whose selection each row holds."""
     B, T, H_kv = case.B, case.T, case.H_kv
     active = np.arange(T)[None, :] < case.n_query[:, None]
     n_units = int(active.sum()) * H_kv
@@ -53,7 +54,7 @@ def compare(case, oracle_mod, ref, gpu_out: np.ndarray, gpu_sel: np.ndarray, reu
             row = gpu_sel[b, i, g]
             chosen = row[row >= 0]
             assert np.all(np.diff(chosen) > 0) and np.all(row[len(chosen):] == -1), (b, i, g, row)
-            J = (int(case.seq_lens[b]) + i) // case.nsa.l_sel
+            J = (int(case.seq_lens[b]) + (i if routed_by is None else int(routed_by[b, i]))) // case.nsa.l_sel
             assert len(chosen) == min(case.nsa.n_sel, J + 1) and chosen.max() <= J, (b, i, g, row)
             forced = {j for j in range(case.nsa.n_init) if j <= J} | \
                      {j for j in range(J - case.nsa.n_local + 1, J + 1) if j >= 0}

@@ -45,6 +45,24 @@ def run_reuse(dev_mod, oracle, case, sel, group_size=0, dev=None):
     return out
 
 
+def run_shared(dev_mod, oracle, case, C):
+    """Approximate shared-index variant with groups of C queries, then reuse of the indices it wrote."""
+    from paper_2605_19893_amd import SSV_REFRESH_SHARED
+    ref = oracle.nsa_verify_shared(case, C)
+    rep = oracle.group_representatives(case, C)
+    dev = dev_mod.DeviceCase(case, mode=SSV_REFRESH_SHARED, group_size=C)
+    assert dev.plan.C == C
+    print(f"[run] {case.name} shared-index C={C} plan={dev.plan.as_dict()}", flush=True)
+    dev.run()
+    out, sel = dev.results()
+    check(case, compare(case, oracle, ref, out, sel, routed_by=rep))
+    for b in range(case.B):
+        for i in range(int(case.n_query[b])):
+            assert np.array_equal(sel[b, i], sel[b, rep[b, i]]), (b, i)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+    return out, sel
+
+
 def test_config0_fp32(dev_mod, oracle):
     case = si.config0()
     dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
@@ -159,3 +177,29 @@ def test_runs_are_bitwise_reproducible(dev_mod, oracle):
     dev.run()
     out2, sel2 = dev.results()
     assert np.array_equal(out1, out2) and np.array_equal(sel1, sel2)
+
+
+@pytest.mark.parametrize("C", [1, 2, 4])
+def test_shared_index_variant_chain(dev_mod, oracle, C):
+    """Section 4.3: the last query of every run of C routes for the run; T = 7 leaves a short last group."""
+    case = si.make_case("shared_chain", "bf16", 2, 7, 32, 2, 192, 128, si.STD_NSA, [3001, 2040], 123, rho=0.3,
+                        poison_pad=True)
+    out, sel = run_shared(dev_mod, oracle, case, C)
+    if C == 1:
+        dev, ref, out_exact, sel_exact = run_refresh(dev_mod, oracle, case, group_size=1)
+        assert np.array_equal(sel, sel_exact) and np.array_equal(out, out_exact)
+
+
+@pytest.mark.parametrize("order", ["bfs", "dfs"])
+def test_shared_index_variant_tree_and_ragged(dev_mod, oracle, order):
+    par = si.tree_parents((3, 2, 2), order)
+    case = si.make_case(f"shared_tree_{order}", "bf16", 3, len(par), 16, 1, 192, 128, si.STD_NSA, [2048, 1500, 777],
+                        125, rho=0.6, parents=par, n_query=[len(par), 9, 1])
+    run_shared(dev_mod, oracle, case, 4)
+
+
+def test_shared_index_variant_small_heads_many_groups(dev_mod, oracle):
+    """H_g = 4, T = 33, C = 2: 17 representatives packed 16 to a routing workgroup; fp32 at head dim 64."""
+    case = si.make_case("shared_hg4", "f32", 1, 33, 8, 2, 64, 64, si.NsaParams(l=32, d=16, l_sel=64, n_sel=6, w=100),
+                        [1990], 127, rho=0.4)
+    run_shared(dev_mod, oracle, case, 2)
