@@ -188,6 +188,45 @@ def measure_workload(torch, oracle, case, name, tag, steps, warmup, n_copies, pa
     return res, ref
 
 
+def shared_index_study(torch, oracle, si, T, rhos, C, steps, warmup, n_copies=8):
+    """Approximate shared-index variant (Section 4.3) against the exact merged schedule on the cfg1 shape with
+    groups of C queries: time per call, bytes of selected blocks loaded, and how far the outputs move (fp64
+    oracle of each variant), as a function of the cross-query correlation rho."""
+    from paper_2605_19893_amd import binding as B
+    from paper_2605_19893_amd.device_case import DeviceCase
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import compare
+    rows = []
+    for rho in rhos:
+        case = si.config1(rho, T=T)
+        exact, shared = oracle.nsa_verify(case), oracle.nsa_verify_shared(case, C)
+        routed_by = oracle.group_representatives(case, C)
+        dev_out = np.abs(shared.out - exact.out)
+        row = {"rho": rho, "T": T, "C": C,
+               "output_deviation_max_abs": float(dev_out.max()),
+               "output_deviation_rms": float(np.sqrt((dev_out ** 2).mean())),
+               "output_rms": float(np.sqrt((exact.out ** 2).mean())),
+               "index_sets_changed": int(np.any(np.sort(shared.sel_idx, -1) != np.sort(exact.sel_idx, -1), axis=-1).sum()),
+               "index_sets": int(case.n_query.sum()) * case.H_kv}
+        for mode, mname, ref in ((B.SSV_REFRESH, "exact", exact), (B.SSV_REFRESH_SHARED, "shared", shared)):
+            devs = [DeviceCase(case, mode=mode, group_size=C) for _ in range(n_copies)]
+            devs[0].run()
+            out, sel = devs[0].results()
+            rep = compare(case, oracle, ref, out, sel, routed_by=routed_by if mode == B.SSV_REFRESH_SHARED else None)
+            cold_ms, _ = time_calls(torch, devs, steps, warmup)
+            kms = kernel_breakdown(devs[:1], 2, 20)
+            ab = algorithmic_bytes(case, ref.sel_idx, C)
+            row[mname] = {"us_per_call_cold": cold_ms * 1e3, "selected_union_bytes": ab["selected_union"],
+                          "algorithmic_bytes_total": ab["total"],
+                          "parity_max_abs_err": rep.max_abs_err, "idx_mismatch_outside_ambiguity": rep.n_mismatch_strict,
+                          "kernel_us_20_back_to_back_launches": {B.kernel_name(i): float(kms[i] * 1e3)
+                                                                  for i in range(B.SSV_NUM_KERNELS) if kms[i] > 0}}
+            del devs
+            torch.cuda.empty_cache()
+        rows.append(row)
+    return rows
+
+
 def cpu_baseline(oracle, case, budget_s=8.0):
     """The oracle as it stands, timed on this machine's host cores on the same workload."""
     threads = oracle.default_threads()
@@ -213,7 +252,8 @@ def main():
     ap.add_argument("--rho", type=float, default=0.5)
     ap.add_argument("--no-extra", action="store_true", help="skip the configuration-2 measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", default="", help="measure only this workload (cfg1, cfg2, cfg3 or cfg4); for profiling runs")
+    ap.add_argument("--only", default="", help="measure only this workload (cfg1, cfg2, cfg3 or cfg4; for profiling runs), "
+                    "or 'shared': the shared-index study alone, at T = 8 and T = 32")
     ap.add_argument("--group-size", type=int, default=0, help="verifier queries per workgroup (0 = library default)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (a known-size reference for HBM byte counters)")
@@ -261,6 +301,13 @@ def main():
             main_res = r2
         else:
             others.append(r2)
+    shared_rows = None
+    if args.only in ("", "shared"):
+        shared_rows = shared_index_study(torch, oracle, si, 8, (0.0, 0.5, 0.9), 4, max(50, args.steps // 3), args.warmup)
+        if args.only == "shared":
+            shared_rows += shared_index_study(torch, oracle, si, 32, (0.0, 0.5, 0.9), 4, max(50, args.steps // 3), args.warmup)
+            print(json.dumps({"approx_shared_index_variant": shared_rows}))
+            return
     base = None
     if not args.no_cpu_baseline and args.only in ("", "cfg1"):
         base = cpu_baseline(oracle, case1)
@@ -282,6 +329,7 @@ def main():
         "parity": main_res.get("parity"),
         "modes": main_res["modes"],
         "other_workloads": others,
+        "approx_shared_index_variant": shared_rows,
     }
     print(json.dumps(line))
 

@@ -72,3 +72,17 @@ def test_config4_mixed_lengths_two_steps(dev_mod, oracle):
     dev.run()
     out, _ = dev.results()
     check(step2, compare(step2, oracle, ref, out, sel1, reuse_sel=sel1))
+
+
+@pytest.mark.parametrize("make,C", [(lambda: si.config1(0.5), 4), (lambda: si.config3("dfs"), 4), (lambda: si.config2(), 2)])
+def test_shared_index_variant_full_size(dev_mod, oracle, make, C):
+    """Approximate shared-index variant (Section 4.3; C = 4 in the paper) at benchmark sizes."""
+    from paper_2605_19893_amd import SSV_REFRESH_SHARED
+    case = make()
+    ref = oracle.nsa_verify_shared(case, C)
+    routed_by = oracle.group_representatives(case, C)
+    dev = dev_mod.DeviceCase(case, mode=SSV_REFRESH_SHARED, group_size=C)
+    print(f"[run] {case.name} shared-index C={C} plan={dev.plan.as_dict()}", flush=True)
+    dev.run()
+    out, sel = dev.results()
+    check(case, compare(case, oracle, ref, out, sel, routed_by=routed_by))
