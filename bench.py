@@ -227,6 +227,92 @@ def shared_index_study(torch, oracle, si, T, rhos, C, steps, warmup, n_copies=8)
     return rows
 
 
+def mean_adjacent_overlap(sel, n_query):
+    """Mean of |I_i and I_(i-1)| over consecutive chain queries and KV groups (the paper's overlap s, Section 7.3)."""
+    tot = cnt = 0
+    for b in range(sel.shape[0]):
+        for i in range(1, int(n_query[b])):
+            for g in range(sel.shape[2]):
+                a, c = sel[b, i, g], sel[b, i - 1, g]
+                tot += len(set(a[a >= 0].tolist()) & set(c[c >= 0].tolist()))
+                cnt += 1
+    return tot / max(cnt, 1)
+
+
+def kernel_workload_study(torch, oracle, si, steps, warmup, contexts=(8192, 16384, 32768, 65536), gammas=(4, 64),
+                          overlaps=(3, 6, 10)):
+    """The paper's isolated-kernel workload (Section 7 setup and Section 7.3): batch 1, 32 query heads / 8 KV heads,
+    head dimension 64, bf16, standard NSA parameters, draft length gamma in {4, 64} (a linear chain), context
+    N in {8K..64K}.  The adjacent-query overlap s is steered through the correlation rho of the synthetic
+    queries (rho = 0 for the lower bound s ~ 3; bisection on the oracle's indices for s ~ 6 and 10), so that
+    refresh and reuse calls see the same, data-driven index sets.  Variants: per-query execution (C = 1), the
+    paper's exact variant (C = 2), this build's default grouping (64 rows: C = min(gamma, 16)), and the
+    approximate shared-index variant (C = 4), each with index construction (refresh) and without (reuse)."""
+    from paper_2605_19893_amd import binding as B
+    from paper_2605_19893_amd.device_case import DeviceCase
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import compare
+    rows = []
+    for N in contexts:
+        for gamma in gammas:
+            case = si.make_case(f"kernel_workload_N{N}_g{gamma}", "bf16", 1, gamma, 32, 8, 64, 64, si.STD_NSA, [N],
+                                si.config_seed(5), rho=0.0)
+            kv_bytes = case.k.nbytes + case.v.nbytes + case.k_cmp.nbytes + case.v_cmp.nbytes
+            n_copies = int(min(32, max(2, -(-600_000_000 // kv_bytes))))
+            devs = [DeviceCase(case) for _ in range(n_copies)]
+            for target in overlaps:
+                lo, hi, rho = 0.0, 1.0, 0.0
+                if target > 3:
+                    for _ in range(9):      # overlap grows with rho
+                        rho = 0.5 * (lo + hi)
+                        si._fill_queries(case, case.seed, rho)
+                        if mean_adjacent_overlap(oracle.nsa_verify(case).sel_idx, case.n_query) < target:
+                            lo = rho
+                        else:
+                            hi = rho
+                si._fill_queries(case, case.seed, rho)
+                exact = oracle.nsa_verify(case)
+                shared = oracle.nsa_verify_shared(case, 4)
+                routed_by = oracle.group_representatives(case, 4)
+                for d in devs:
+                    d.set_queries(case.q)
+                row = {"N": N, "gamma": gamma, "target_overlap": target, "rho": rho,
+                       "mean_adjacent_overlap": mean_adjacent_overlap(exact.sel_idx, case.n_query), "input_copies": n_copies}
+                variants = (("per_query", B.SSV_REFRESH, 1, exact), ("exact_C2", B.SSV_REFRESH, 2, exact),
+                            ("exact_default_C", B.SSV_REFRESH, 0, exact), ("shared_C4", B.SSV_REFRESH_SHARED, 4, shared))
+                worst = 0.0
+                for vname, mode, C, ref in variants:
+                    for d in devs:
+                        d.set_group_size(C, mode)
+                    devs[0].run()
+                    out, sel = devs[0].results()
+                    rep = compare(case, oracle, ref, out, sel, routed_by=routed_by if mode == B.SSV_REFRESH_SHARED else None)
+                    assert rep.n_mismatch_strict == 0, (vname, rep.line())
+                    worst = max(worst, rep.max_abs_err)
+                    t_refresh, _ = time_calls(torch, devs, steps, warmup)
+                    for d in devs:
+                        d.set_mode(B.SSV_REUSE)
+                        d.set_sel_idx(ref.sel_idx)
+                    devs[0].run()
+                    out2, _ = devs[0].results()
+                    worst = max(worst, float(np.abs(out2 - ref.out).max()))
+                    t_reuse, _ = time_calls(torch, devs, steps, warmup)
+                    row[vname] = {"C": int(devs[0].plan.C), "refresh_us": t_refresh * 1e3, "reuse_us": t_reuse * 1e3}
+                base = row["per_query"]["refresh_us"]
+                row["speedup_over_per_query_refresh"] = {f"{v}_{m}": base / row[v][f"{m}_us"]
+                                                         for v in ("per_query", "exact_C2", "exact_default_C", "shared_C4")
+                                                         for m in ("refresh", "reuse")}
+                row["index_construction_share_of_refresh"] = 1.0 - row["exact_default_C"]["reuse_us"] / row["exact_default_C"]["refresh_us"]
+                row["parity_max_abs_err"] = worst
+                rows.append(row)
+                print(f"[kernel workload] N={N} gamma={gamma} s~{row['mean_adjacent_overlap']:.1f}: " +
+                      " ".join(f"{v}={row[v]['refresh_us']:.0f}/{row[v]['reuse_us']:.0f}us" for v, *_ in variants),
+                      file=sys.stderr, flush=True)
+            del devs
+            torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(oracle, case, budget_s=8.0):
     """The oracle as it stands, timed on this machine's host cores on the same workload."""
     threads = oracle.default_threads()
@@ -253,7 +339,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the configuration-2 measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default="", help="measure only this workload (cfg1, cfg2, cfg3 or cfg4; for profiling runs), "
-                    "or 'shared': the shared-index study alone, at T = 8 and T = 32")
+                    "'shared': the shared-index study alone, at T = 8 and T = 32, or 'kernel-workload': the paper's "
+                    "isolated-kernel workload (32/8 heads of dimension 64, draft lengths 4 and 64, contexts 8K-64K)")
     ap.add_argument("--group-size", type=int, default=0, help="verifier queries per workgroup (0 = library default)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (a known-size reference for HBM byte counters)")
@@ -301,6 +388,10 @@ def main():
             main_res = r2
         else:
             others.append(r2)
+    if args.only == "kernel-workload":
+        rows = kernel_workload_study(torch, oracle, si, max(50, args.steps // 3), max(5, args.warmup // 3))
+        print(json.dumps({"paper_kernel_workload": rows}))
+        return
     shared_rows = None
     if args.only in ("", "shared"):
         shared_rows = shared_index_study(torch, oracle, si, 8, (0.0, 0.5, 0.9), 4, max(50, args.steps // 3), args.warmup)

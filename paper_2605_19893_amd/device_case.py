@@ -47,18 +47,31 @@ class DeviceCase:
             avg_seq_len=int(case.seq_lens.mean()),
             k_stride=self.k.stride()[:3], v_stride=self.v.stride()[:3],
             kc_stride=self.k_cmp.stride()[:3], vc_stride=self.v_cmp.stride()[:3])
-        # the split plan (and with it the scratch size) depends on the mode: size the workspace for both
+        self.workspace_bytes = 0
+        self.workspace = None
+        self.set_group_size(group_size, mode)
+
+    def set_group_size(self, group_size: int, mode=None) -> None:
+        """Change C (verifier queries per workgroup); the workspace grows if the new plan needs more."""
+        self.params.group_size = group_size
+        mode = self.params.mode if mode is None else mode
+        # the split plan (and with it the scratch size) depends on the mode: size the workspace for all of them
         need = 0
         for m in (B.SSV_REFRESH, B.SSV_REUSE, B.SSV_REFRESH_SHARED):
             self.params.mode = m
             need = max(need, B.ssv_nsa_workspace_bytes(self.params))
-        self.workspace_bytes = need
-        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=self.device)
+        if need > self.workspace_bytes:
+            self.workspace_bytes = need
+            self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
         self.set_mode(mode)
 
     def set_mode(self, mode: int) -> None:
         self.params.mode = mode
         self.plan = B.ssv_nsa_plan_query(self.params)
+
+    def set_queries(self, q: np.ndarray) -> None:
+        """Replace the verifier queries (same shape), keeping the caches."""
+        self.q.copy_(_to_device(q, self.case.dtype, self.device))
 
     def set_sel_idx(self, sel: np.ndarray) -> None:
         self.sel_idx.copy_(torch.from_numpy(np.ascontiguousarray(sel, np.int32)).to(self.device))

@@ -203,3 +203,26 @@ def test_shared_index_variant_small_heads_many_groups(dev_mod, oracle):
     case = si.make_case("shared_hg4", "f32", 1, 33, 8, 2, 64, 64, si.NsaParams(l=32, d=16, l_sel=64, n_sel=6, w=100),
                         [1990], 127, rho=0.4)
     run_shared(dev_mod, oracle, case, 2)
+
+
+@pytest.mark.parametrize("gamma,C", [(64, 1), (64, 2), (64, 0), (4, 1), (4, 2)])
+def test_paper_kernel_workload_shape(dev_mod, oracle, gamma, C):
+    """32 query heads / 8 KV heads of dimension 64 and draft lengths 4 and 64 (the paper's isolated-kernel
+    setting, Section 7): per-query execution (C = 1), the paper's exact variant (C = 2), default grouping."""
+    case = si.make_case(f"kw_g{gamma}", "bf16", 1, gamma, 32, 8, 64, 64, si.STD_NSA, [8192 + 37], 129, rho=0.6)
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case, group_size=C)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+
+
+def test_group_size_can_change_on_a_live_case(dev_mod, oracle):
+    case = si.make_case("regroup", "bf16", 1, 12, 32, 8, 64, 64, si.STD_NSA, [4000], 131, rho=0.5)
+    ref = oracle.nsa_verify(case)
+    dev = dev_mod.DeviceCase(case, group_size=1)
+    outs = []
+    for C in (1, 3, 0, 12):
+        dev.set_group_size(C)
+        dev.run()
+        out, sel = dev.results()
+        check(case, compare(case, oracle, ref, out, sel))
+        outs.append(sel)
+    assert all(np.array_equal(outs[0], s) for s in outs[1:])
