@@ -290,14 +290,14 @@ def kernel_workload_study(torch, oracle, si, steps, warmup, contexts=(8192, 1638
                     assert rep.n_mismatch_strict == 0, (vname, rep.line())
                     worst = max(worst, rep.max_abs_err)
                     t_refresh, _ = time_calls(torch, devs, steps, warmup)
-                    for d in devs:
-                        d.set_mode(B.SSV_REUSE)
+                    for d in devs:      # indices are an input now: the shared sets need no particular grouping
+                        d.set_group_size(0 if mode == B.SSV_REFRESH_SHARED else C, B.SSV_REUSE)
                         d.set_sel_idx(ref.sel_idx)
                     devs[0].run()
                     out2, _ = devs[0].results()
                     worst = max(worst, float(np.abs(out2 - ref.out).max()))
                     t_reuse, _ = time_calls(torch, devs, steps, warmup)
-                    row[vname] = {"C": int(devs[0].plan.C), "refresh_us": t_refresh * 1e3, "reuse_us": t_reuse * 1e3}
+                    row[vname] = {"C": int(devs[0].plan.C), "share_group": C if mode == B.SSV_REFRESH_SHARED else 0, "refresh_us": t_refresh * 1e3, "reuse_us": t_reuse * 1e3}
                 base = row["per_query"]["refresh_us"]
                 row["speedup_over_per_query_refresh"] = {f"{v}_{m}": base / row[v][f"{m}_us"]
                                                          for v in ("per_query", "exact_C2", "exact_default_C", "shared_C4")

@@ -76,8 +76,9 @@ typedef struct ssv_nsa_params {
     int32_t n_local;      /* forced blocks ending at the block of the query's own slot */
     int32_t dtype;        /* SSV_F32 or SSV_BF16: type of q, k, v, k_cmp, v_cmp, out */
     int32_t mode;         /* SSV_REFRESH, SSV_REFRESH_SHARED: sel_idx is written; SSV_REUSE: sel_idx is read */
-    int32_t group_size;   /* C: verifier queries per workgroup (C * H_g <= 128); 0 = auto (C * H_g <= 64).  Never changes
-                             the result of SSV_REFRESH / SSV_REUSE; defines the groups of SSV_REFRESH_SHARED */
+    int32_t group_size;   /* SSV_REFRESH, SSV_REUSE: C, verifier queries per workgroup (C * H_g <= 128); 0 = auto
+                             (C * H_g <= 64); never changes the result.  SSV_REFRESH_SHARED: queries per index-sharing
+                             group (1..T; 0 = the automatic C); the workgroup grouping is then the automatic one */
     float   scale;        /* softmax scale; 0 => 1/sqrt(d_k) */
     int32_t max_seq_len;  /* host-side upper bound on seq_lens[b] (sizes grids and scratch) */
     int32_t max_n_cmp;    /* host-side upper bound on n_cmp[b] */
@@ -97,6 +98,7 @@ typedef struct ssv_nsa_plan {
     int32_t min_tiles_per_split;
     int32_t n_slots;          /* partial softmax states per output row = sum of the three above */
     int32_t max_sched_entries;/* capacity of the merged schedule of one group */
+    int32_t share_group;      /* SSV_REFRESH_SHARED: queries per index-sharing group; 0 in the other modes */
     int64_t workspace_bytes;
 } ssv_nsa_plan;
 
@@ -110,8 +112,8 @@ typedef struct ssv_nsa_plan {
  *   its slots are visible to i as a contiguous run from slot 0.
  *   sel_idx: written in SSV_REFRESH; read in SSV_REUSE, where negative, repeated or out-of-range
  *   entries are ignored.  Rows of queries i >= n_query[b]: out = 0, sel_idx = -1 (refresh).
- *   SSV_REFRESH_SHARED (Section 4.3): queries [m*C, (m+1)*C) of a sequence (flattened order, C = plan.C) form
- *   a group; its representative is the member with the largest position L + depth, the last such member if
+ *   SSV_REFRESH_SHARED (Section 4.3): queries [m*G, (m+1)*G) of a sequence (flattened order, G = plan.share_group)
+ *   form a group; its representative is the member with the largest position L + depth, the last such member if
  *   several are equally deep (the last query of the group in a chain).  Block importance and top-n run for the
  *   representative only; its index set is written to the sel_idx row of every member and every member's
  *   selected branch attends to it under the member's own visibility.  Compressed and window branches are

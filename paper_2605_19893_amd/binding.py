@@ -37,7 +37,7 @@ class SsvNsaParams(ctypes.Structure):
 class SsvNsaPlan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("C", "n_qg", "rows_per_wg", "n_cmp_chunks", "tiles_per_chunk", "n_win_splits", "n_slc_splits",
-                 "min_tiles_per_split", "n_slots", "max_sched_entries")] + [("workspace_bytes", ctypes.c_int64)]
+                 "min_tiles_per_split", "n_slots", "max_sched_entries", "share_group")] + [("workspace_bytes", ctypes.c_int64)]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}

@@ -61,7 +61,8 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
             if (strides[a][j] < 0 || (strides[a][j] * es) % 16) return SSV_EINVAL;
             if (j == 2 && strides[a][j] < dims[a]) return SSV_EINVAL;
         }
-    const int c_max = std::min(p->T, 128 / H_g);
+    const bool shared = p->mode == SSV_REFRESH_SHARED;
+    const int c_max = shared ? p->T : std::min(p->T, 128 / H_g);
     if (p->group_size > c_max) return SSV_EINVAL;
     const int max_blocks = (p->max_seq_len + p->T) / p->l_sel + 1;
     if (max_blocks > 16384) return SSV_EUNSUPPORTED;
@@ -70,7 +71,9 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     ssv_nsa_plan& pl = lo->plan;
     // default: 64 rows per workgroup (one 16-row tile per wave keeps the software pipeline in registers);
     // up to 128 rows (two row tiles per wave) on request
-    pl.C = p->group_size ? p->group_size : std::max(1, std::min(p->T, 64 / H_g));
+    // (the shared-index variant keeps this automatic grouping: its group_size is the sharing group)
+    pl.C = (p->group_size && !shared) ? p->group_size : std::max(1, std::min(p->T, 64 / H_g));
+    pl.share_group = shared ? (p->group_size ? p->group_size : pl.C) : 0;
     pl.n_qg = ceil_div(p->T, pl.C);
     pl.rows_per_wg = pl.C * H_g;
     // Split plan.  A launch should fill the chip once with resident workgroups (LDS and registers allow
@@ -87,7 +90,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     const int ntw = (p->w + p->T) / kTile + 2;                          // window tiles
     pl.max_sched_entries = pl.C * p->n_sel;
     // selected tiles, at most; with one shared index set per group the schedule is a single set
-    const int nts = p->mode == SSV_REFRESH_SHARED ? p->n_sel : pl.max_sched_entries;
+    const int nts = shared ? ceil_div(pl.C, pl.share_group) * p->n_sel : pl.max_sched_entries;
     pl.min_tiles_per_split = env_int("SSV_MIN_TILES", 2);
     const int mt = pl.min_tiles_per_split;
     // Tiles per slice.  If one round of resident workgroups can take the launch with slices of at most 24
@@ -131,8 +134,8 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // importance pass: every query is routed, or one representative per group of C (shared-index variant), then
     // packed 64 rows to a workgroup; 4 workgroups per CU are resident (120 VGPRs, about 30 KB LDS): one round of
     // at most 1024
-    if (p->mode == SSV_REFRESH_SHARED) {
-        const int routed = ceil_div(p->T, pl.C);
+    if (shared) {
+        const int routed = ceil_div(p->T, pl.share_group);
         lo->imp_C = std::max(1, std::min(routed, 64 / H_g));
         lo->imp_n_qg = ceil_div(routed, lo->imp_C);
     } else {
@@ -252,7 +255,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         ia.q = sa.q; ia.kc = sa.kc; ia.seq_lens = seq_lens; ia.n_cmp = n_cmp; ia.n_query = n_query; ia.parents = parents;
         ia.part_stats = part_stats; ia.colsum = colsum;
         ia.B = p->B; ia.T = p->T; ia.H = p->H; ia.H_kv = p->H_kv; ia.H_g = lo.H_g; ia.C = lo.imp_C; ia.n_qg = lo.imp_n_qg;
-        ia.share = p->mode == SSV_REFRESH_SHARED ? pl.C : 0;
+        ia.share = pl.share_group;
         ia.l = p->l; ia.d = p->d; ia.scale_log2 = scale_log2; ia.n_cmp_chunks = pl.n_cmp_chunks; ia.n_imp_chunks = lo.n_imp_chunks;
         ia.n_wg = p->B * p->H_kv * lo.imp_n_qg * lo.n_imp_chunks; ia.nc_pitch = lo.nc_pitch; ia.rows_total = lo.rows_total;
         for (int j = 0; j < 3; ++j) ia.kc_s[j] = sa.kc_s[j];

@@ -32,9 +32,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    # 20 four-byte fields followed by 12 int64 strides; 10 ints + int64 in the plan
+    # 20 four-byte fields followed by 12 int64 strides; 11 ints, padding and an int64 in the plan
     assert ctypes.sizeof(B.SsvNsaParams) == 20 * 4 + 12 * 8
-    assert ctypes.sizeof(B.SsvNsaPlan) == 10 * 4 + 8
+    assert ctypes.sizeof(B.SsvNsaPlan) == 12 * 4 + 8
 
 
 def test_error_strings():
@@ -56,6 +56,7 @@ def test_supported_shapes():
     (dict(n_sel=2), B.SSV_EINVAL), (dict(dtype=7), B.SSV_EINVAL), (dict(mode=3), B.SSV_EINVAL),
     (dict(w=0), B.SSV_EINVAL), (dict(avg_seq_len=40000), B.SSV_EINVAL), (dict(group_size=9), B.SSV_EINVAL), (dict(scale=-1.0), B.SSV_EINVAL),
     (dict(k_stride=(1, 1, 100)), B.SSV_EINVAL), (dict(k_stride=(4 * 32832 * 192, 32832 * 192, 196)), B.SSV_EINVAL),
+    (dict(mode=B.SSV_REFRESH_SHARED, group_size=9), B.SSV_EINVAL),
     (dict(T=65), B.SSV_EUNSUPPORTED), (dict(H=96, H_kv=4), B.SSV_EUNSUPPORTED), (dict(l_sel=128), B.SSV_EUNSUPPORTED),
     (dict(d_k=96), B.SSV_EUNSUPPORTED), (dict(n_sel=40), B.SSV_EUNSUPPORTED),
     (dict(max_seq_len=2 ** 21), B.SSV_EUNSUPPORTED),
@@ -114,3 +115,13 @@ def test_plan_fills_the_chip_and_respects_limits():
     assert (pl.C, pl.n_qg, pl.rows_per_wg) == (2, 4, 32)
     pl = B.ssv_nsa_plan_query(std_params(group_size=8))
     assert (pl.C, pl.n_qg, pl.rows_per_wg) == (8, 1, 128)
+
+
+def test_shared_index_plan_keeps_the_automatic_grouping():
+    p = std_params(mode=B.SSV_REFRESH_SHARED, group_size=2)
+    plan = B.ssv_nsa_plan_query(p)
+    auto = B.ssv_nsa_plan_query(std_params())
+    assert plan.share_group == 2 and plan.C == auto.C and auto.share_group == 0
+    assert B.ssv_nsa_plan_query(std_params(mode=B.SSV_REFRESH_SHARED)).share_group == auto.C
+    # T = 8 queries may share one set even though a workgroup holds only 4 of them
+    assert B.ssv_nsa_plan_query(std_params(mode=B.SSV_REFRESH_SHARED, group_size=8)).share_group == 8

@@ -51,7 +51,7 @@ def run_shared(dev_mod, oracle, case, C):
     ref = oracle.nsa_verify_shared(case, C)
     rep = oracle.group_representatives(case, C)
     dev = dev_mod.DeviceCase(case, mode=SSV_REFRESH_SHARED, group_size=C)
-    assert dev.plan.C == C
+    assert dev.plan.share_group == C
     print(f"[run] {case.name} shared-index C={C} plan={dev.plan.as_dict()}", flush=True)
     dev.run()
     out, sel = dev.results()
@@ -186,7 +186,7 @@ def test_shared_index_variant_chain(dev_mod, oracle, C):
                         poison_pad=True)
     out, sel = run_shared(dev_mod, oracle, case, C)
     if C == 1:
-        dev, ref, out_exact, sel_exact = run_refresh(dev_mod, oracle, case, group_size=1)
+        dev, ref, out_exact, sel_exact = run_refresh(dev_mod, oracle, case)
         assert np.array_equal(sel, sel_exact) and np.array_equal(out, out_exact)
 
 
