@@ -141,6 +141,38 @@ int ssv_nsa_verify_timed(const void* q, const void* k, const void* v, const void
                          const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx,
                          void* workspace, size_t workspace_bytes, void* stream, int repeats, float* kernel_ms);
 
+/* Parameters of ssv_nsa_compress.  Strides in elements (sequence, KV head, row), as in ssv_nsa_params. */
+typedef struct ssv_cmp_params {
+    int32_t B, H_kv;
+    int32_t d_k, d_v;        /* row lengths; d_k * elem and d_v * elem must be multiples of 16 bytes */
+    int32_t l, d;            /* compression block length and stride (l % d == 0) */
+    int32_t dtype;           /* SSV_F32 or SSV_BF16: type of k, v, k_cmp, v_cmp */
+    int32_t max_new_rows;    /* host-side bound (>= 1) on the compressed rows one sequence gains in this call (sizes the grid) */
+    int32_t kv_capacity;     /* rows of k / v per (sequence, KV head) */
+    int32_t cmp_capacity;    /* rows (>= 1) of k_cmp / v_cmp per (sequence, KV head) */
+    int64_t k_stride[3], v_stride[3], kc_stride[3], vc_stride[3];
+} ssv_cmp_params;
+
+/*
+ * Compressed-cache construction, the step before ssv_nsa_verify: the compression branch aggregates committed
+ * tokens into blocks of length l taken every d tokens (Section 2.2); the aggregate here is the mean of the
+ * block's rows, accumulated in fp32 and rounded once to the storage type.  Compressed row c = mean of raw rows
+ * [c*d, c*d + l) and exists only when all of them are committed: N(L) = 0 for L < l, else (L - l) / d + 1, so
+ * draft tokens enter the compressed cache only once they are accepted (Sections 3.1 and 6 keep the raw and
+ * compressed caches consistent across verification rounds).
+ *   k, v (device, read), k_cmp, v_cmp (device, written): layouts of ssv_nsa_verify.
+ *   committed_before [B] (device int32, or NULL = 0 everywhere: build from scratch), committed_after [B] (device
+ *   int32): committed tokens per sequence before and after the update.  Rows N(before) .. N(after)-1 of every KV
+ *   head are written, at most max_new_rows per sequence and never beyond cmp_capacity; committed_after is
+ *   clamped to kv_capacity.  n_cmp [B] (device int32, written): rows valid after the call, min(N(after),
+ *   N(before) + max_new_rows, cmp_capacity); with committed_after < committed_before (rollback) nothing is
+ *   written and n_cmp shrinks to N(after).
+ * All work is enqueued on `stream`; no synchronisation, no allocation.  Returns SSV_OK or a negative SSV_E* code
+ * (SSV_EUNSUPPORTED: l / d > 64, or a row length above 1024 elements).
+ */
+int ssv_nsa_compress(const void* k, const void* v, void* k_cmp, void* v_cmp, const int32_t* committed_before,
+                     const int32_t* committed_after, int32_t* n_cmp, const ssv_cmp_params* p, void* stream);
+
 /* Validates p (host only, no GPU needed) and describes the launch plan.  Returns SSV_OK or an error code. */
 int ssv_nsa_plan_query(const ssv_nsa_params* p, ssv_nsa_plan* plan);
 

@@ -2,6 +2,6 @@
 
 The product is the HIP library behind include/ssv_nsa.h; this package is its thin Python binding.
 """
-from .binding import (SSV_BF16, SSV_F32, SSV_REFRESH, SSV_REFRESH_SHARED, SSV_REUSE, SsvError, SsvNsaParams, SsvNsaPlan,  # noqa: F401
-                      load_library, make_params, ssv_nsa_plan_query, ssv_nsa_supported, ssv_nsa_verify,
+from .binding import (SSV_BF16, SSV_F32, SSV_REFRESH, SSV_REFRESH_SHARED, SSV_REUSE, SsvCmpParams, SsvError, SsvNsaParams, SsvNsaPlan,  # noqa: F401
+                      load_library, make_cmp_params, make_params, ssv_nsa_compress, ssv_nsa_plan_query, ssv_nsa_supported, ssv_nsa_verify,
                       ssv_nsa_workspace_bytes)

@@ -22,7 +22,7 @@ SSV_NUM_KERNELS = 5
 SSV_T_EVENT_PAIR, SSV_NUM_TIMINGS = 5, 6
 
 EXPORTS = ("ssv_nsa_verify", "ssv_nsa_verify_timed", "ssv_nsa_plan_query", "ssv_nsa_workspace_bytes",
-           "ssv_nsa_supported", "ssv_nsa_strerror", "ssv_nsa_kernel_name", "ssv_nsa_version")
+           "ssv_nsa_supported", "ssv_nsa_strerror", "ssv_nsa_kernel_name", "ssv_nsa_version", "ssv_nsa_compress")
 
 
 class SsvNsaParams(ctypes.Structure):
@@ -31,6 +31,12 @@ class SsvNsaParams(ctypes.Structure):
                  "dtype", "mode", "group_size")] + \
                [("scale", ctypes.c_float), ("max_seq_len", ctypes.c_int32), ("max_n_cmp", ctypes.c_int32),
                 ("avg_seq_len", ctypes.c_int32)] + \
+               [(n, ctypes.c_int64 * 3) for n in ("k_stride", "v_stride", "kc_stride", "vc_stride")]
+
+
+class SsvCmpParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("B", "H_kv", "d_k", "d_v", "l", "d", "dtype", "max_new_rows", "kv_capacity", "cmp_capacity")] + \
                [(n, ctypes.c_int64 * 3) for n in ("k_stride", "v_stride", "kc_stride", "vc_stride")]
 
 
@@ -76,6 +82,8 @@ def load_library() -> ctypes.CDLL:
         lib.ssv_nsa_kernel_name.restype = ctypes.c_char_p
         lib.ssv_nsa_kernel_name.argtypes = [ctypes.c_int]
         lib.ssv_nsa_version.restype = ctypes.c_int
+        lib.ssv_nsa_compress.restype = ctypes.c_int
+        lib.ssv_nsa_compress.argtypes = [vp] * 4 + [i32p] * 3 + [ctypes.POINTER(SsvCmpParams), vp]
         _lib = lib
     return _lib
 
@@ -144,3 +152,20 @@ def ssv_nsa_verify(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_
         kernel_ms.extend(float(x) for x in ms)
     if rc != SSV_OK:
         raise SsvError(rc, "ssv_nsa_verify")
+
+
+def make_cmp_params(*, B, H_kv, d_k, d_v, l, d, dtype, max_new_rows, kv_capacity, cmp_capacity, k_stride, v_stride,
+                    kc_stride, vc_stride) -> SsvCmpParams:
+    p = SsvCmpParams(B=B, H_kv=H_kv, d_k=d_k, d_v=d_v, l=l, d=d, dtype=dtype, max_new_rows=max_new_rows,
+                     kv_capacity=kv_capacity, cmp_capacity=cmp_capacity)
+    for name, st in (("k_stride", k_stride), ("v_stride", v_stride), ("kc_stride", kc_stride), ("vc_stride", vc_stride)):
+        setattr(p, name, (ctypes.c_int64 * 3)(*[int(x) for x in st]))
+    return p
+
+
+def ssv_nsa_compress(k, v, k_cmp, v_cmp, committed_before, committed_after, n_cmp, p: SsvCmpParams, stream: int) -> None:
+    """Enqueue the construction of the compressed rows that become complete between two committed lengths."""
+    rc = load_library().ssv_nsa_compress(_ptr(k), _ptr(v), _ptr(k_cmp), _ptr(v_cmp), _ptr(committed_before),
+                                         _ptr(committed_after), _ptr(n_cmp), ctypes.byref(p), ctypes.c_void_p(int(stream)))
+    if rc != SSV_OK:
+        raise SsvError(rc, "ssv_nsa_compress")

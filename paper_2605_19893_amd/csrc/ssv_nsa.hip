@@ -8,6 +8,7 @@
 
 #include "../../include/ssv_nsa.h"
 #include "k_combine.hpp"
+#include "k_compress.hpp"
 #include "k_importance.hpp"
 #include "k_stream.hpp"
 #include "k_topn.hpp"
@@ -370,6 +371,48 @@ int ssv_nsa_verify_timed(const void* q, const void* k, const void* v, const void
                          void* workspace, size_t workspace_bytes, void* stream, int repeats, float* kernel_ms) {
     return verify_impl(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_parents, p, out, sel_idx, workspace,
                        workspace_bytes, stream, kernel_ms, repeats, true);
+}
+
+int ssv_nsa_compress(const void* k, const void* v, void* k_cmp, void* v_cmp, const int32_t* committed_before,
+                     const int32_t* committed_after, int32_t* n_cmp, const ssv_cmp_params* p, void* stream) {
+    if (!k || !v || !k_cmp || !v_cmp || !committed_after || !n_cmp || !p) return SSV_EINVAL;
+    if (p->B < 1 || p->H_kv < 1 || p->d_k < 1 || p->d_v < 1 || p->l < 1 || p->d < 1 || p->l % p->d) return SSV_EINVAL;
+    if (p->dtype != SSV_F32 && p->dtype != SSV_BF16) return SSV_EINVAL;
+    if (p->max_new_rows < 1 || p->kv_capacity < 0 || p->cmp_capacity < 1) return SSV_EINVAL;
+    const int es = p->dtype == SSV_BF16 ? 2 : 4;
+    if ((p->d_k * es) % 16 || (p->d_v * es) % 16) return SSV_EINVAL;
+    const int64_t* strides[4] = {p->k_stride, p->v_stride, p->kc_stride, p->vc_stride};
+    const int dims[4] = {p->d_k, p->d_v, p->d_k, p->d_v};
+    for (int a = 0; a < 4; ++a)
+        for (int j = 0; j < 3; ++j) {
+            if (strides[a][j] < 0 || (strides[a][j] * es) % 16) return SSV_EINVAL;
+            if (j == 2 && strides[a][j] < dims[a]) return SSV_EINVAL;
+        }
+    const void* aligned16[] = {k, v, k_cmp, v_cmp};
+    for (const void* ptr : aligned16)
+        if (reinterpret_cast<uintptr_t>(ptr) % 16) return SSV_EINVAL;
+    const int ratio = p->l / p->d;
+    if (ratio > 64 || p->d_k > 1024 || p->d_v > 1024) return SSV_EUNSUPPORTED;
+
+    CompressArgs ca{};
+    ca.k = (const char*)k; ca.v = (const char*)v; ca.kc = (char*)k_cmp; ca.vc = (char*)v_cmp;
+    ca.before = committed_before; ca.after = committed_after; ca.n_cmp = n_cmp;
+    ca.B = p->B; ca.H_kv = p->H_kv; ca.l = p->l; ca.d = p->d; ca.ratio = ratio;
+    ca.rows_per_wg = std::min(32, p->max_new_rows); ca.cap = p->cmp_capacity; ca.kv_cap = p->kv_capacity;
+    ca.max_new = p->max_new_rows;
+    ca.k_groups = p->d_k * es / 16; ca.v_groups = p->d_v * es / 16;
+    ca.inv_l = 1.0f / (float)p->l;
+    for (int j = 0; j < 3; ++j) {
+        ca.k_s[j] = p->k_stride[j] * es; ca.v_s[j] = p->v_stride[j] * es;
+        ca.kc_s[j] = p->kc_stride[j] * es; ca.vc_s[j] = p->vc_stride[j] * es;
+    }
+    const size_t lds = (size_t)(ca.rows_per_wg + ratio - 1) * std::max(p->d_k, p->d_v) * sizeof(float);
+    if (lds > 64 * 1024) return SSV_EUNSUPPORTED;
+    const dim3 grid(ceil_div(p->max_new_rows, ca.rows_per_wg), p->B * p->H_kv, 2);
+    if (grid.y > 65535) return SSV_EUNSUPPORTED;
+    if (p->dtype == SSV_BF16) hipLaunchKernelGGL((k_compress<true>), grid, dim3(kThreads), lds, (hipStream_t)stream, ca);
+    else hipLaunchKernelGGL((k_compress<false>), grid, dim3(kThreads), lds, (hipStream_t)stream, ca);
+    return hipGetLastError() == hipSuccess ? SSV_OK : SSV_ELAUNCH;
 }
 
 const char* ssv_nsa_strerror(int code) {

@@ -125,3 +125,27 @@ def test_shared_index_plan_keeps_the_automatic_grouping():
     assert B.ssv_nsa_plan_query(std_params(mode=B.SSV_REFRESH_SHARED)).share_group == auto.C
     # T = 8 queries may share one set even though a workgroup holds only 4 of them
     assert B.ssv_nsa_plan_query(std_params(mode=B.SSV_REFRESH_SHARED, group_size=8)).share_group == 8
+
+
+def cmp_params(**over):
+    kw = dict(B=2, H_kv=4, d_k=192, d_v=128, l=32, d=16, dtype=B.SSV_BF16, max_new_rows=8, kv_capacity=4096,
+              cmp_capacity=256, k_stride=(4 * 4096 * 192, 4096 * 192, 192), v_stride=(4 * 4096 * 128, 4096 * 128, 128),
+              kc_stride=(4 * 256 * 192, 256 * 192, 192), vc_stride=(4 * 256 * 128, 256 * 128, 128))
+    kw.update(over)
+    return B.make_cmp_params(**kw)
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(B=0), B.SSV_EINVAL), (dict(l=32, d=12), B.SSV_EINVAL), (dict(dtype=5), B.SSV_EINVAL),
+    (dict(max_new_rows=0), B.SSV_EINVAL), (dict(cmp_capacity=0), B.SSV_EINVAL), (dict(d_k=100), B.SSV_EINVAL),
+    (dict(k_stride=(1, 1, 100)), B.SSV_EINVAL), (dict(l=2048, d=16), B.SSV_EUNSUPPORTED), (dict(d_k=2048, k_stride=(4 * 4096 * 2048, 4096 * 2048, 2048), kc_stride=(4 * 256 * 2048, 256 * 2048, 2048)), B.SSV_EUNSUPPORTED),
+])
+def test_compress_rejects_bad_parameters_without_a_launch(over, code):
+    assert ctypes.sizeof(B.SsvCmpParams) == 10 * 4 + 12 * 8
+    fake = 4096
+    with pytest.raises(B.SsvError) as e:
+        B.ssv_nsa_compress(fake, fake, fake, fake, None, fake, fake, cmp_params(**over), 0)
+    assert e.value.code == code
+    with pytest.raises(B.SsvError) as e:
+        B.ssv_nsa_compress(fake, fake, fake, None, None, fake, fake, cmp_params(), 0)
+    assert e.value.code == B.SSV_EINVAL
