@@ -313,6 +313,76 @@ def kernel_workload_study(torch, oracle, si, steps, warmup, contexts=(8192, 1638
     return rows
 
 
+def compress_study(torch, si, steps, warmup):
+    """Compressed-cache construction (ssv_nsa_compress): a from-scratch build at the cfg2 shape (the prefill-sized
+    case, HBM-bound: every raw K/V row is read once) and an incremental update after a verification round at the
+    cfg4 shape (0..16 newly committed tokens per sequence: latency-bound).  Sampled rows are checked against the
+    fp64 compression oracle."""
+    import paper_2605_19893_amd as P
+    from oracle import compress as oc
+    res = {}
+    stream = torch.cuda.current_stream().cuda_stream
+    rng = np.random.default_rng(si.config_seed(6))
+    for name, B_, L in (("full_build_cfg2_shape", 16, 65536), ("incremental_cfg4_shape", 32, None)):
+        H_kv, d_k, d_v, l, d = 4, 192, 128, 32, 16
+        if L is None:
+            before = si.config4_lengths(B_, si.config_seed(4)).astype(np.int32)
+            after = before + rng.integers(0, 17, B_).astype(np.int32)
+        else:
+            before, after = np.zeros(B_, np.int32), np.full(B_, L, np.int32)
+        S = int(after.max())
+        cap = oc.n_cmp_rows(S, l, d)
+        k = torch.randn((B_, H_kv, S, d_k), dtype=torch.bfloat16, device="cuda")
+        v = torch.randn((B_, H_kv, S, d_v), dtype=torch.bfloat16, device="cuda")
+        kc = torch.zeros((B_, H_kv, cap, d_k), dtype=torch.bfloat16, device="cuda")
+        vc = torch.zeros((B_, H_kv, cap, d_v), dtype=torch.bfloat16, device="cuda")
+        n_cmp = torch.zeros(B_, dtype=torch.int32, device="cuda")
+        bef_d, aft_d = torch.from_numpy(before).cuda(), torch.from_numpy(after).cuda()
+        new_rows = [oc.n_cmp_rows(int(a), l, d) - oc.n_cmp_rows(int(b0), l, d) for a, b0 in zip(after, before)]
+        p = P.make_cmp_params(B=B_, H_kv=H_kv, d_k=d_k, d_v=d_v, l=l, d=d, dtype=P.SSV_BF16, max_new_rows=max(1, max(new_rows)),
+                              kv_capacity=S, cmp_capacity=cap, k_stride=k.stride()[:3], v_stride=v.stride()[:3],
+                              kc_stride=kc.stride()[:3], vc_stride=vc.stride()[:3])
+        call = lambda: P.ssv_nsa_compress(k, v, kc, vc, bef_d, aft_d, n_cmp, p, stream)
+        for _ in range(warmup):
+            call()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(steps):
+            call()
+        ev1.record()
+        torch.cuda.synchronize()
+        ms = ev0.elapsed_time(ev1) / steps
+        # algorithmic bytes: every raw row under a new compressed row once, every new compressed row once
+        raw_rows = sum((n - 1) * d + l for n in new_rows if n > 0)
+        nbytes = H_kv * (d_k + d_v) * 2 * (raw_rows + sum(new_rows))
+        # sampled parity against the oracle
+        worst_ulps, checked = 0.0, 0
+        kh, vh = None, None
+        for _ in range(48):
+            b = int(rng.integers(0, B_))
+            if new_rows[b] <= 0:
+                continue
+            h = int(rng.integers(0, H_kv))
+            c = oc.n_cmp_rows(int(before[b]), l, d) + int(rng.integers(0, new_rows[b]))
+            for src, dst in ((k, kc), (v, vc)):
+                raw = src[b, h, c * d:c * d + l].float().cpu().numpy().astype(np.float64)
+                _, want, mean = oc.compress(raw, 0, l, l, d, "bf16")
+                got = dst[b, h, c].float().cpu().numpy().astype(np.float64)
+                spacing = np.ldexp(1.0, np.frexp(mean[0])[1] - 8)
+                worst_ulps = max(worst_ulps, float((np.abs(got - mean[0]) / spacing).max()))
+                checked += got.size
+        assert worst_ulps <= 0.5 + 1e-3, worst_ulps
+        assert np.array_equal(n_cmp.cpu().numpy(), [oc.n_cmp_rows(int(a), l, d) for a in after])
+        res[name] = {"B": B_, "new_compressed_rows_per_head": int(sum(new_rows)), "us_per_call": ms * 1e3,
+                     "algorithmic_bytes": int(nbytes), "achieved_GBs": nbytes / (ms * 1e-3) / 1e9,
+                     "hbm_frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "parity_sampled_elements": checked, "parity_max_error_in_storage_ulps": worst_ulps}
+        del k, v, kc, vc
+        torch.cuda.empty_cache()
+    return res
+
+
 def cpu_baseline(oracle, case, budget_s=8.0):
     """The oracle as it stands, timed on this machine's host cores on the same workload."""
     threads = oracle.default_threads()
@@ -340,10 +410,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", default="", help="measure only this workload (cfg1, cfg2, cfg3 or cfg4; for profiling runs), "
                     "'shared': the shared-index study alone, at T = 8 and T = 32, or 'kernel-workload': the paper's "
-                    "isolated-kernel workload (32/8 heads of dimension 64, draft lengths 4 and 64, contexts 8K-64K)")
+                    "isolated-kernel workload (32/8 heads of dimension 64, draft lengths 4 and 64, contexts 8K-64K), "
+                    "or 'compress': the compressed-cache construction kernel")
     ap.add_argument("--group-size", type=int, default=0, help="verifier queries per workgroup (0 = library default)")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 1 GiB device-to-device copy (a known-size reference for HBM byte counters)")
+                    help="kept for the profiling commands: the plain 1 GiB device-to-device copy (a known-size reference for HBM "
+                         "byte counters) now runs in every invocation")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -357,14 +429,21 @@ def main():
     import ssv_inputs as si
 
     torch.cuda.set_device(0)
-    if args.copy_calibration:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)       # reads 1 GiB, writes 1 GiB per copy
-        torch.cuda.synchronize()
-        del src, dst
-        torch.cuda.empty_cache()
+    # a plain 1 GiB device-to-device copy: the known-size reference for the HBM byte counters, and the copy
+    # bandwidth of this machine (read + write bytes over time) to set next to the 8 TB/s peak
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(3):
+        dst.copy_(src)       # reads 1 GiB, writes 1 GiB per copy
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 3 * 2 * (1 << 30) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del src, dst
+    torch.cuda.empty_cache()
     others = []
     main_res = None
     if args.only in ("", "cfg1"):
@@ -388,6 +467,10 @@ def main():
             main_res = r2
         else:
             others.append(r2)
+    if args.only == "compress":
+        print(json.dumps({"compressed_cache_construction": compress_study(torch, si, max(20, args.steps // 10), 5),
+                          "device_copy_GBs": copy_gbs}))
+        return
     if args.only == "kernel-workload":
         rows = kernel_workload_study(torch, oracle, si, max(50, args.steps // 3), max(5, args.warmup // 3))
         print(json.dumps({"paper_kernel_workload": rows}))
@@ -421,6 +504,7 @@ def main():
         "modes": main_res["modes"],
         "other_workloads": others,
         "approx_shared_index_variant": shared_rows,
+        "device_copy_GBs": copy_gbs,
     }
     print(json.dumps(line))
 

@@ -58,9 +58,7 @@ __global__ void __launch_bounds__(kThreads) k_compress(const CompressArgs a) {
         float acc[EPG];
 #pragma unroll
         for (int e = 0; e < EPG; ++e) acc[e] = 0.f;
-#pragma unroll 8
-        for (int r = 0; r < a.d; ++r) {
-            const u32x4 raw = *reinterpret_cast<const u32x4*>(p + r * src_row);
+        auto add_row = [&](const u32x4 raw) {
             if (BF16) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -71,6 +69,16 @@ __global__ void __launch_bounds__(kThreads) k_compress(const CompressArgs a) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[e] += __uint_as_float(raw[e]);
             }
+        };
+        if (a.d == 16) {        // the standard stride: all sixteen row loads in flight before the first add
+            u32x4 raw[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) raw[r] = *reinterpret_cast<const u32x4*>(p + r * src_row);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) add_row(raw[r]);
+        } else {
+#pragma unroll 4
+            for (int r = 0; r < a.d; ++r) add_row(*reinterpret_cast<const u32x4*>(p + r * src_row));
         }
 #pragma unroll
         for (int e = 0; e < EPG; e += 4)

@@ -398,7 +398,8 @@ int ssv_nsa_compress(const void* k, const void* v, void* k_cmp, void* v_cmp, con
     ca.k = (const char*)k; ca.v = (const char*)v; ca.kc = (char*)k_cmp; ca.vc = (char*)v_cmp;
     ca.before = committed_before; ca.after = committed_after; ca.n_cmp = n_cmp;
     ca.B = p->B; ca.H_kv = p->H_kv; ca.l = p->l; ca.d = p->d; ca.ratio = ratio;
-    ca.rows_per_wg = std::min(32, p->max_new_rows); ca.cap = p->cmp_capacity; ca.kv_cap = p->kv_capacity;
+    // 32 chunks per workgroup: with 16 or 24 column groups per row the chunk tasks fill whole passes of 256 threads
+    ca.rows_per_wg = std::min(std::max(1, env_int("SSV_CMP_ROWS", 33 - ratio)), p->max_new_rows); ca.cap = p->cmp_capacity; ca.kv_cap = p->kv_capacity;
     ca.max_new = p->max_new_rows;
     ca.k_groups = p->d_k * es / 16; ca.v_groups = p->d_v * es / 16;
     ca.inv_l = 1.0f / (float)p->l;
