@@ -1,4 +1,4 @@
-// Routing, part 2 (Section 5.1 routing launch; "importance scoring", Section 5.1): the compressed
+// Routing, part 2 (Section 5.1: the routing launch scores the importance of blocks): the compressed
 // probabilities of every head must be normalised with that head's global softmax statistics before
 // they are summed over the heads of a GQA group, so this pass runs after the compressed scan has
 // produced the per-slice (max, sum) pairs.  It recomputes S = Q K_cmp^T for its slice of compressed

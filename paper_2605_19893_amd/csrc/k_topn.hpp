@@ -1,5 +1,5 @@
 // Routing, part 3: block importance and top-n selection per (sequence, verifier query, KV group)
-// ("Top-n reduction", Section 5.1; mandatory initial and local blocks that count toward n, Section 7.3).
+// (the top-n reduction of the routing launch, Section 5.1; mandatory initial and local blocks that count toward n, Section 7.3).
 //
 //   imp[j] = sum_{m < l'/d} sum_{n' < l/d} colsum[(l'/d) j + m - n']      (terms outside [0, visible) are 0)
 //   candidates j = 0..J, J = block of the query's own slot; forced blocks are ranked first;
