@@ -173,6 +173,59 @@ typedef struct ssv_cmp_params {
 int ssv_nsa_compress(const void* k, const void* v, void* k_cmp, void* v_cmp, const int32_t* committed_before,
                      const int32_t* committed_after, int32_t* n_cmp, const ssv_cmp_params* p, void* stream);
 
+/*
+ * Runtime guard of the throughput-aware planner (Section 6.3, Algorithm 1; host only, no GPU work).  A request
+ * starts on the best-ranked valid strategy of its profile entry; every verification step reports its accepted-token
+ * count A_t and latency T_t.  The guard smooths A_t (ema = alpha*A_t + (1-alpha)*ema, starting at the first
+ * observation of a strategy); once a strategy has run warmup_steps steps, each step whose smoothed value is below
+ * ratio * expected[active] counts, any other step clears the count, and patience counted steps in a row move the
+ * request to the next-ranked valid strategy, restarting smoothing, warm-up and count.  After max_transitions moves
+ * (or with no candidate left) a further trigger settles the request on the explored strategy with the largest
+ * sum(A) / sum(T) and ends refinement; refinement also ends after early_steps steps (0 = no limit).
+ * The paper's constants: alpha 0.40, warm-up 8, ratio 0.85, patience 5, two moves (ssv_guard_default_config).
+ */
+#define SSV_GUARD_MAX_CANDIDATES 16   /* a profile entry holds 12 ranked candidates in the paper */
+
+typedef struct ssv_guard_config {
+    double  alpha;            /* smoothing coefficient in (0, 1] */
+    double  ratio;            /* fraction of the profiled expectation below which a step counts as a miss */
+    int32_t warmup_steps;     /* steps of a strategy that only update the smoothed value */
+    int32_t patience;         /* consecutive misses that trigger a move */
+    int32_t max_transitions;  /* moves allowed per request */
+    int32_t early_steps;      /* steps of the request during which refinement is active; 0 = all */
+} ssv_guard_config;
+
+/* Plain state of one request (host memory owned by the caller; no pointers inside, so it may be copied or stored). */
+typedef struct ssv_guard_state {
+    ssv_guard_config cfg;
+    int32_t n_candidates, active, transitions, settled;
+    int32_t total_steps, steps_on_active, below_streak, has_ema;
+    double  ema;
+    double  expected[SSV_GUARD_MAX_CANDIDATES];      /* profiled E[A] per candidate, best-ranked first */
+    uint8_t valid[SSV_GUARD_MAX_CANDIDATES], explored[SSV_GUARD_MAX_CANDIDATES];
+    double  sum_accepted[SSV_GUARD_MAX_CANDIDATES], sum_latency[SSV_GUARD_MAX_CANDIDATES];
+} ssv_guard_state;
+
+void ssv_guard_default_config(ssv_guard_config* cfg);
+/* expected [n] (host), valid [n] (host, or NULL = all valid), 1 <= n <= SSV_GUARD_MAX_CANDIDATES.  SSV_EINVAL if no
+ * candidate is valid or a parameter is out of range. */
+int ssv_guard_init(ssv_guard_state* state, const ssv_guard_config* cfg, const double* expected, const uint8_t* valid,
+                   int32_t n);
+/* Feeds one verification step; returns the index (>= 0) of the strategy to use for the next step, or SSV_EINVAL. */
+int ssv_guard_observe(ssv_guard_state* state, double accepted_tokens, double step_latency);
+
+/*
+ * Draft-tree flattening (Section 4.1; host only): reorders a tree given as parent indices (parents[i] in
+ * {-1, 0..i-1}, -1 = child of the last committed token) into the verifier batch, breadth-first (siblings become
+ * adjacent) or depth-first pre-order (parent and children become adjacent); children keep their relative order.
+ * perm [n] (host, out): perm[new] = old index; new_parents [n] (host, out): parents in the new numbering, ready to
+ * be uploaded as tree_parents of ssv_nsa_verify (q, gates and the draft K/V rows must be permuted with perm).
+ * Returns SSV_OK, or SSV_EINVAL for a malformed tree.
+ */
+#define SSV_TREE_BFS 0
+#define SSV_TREE_DFS 1
+int ssv_tree_flatten(const int32_t* parents, int32_t n, int32_t order, int32_t* perm, int32_t* new_parents);
+
 /* Validates p (host only, no GPU needed) and describes the launch plan.  Returns SSV_OK or an error code. */
 int ssv_nsa_plan_query(const ssv_nsa_params* p, ssv_nsa_plan* plan);
 

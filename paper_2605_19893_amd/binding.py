@@ -22,7 +22,10 @@ SSV_NUM_KERNELS = 5
 SSV_T_EVENT_PAIR, SSV_NUM_TIMINGS = 5, 6
 
 EXPORTS = ("ssv_nsa_verify", "ssv_nsa_verify_timed", "ssv_nsa_plan_query", "ssv_nsa_workspace_bytes",
-           "ssv_nsa_supported", "ssv_nsa_strerror", "ssv_nsa_kernel_name", "ssv_nsa_version", "ssv_nsa_compress")
+           "ssv_nsa_supported", "ssv_nsa_strerror", "ssv_nsa_kernel_name", "ssv_nsa_version", "ssv_nsa_compress",
+           "ssv_guard_default_config", "ssv_guard_init", "ssv_guard_observe", "ssv_tree_flatten")
+SSV_GUARD_MAX_CANDIDATES = 16
+SSV_TREE_BFS, SSV_TREE_DFS = 0, 1
 
 
 class SsvNsaParams(ctypes.Structure):
@@ -38,6 +41,21 @@ class SsvCmpParams(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("B", "H_kv", "d_k", "d_v", "l", "d", "dtype", "max_new_rows", "kv_capacity", "cmp_capacity")] + \
                [(n, ctypes.c_int64 * 3) for n in ("k_stride", "v_stride", "kc_stride", "vc_stride")]
+
+
+class SsvGuardConfig(ctypes.Structure):
+    _fields_ = [("alpha", ctypes.c_double), ("ratio", ctypes.c_double), ("warmup_steps", ctypes.c_int32),
+                ("patience", ctypes.c_int32), ("max_transitions", ctypes.c_int32), ("early_steps", ctypes.c_int32)]
+
+
+class SsvGuardState(ctypes.Structure):
+    _fields_ = [("cfg", SsvGuardConfig)] + \
+               [(n, ctypes.c_int32) for n in ("n_candidates", "active", "transitions", "settled", "total_steps",
+                                              "steps_on_active", "below_streak", "has_ema")] + \
+               [("ema", ctypes.c_double), ("expected", ctypes.c_double * SSV_GUARD_MAX_CANDIDATES),
+                ("valid", ctypes.c_uint8 * SSV_GUARD_MAX_CANDIDATES), ("explored", ctypes.c_uint8 * SSV_GUARD_MAX_CANDIDATES),
+                ("sum_accepted", ctypes.c_double * SSV_GUARD_MAX_CANDIDATES),
+                ("sum_latency", ctypes.c_double * SSV_GUARD_MAX_CANDIDATES)]
 
 
 class SsvNsaPlan(ctypes.Structure):
@@ -82,6 +100,16 @@ def load_library() -> ctypes.CDLL:
         lib.ssv_nsa_kernel_name.restype = ctypes.c_char_p
         lib.ssv_nsa_kernel_name.argtypes = [ctypes.c_int]
         lib.ssv_nsa_version.restype = ctypes.c_int
+        lib.ssv_guard_default_config.restype = None
+        lib.ssv_guard_default_config.argtypes = [ctypes.POINTER(SsvGuardConfig)]
+        lib.ssv_guard_init.restype = ctypes.c_int
+        lib.ssv_guard_init.argtypes = [ctypes.POINTER(SsvGuardState), ctypes.POINTER(SsvGuardConfig),
+                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint8), ctypes.c_int32]
+        lib.ssv_guard_observe.restype = ctypes.c_int
+        lib.ssv_guard_observe.argtypes = [ctypes.POINTER(SsvGuardState), ctypes.c_double, ctypes.c_double]
+        lib.ssv_tree_flatten.restype = ctypes.c_int
+        lib.ssv_tree_flatten.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
         lib.ssv_nsa_compress.restype = ctypes.c_int
         lib.ssv_nsa_compress.argtypes = [vp] * 4 + [i32p] * 3 + [ctypes.POINTER(SsvCmpParams), vp]
         _lib = lib
@@ -169,3 +197,38 @@ def ssv_nsa_compress(k, v, k_cmp, v_cmp, committed_before, committed_after, n_cm
                                          _ptr(committed_after), _ptr(n_cmp), ctypes.byref(p), ctypes.c_void_p(int(stream)))
     if rc != SSV_OK:
         raise SsvError(rc, "ssv_nsa_compress")
+
+
+def ssv_guard_default_config() -> SsvGuardConfig:
+    cfg = SsvGuardConfig()
+    load_library().ssv_guard_default_config(ctypes.byref(cfg))
+    return cfg
+
+
+def ssv_guard_init(cfg: SsvGuardConfig, expected, valid=None) -> SsvGuardState:
+    n = len(expected)
+    state = SsvGuardState()
+    exp = (ctypes.c_double * max(n, 1))(*[float(x) for x in expected])
+    val = None if valid is None else (ctypes.c_uint8 * max(n, 1))(*[1 if x else 0 for x in valid])
+    rc = load_library().ssv_guard_init(ctypes.byref(state), ctypes.byref(cfg), exp, val, n)
+    if rc != SSV_OK:
+        raise SsvError(rc, "ssv_guard_init")
+    return state
+
+
+def ssv_guard_observe(state: SsvGuardState, accepted_tokens: float, step_latency: float) -> int:
+    rc = load_library().ssv_guard_observe(ctypes.byref(state), float(accepted_tokens), float(step_latency))
+    if rc < 0:
+        raise SsvError(rc, "ssv_guard_observe")
+    return rc
+
+
+def ssv_tree_flatten(parents, order: int):
+    """(perm, new_parents) as Python lists; perm[new] = old."""
+    n = len(parents)
+    par = (ctypes.c_int32 * max(n, 1))(*[int(x) for x in parents])
+    perm, newp = (ctypes.c_int32 * max(n, 1))(), (ctypes.c_int32 * max(n, 1))()
+    rc = load_library().ssv_tree_flatten(par, n, order, perm, newp)
+    if rc != SSV_OK:
+        raise SsvError(rc, "ssv_tree_flatten")
+    return list(perm)[:n], list(newp)[:n]

@@ -12,6 +12,7 @@
 #include "k_importance.hpp"
 #include "k_stream.hpp"
 #include "k_topn.hpp"
+#include "planner.hpp"
 
 namespace {
 
@@ -414,6 +415,25 @@ int ssv_nsa_compress(const void* k, const void* v, void* k_cmp, void* v_cmp, con
     if (p->dtype == SSV_BF16) hipLaunchKernelGGL((k_compress<true>), grid, dim3(kThreads), lds, (hipStream_t)stream, ca);
     else hipLaunchKernelGGL((k_compress<false>), grid, dim3(kThreads), lds, (hipStream_t)stream, ca);
     return hipGetLastError() == hipSuccess ? SSV_OK : SSV_ELAUNCH;
+}
+
+void ssv_guard_default_config(ssv_guard_config* cfg) {
+    if (!cfg) return;
+    cfg->alpha = 0.40; cfg->ratio = 0.85; cfg->warmup_steps = 8; cfg->patience = 5; cfg->max_transitions = 2;
+    cfg->early_steps = 0;
+}
+
+int ssv_guard_init(ssv_guard_state* state, const ssv_guard_config* cfg, const double* expected, const uint8_t* valid,
+                   int32_t n) {
+    return ssv::guard_init(state, cfg, expected, valid, n);
+}
+
+int ssv_guard_observe(ssv_guard_state* state, double accepted_tokens, double step_latency) {
+    return ssv::guard_observe(state, accepted_tokens, step_latency);
+}
+
+int ssv_tree_flatten(const int32_t* parents, int32_t n, int32_t order, int32_t* perm, int32_t* new_parents) {
+    return ssv::tree_flatten(parents, n, order, perm, new_parents);
 }
 
 const char* ssv_nsa_strerror(int code) {

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     lib = B.load_library()
     with open(os.path.join(ROOT, "include", "ssv_nsa.h")) as f:
         header = f.read()
-    declared = set(re.findall(r"\b(ssv_nsa_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(ssv_(?:nsa|guard|tree)_[a-z_]+)\s*\(", header))
     assert declared == set(B.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None

@@ -226,3 +226,27 @@ def test_group_size_can_change_on_a_live_case(dev_mod, oracle):
         check(case, compare(case, oracle, ref, out, sel))
         outs.append(sel)
     assert all(np.array_equal(outs[0], s) for s in outs[1:])
+
+
+def test_library_flattening_reorders_a_tree_without_changing_results(dev_mod, oracle):
+    """A BFS-ordered draft tree re-flattened to DFS with ssv_tree_flatten (Section 4.1): queries, gates and draft
+    K/V rows are permuted with the returned order; every node keeps its output and index set.  All 21 draft slots
+    lie in one selection block and no compressed block reaches into the drafts, so slot order is immaterial."""
+    from paper_2605_19893_amd import binding as B
+    import copy
+    par = si.tree_parents((3, 2, 2), "bfs")
+    T, L = len(par), 2048
+    bfs = si.make_case("flatten_bfs", "bf16", 1, T, 32, 2, 192, 128, si.STD_NSA, [L], 135, rho=0.6, parents=par)
+    perm, new_par = B.ssv_tree_flatten(par.tolist(), B.SSV_TREE_DFS)
+    assert new_par == si.tree_parents((3, 2, 2), "dfs").tolist()
+    dfs = copy.deepcopy(bfs)
+    dfs.name = "flatten_dfs"
+    dfs.parents = np.asarray(new_par, np.int32)[None, :].copy()
+    dfs.q[0] = bfs.q[0, perm]
+    dfs.gates[0] = bfs.gates[0, perm]
+    for arr_d, arr_b in ((dfs.k, bfs.k), (dfs.v, bfs.v)):
+        arr_d[0, :, L:L + T] = arr_b[0, :, [L + t for t in perm]].transpose(1, 0, 2)
+    _, _, out_b, sel_b = run_refresh(dev_mod, oracle, bfs)
+    _, _, out_d, sel_d = run_refresh(dev_mod, oracle, dfs)
+    assert np.array_equal(sel_d[0], sel_b[0, perm])
+    assert np.abs(out_d[0] - out_b[0, perm]).max() <= 2e-2
