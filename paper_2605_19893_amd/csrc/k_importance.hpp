@@ -196,8 +196,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
                 const int key = 16 * kt + n;
                 if (a.H_g >= 4) {
                     float v = (p[0] + p[1]) + (p[2] + p[3]);
-                    if (a.H_g >= 8) v += __shfl_xor(v, 16);
-                    if (a.H_g >= 16) v += __shfl_xor(v, 32);
+                    if (a.H_g >= 8) v = xor16_add(v);
+                    if (a.H_g >= 16) v = xor32_add(v);
                     const int gpq = a.H_g >> 2;                  // lane groups per query
                     if ((G % gpq) == 0) {
                         const int j = (rt * 16 + 4 * G) / a.H_g;

@@ -406,8 +406,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                 for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[t][kt][r]);
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                mx = xor16_max(mx);
+                mx = xor32_max(mx);
                 const float m_new = fmaxf(mrun[t], mx);
                 const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
                 const float alpha = fast_exp2((mrun[t] - m_use) * a.scale_log2);
@@ -421,8 +421,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                         s[t][kt][r] = pz;
                         rs += pz;
                     }
-                rs += __shfl_xor(rs, 16);
-                rs += __shfl_xor(rs, 32);
+                rs = xor16_add(rs);
+                rs = xor32_add(rs);
                 zrun[t] = zrun[t] * alpha + rs;
                 mrun[t] = m_new;
                 if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0ull) {      // uniform: some running max moved
