@@ -97,14 +97,15 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     const int mt = pl.min_tiles_per_split;
     // Tiles per slice.  If one round of resident workgroups can take the launch with slices of at most 24
     // tiles, `per` is grown until the slices of an average unit fit the capacity (no partial second round).
-    // Otherwise slices are cut short (12 tiles): several rounds of workgroups, and the longest slice, the long
-    // pole of a mixed-length batch, stays short.
+    // Otherwise slices are cut to 24 tiles: several rounds of workgroups, and the longest slice, the long pole of
+    // a mixed-length batch, stays bounded (12-tile slices balanced better but cost 5-10 % at the 128K-context
+    // configurations: twice the partial states to write and merge, twice the per-workgroup start-up).
     auto tiles_per_slice = [&](const int* tiles, int n_roles) {
         const int spu = std::max(n_roles, capacity / units);      // slices per unit one round can hold
         int total = 0;
         for (int r = 0; r < n_roles; ++r) total += tiles[r];
         int per = std::max(mt, ceil_div(total, spu));
-        if (per > 24) return 12;
+        if (per > 24) return env_int("SSV_LONG_SLICE", 24);
         for (;; ++per) {
             int sum = 0;
             for (int r = 0; r < n_roles; ++r) sum += std::max(1, ceil_div(tiles[r], per));
