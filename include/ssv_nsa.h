@@ -80,8 +80,10 @@ typedef struct ssv_nsa_params {
                              (C * H_g <= 64); never changes the result.  SSV_REFRESH_SHARED: queries per index-sharing
                              group (1..T; 0 = the automatic C); the workgroup grouping is then the automatic one */
     float   scale;        /* softmax scale; 0 => 1/sqrt(d_k) */
-    int32_t max_seq_len;  /* host-side upper bound on seq_lens[b] (sizes grids and scratch) */
-    int32_t max_n_cmp;    /* host-side upper bound on n_cmp[b] */
+    int32_t max_seq_len;  /* host-side upper bound on seq_lens[b] (sizes grids and scratch); k and v hold at least
+                             max_seq_len + T rows per (sequence, KV head); larger seq_lens[b] are clamped to it */
+    int32_t max_n_cmp;    /* host-side upper bound on n_cmp[b] = rows of k_cmp / v_cmp per (sequence, KV head); larger
+                             n_cmp[b] are clamped to it */
     int32_t avg_seq_len;  /* host-side hint: mean of seq_lens[b] (balances splits of mixed-length batches); 0 = max_seq_len */
     int64_t k_stride[3], v_stride[3], kc_stride[3], vc_stride[3];  /* elements: batch, KV head, row */
 } ssv_nsa_params;

@@ -230,13 +230,15 @@ struct SeqMeta {
     int L, Tq, n_cmp;
 };
 
+// Lengths read from device memory are clamped to the host-side bounds every buffer and grid was sized with, so that
+// an inconsistent length array cannot take a load past the end of a cache.
 __device__ __forceinline__ SeqMeta build_tree_meta(int tid, int b, int T, const int32_t* seq_lens, const int32_t* n_query,
-                                                   const int32_t* n_cmp, const int32_t* parents, int l, int d, int* s_par,
-                                                   int* s_depth, int* s_cmax, uint64_t* s_anc) {
+                                                   const int32_t* n_cmp, const int32_t* parents, int l, int d, int max_seq_len,
+                                                   int max_n_cmp, int* s_par, int* s_depth, int* s_cmax, uint64_t* s_anc) {
     SeqMeta sm;
-    sm.L = seq_lens[b];
+    sm.L = min(max(seq_lens[b], 0), max_seq_len);
     sm.Tq = n_query ? min(max(n_query[b], 0), T) : T;
-    sm.n_cmp = max(n_cmp[b], 0);
+    sm.n_cmp = min(max(n_cmp[b], 0), max_n_cmp);
     if (parents) {
         if (tid < kMaxT) {
             int par = -1;

@@ -25,6 +25,7 @@ struct ImportanceArgs {
     int C, n_qg;               // routed queries per workgroup; workgroups over the routed queries of a sequence
     int share;                 // 0: every query is routed; > 0: one representative per group of `share` queries
     int l, d;
+    int max_seq_len, max_n_cmp;   // host-side bounds the lengths read from device memory are clamped to
     float scale_log2;
     int n_cmp_chunks;          // slices of the compressed scan (partial statistics to merge)
     int n_imp_chunks;          // slices of this kernel's own pass over k_cmp
@@ -71,7 +72,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     const int bg = wg / (a.n_qg * a.n_imp_chunks);
     const int b = bg / a.H_kv, g = bg % a.H_kv;
 
-    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, s_par, s_depth, s_cmax,
+    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, a.max_seq_len, a.max_n_cmp, s_par, s_depth,
+                                       s_cmax,
                                        s_anc);
     const int L = sm.L, Tq = sm.Tq;
     const int n_routed = a.share ? (Tq + a.share - 1) / a.share : Tq;

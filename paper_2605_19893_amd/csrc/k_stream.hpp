@@ -25,6 +25,7 @@ struct StreamArgs {
     float *part_stats, *part_acc;
     int B, T, H, H_kv, H_g, C, n_qg;
     int l, d, n_sel, w;
+    int max_seq_len, max_n_cmp;   // host-side bounds the lengths read from device memory are clamped to
     float scale_log2;
     int n_cmp_chunks, n_win_splits, n_slc_splits, min_tiles;
     int slot_lo, slot_cnt;   // partial-state slots computed by this launch
@@ -126,7 +127,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     const bool r_win = (ROLES & 2) && role == ROLE_WIN;
     const bool r_slc = (ROLES & 4) && role == ROLE_SLC;
 
-    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, s_par, s_depth, s_cmax,
+    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, a.max_seq_len, a.max_n_cmp, s_par, s_depth,
+                                       s_cmax,
                                        s_anc);
     const int L = sm.L, Tq = sm.Tq;
     SSV_STAMP(1);

@@ -26,6 +26,7 @@ struct TopnArgs {
     int32_t* sel_idx;        // [B, T, H_kv, n_sel]
     int B, T, H_kv;
     int l, d, l_sel, n_sel, n_init, n_local;
+    int max_seq_len, max_n_cmp;   // host-side bounds the lengths read from device memory are clamped to
     int nc_pitch;
     int max_blocks;          // capacity of the key array in LDS
     int share;               // 0: every query selects for itself; > 0: groups of `share` queries share a set
@@ -67,7 +68,8 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     const int x = (blockIdx.x / a.H_kv) % a.T;
     const int b = blockIdx.x / (a.H_kv * a.T);
 
-    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, s_par, s_depth, s_cmax,
+    const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, a.max_seq_len, a.max_n_cmp, s_par, s_depth,
+                                       s_cmax,
                                        s_anc);
     if (x >= sm.Tq) {
         if (tid < a.n_sel) a.sel_idx[(((int64_t)b * a.T + x) * a.H_kv + g) * a.n_sel + tid] = -1;

@@ -215,6 +215,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     sa.part_stats = part_stats; sa.part_acc = part_acc;
     sa.B = p->B; sa.T = p->T; sa.H = p->H; sa.H_kv = p->H_kv; sa.H_g = lo.H_g; sa.C = pl.C; sa.n_qg = pl.n_qg;
     sa.l = p->l; sa.d = p->d; sa.n_sel = p->n_sel; sa.w = p->w; sa.scale_log2 = scale_log2;
+    sa.max_seq_len = p->max_seq_len; sa.max_n_cmp = p->max_n_cmp;
     sa.n_cmp_chunks = pl.n_cmp_chunks; sa.n_win_splits = pl.n_win_splits; sa.n_slc_splits = pl.n_slc_splits;
     sa.min_tiles = pl.min_tiles_per_split;
     // rounded so that every LDS array behind them stays 16-byte aligned
@@ -259,7 +260,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         ia.part_stats = part_stats; ia.colsum = colsum;
         ia.B = p->B; ia.T = p->T; ia.H = p->H; ia.H_kv = p->H_kv; ia.H_g = lo.H_g; ia.C = lo.imp_C; ia.n_qg = lo.imp_n_qg;
         ia.share = pl.share_group;
-        ia.l = p->l; ia.d = p->d; ia.scale_log2 = scale_log2; ia.n_cmp_chunks = pl.n_cmp_chunks; ia.n_imp_chunks = lo.n_imp_chunks;
+        ia.l = p->l; ia.d = p->d; ia.max_seq_len = p->max_seq_len; ia.max_n_cmp = p->max_n_cmp; ia.scale_log2 = scale_log2; ia.n_cmp_chunks = pl.n_cmp_chunks; ia.n_imp_chunks = lo.n_imp_chunks;
         ia.n_wg = p->B * p->H_kv * lo.imp_n_qg * lo.n_imp_chunks; ia.nc_pitch = lo.nc_pitch; ia.rows_total = lo.rows_total;
         for (int j = 0; j < 3; ++j) ia.kc_s[j] = sa.kc_s[j];
         const int grid_i = ceil_div(ia.n_wg, 8) * 8;
@@ -273,6 +274,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         TopnArgs ta{};
         ta.colsum = colsum; ta.seq_lens = seq_lens; ta.n_cmp = n_cmp; ta.n_query = n_query; ta.parents = parents;
         ta.sel_idx = sel_idx; ta.B = p->B; ta.T = p->T; ta.H_kv = p->H_kv;
+        ta.max_seq_len = p->max_seq_len; ta.max_n_cmp = p->max_n_cmp;
         ta.l = p->l; ta.d = p->d; ta.l_sel = p->l_sel; ta.n_sel = p->n_sel; ta.n_init = p->n_init; ta.n_local = p->n_local;
         ta.nc_pitch = lo.nc_pitch; ta.max_blocks = lo.max_blocks; ta.share = ia.share;
         const size_t lds_topn = topn_lds_bytes(lo.max_blocks);

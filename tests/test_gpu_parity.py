@@ -250,3 +250,22 @@ def test_library_flattening_reorders_a_tree_without_changing_results(dev_mod, or
     _, _, out_d, sel_d = run_refresh(dev_mod, oracle, dfs)
     assert np.array_equal(sel_d[0], sel_b[0, perm])
     assert np.abs(out_d[0] - out_b[0, perm]).max() <= 2e-2
+
+
+def test_lengths_beyond_the_host_bounds_are_clamped(dev_mod, oracle):
+    """seq_lens / n_cmp entries larger than max_seq_len / max_n_cmp (what every buffer was sized with) are clamped on
+    the device instead of taking loads past the caches: the longest sequence then behaves as declared."""
+    import torch
+    case = si.make_case("clamp", "bf16", 2, 4, 32, 2, 192, 128, si.STD_NSA, [3000, 1200], 143, rho=0.5)
+    ref = oracle.nsa_verify(case)
+    dev = dev_mod.DeviceCase(case)
+    dev.seq_lens.copy_(torch.tensor([10 ** 6, 1200], dtype=torch.int32))
+    dev.n_cmp.copy_(torch.tensor([2 ** 30, int(case.n_cmp[1])], dtype=torch.int32))
+    dev.run()
+    out, sel = dev.results()
+    check(case, compare(case, oracle, ref, out, sel))
+    dev.seq_lens.copy_(torch.tensor([-5, 1200], dtype=torch.int32))      # negative: an empty context
+    dev.n_cmp.copy_(torch.tensor([-1, int(case.n_cmp[1])], dtype=torch.int32))
+    dev.run()
+    out2, sel2 = dev.results()
+    assert np.all(np.isfinite(out2)) and np.array_equal(out2[1], out[1]) and np.array_equal(sel2[1], sel[1])
