@@ -11,14 +11,22 @@
 // sums of probabilities, hence non-negative, and their IEEE bit patterns order like the values.
 //
 // Selection without a serial argmax loop: every thread owns the blocks j = tid (mod 256) and keeps
-// its best key.  The n_eff-th largest of the 256 per-thread bests is a lower bound of the n_eff-th
-// largest key overall, so every winner is >= that threshold; the (few) keys at or above it are
-// compacted into a candidate list and ranked by counting.  If the list overflows (massive ties), a
+// its best key.  The n_eff-th largest of the 64 per-thread bests of one wavefront is a lower bound of
+// the n_eff-th largest key overall (they are n_eff distinct keys), so every winner is >= the largest of
+// the four wavefronts' bounds; the (few) keys at or above it are compacted into a candidate list and
+// ranked by counting.  If the list overflows (massive ties), a
 // plain serial argmax over LDS takes over.
 #pragma once
 #include "device_common.hpp"
 
 namespace ssv {
+
+#ifdef SSV_CLOCKS   // development builds only: time stamps of the selection phases
+__device__ long long g_clk_topn[4096 * 8];
+#define SSV_TOPN_STAMP(i) do { if (threadIdx.x == 0 && wg < 4096) g_clk_topn[wg * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define SSV_TOPN_STAMP(i) do { } while (0)
+#endif
 
 struct TopnArgs {
     const float* colsum;     // [B, T, H_kv, nc_pitch]
@@ -64,6 +72,10 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     int* s_cmax = s_depth + kMaxT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#ifdef SSV_CLOCKS
+    const int wg = blockIdx.x;
+#endif
+    SSV_TOPN_STAMP(0);
     const int g = blockIdx.x % a.H_kv;
     const int x = (blockIdx.x / a.H_kv) % a.T;
     const int b = blockIdx.x / (a.H_kv * a.T);
@@ -71,6 +83,7 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, a.max_seq_len, a.max_n_cmp, s_par, s_depth,
                                        s_cmax,
                                        s_anc);
+    SSV_TOPN_STAMP(1);
     if (x >= sm.Tq) {
         if (tid < a.n_sel) a.sel_idx[(((int64_t)b * a.T + x) * a.H_kv + g) * a.n_sel + tid] = -1;
         return;
@@ -89,13 +102,24 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     const float* cs = a.colsum + (((int64_t)b * a.T + i) * a.H_kv + g) * a.nc_pitch;
     const int n_eff = min(a.n_sel, J + 1);
     if (tid == 0) s_red[1] = 0;     // candidate counter
+    if (tid < 4) s_red[12 + tid] = 0;   // per-wavefront thresholds
 
     // imp[j] = sum_delta wt[delta] * colsum[a_ratio * j + delta], delta in [-(b_ratio-1), a_ratio-1], where wt counts
     // the (m, n') pairs with m - n' = delta.  Loads are unconditional (clamped column, zero weight) and issued
     // for several blocks at once so that they are in flight together.
     const int n_terms = a_ratio + b_ratio - 1;
     uint64_t best = 0;   // best key among the blocks owned by this thread (index % 256 == tid)
-    for (int j0 = tid; j0 <= J; j0 += kThreads * kBlocksPerBatch) {
+    // The trailing local blocks are forced and need no importance: leaving them out of the load loop saves a
+    // whole batch of loads whenever J + 1 is just above a multiple of the batch (contexts of 2^k tokens).
+    const int j_last_scored = J - max(a.n_local, 0);
+    for (int j = max(j_last_scored + 1, 0); j <= J; ++j) {
+        if ((j % kThreads) == tid) {          // the owner of block j
+            const uint64_t key = ((uint64_t)0x7F800000u << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
+            s_key[j] = key;
+            best = key > best ? key : best;
+        }
+    }
+    for (int j0 = tid; j0 <= j_last_scored; j0 += kThreads * kBlocksPerBatch) {
         float imp[kBlocksPerBatch];
         if (n_terms <= kMaxImpTerms) {
             float x[kBlocksPerBatch][kMaxImpTerms];
@@ -131,8 +155,8 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
 #pragma unroll
         for (int v = 0; v < kBlocksPerBatch; ++v) {
             const int j = j0 + v * kThreads;
-            if (j <= J) {
-                const bool forced = j < a.n_init || j > J - a.n_local;
+            if (j <= j_last_scored) {
+                const bool forced = j < a.n_init;
                 const uint32_t bits = forced ? 0x7F800000u : __float_as_uint(imp[v]);
                 const uint64_t key = ((uint64_t)bits << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
                 s_key[j] = key;
@@ -141,17 +165,23 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
         }
     }
     s_best[tid] = best;
+    SSV_TOPN_STAMP(2);
     __syncthreads();
 
-    // threshold: the n_eff-th largest per-thread best (keys are distinct; threads without blocks hold 0)
+    // threshold: per wavefront, the n_eff-th largest of its per-thread bests (keys are distinct; threads without
+    // blocks hold 0; a wavefront with fewer than n_eff keys leaves 0)
     {
         int rank = 0;
+        const uint64_t* wb = s_best + wave * 64;
 #pragma unroll 16
-        for (int k = 0; k < kThreads; ++k) rank += s_best[k] > best;   // broadcast LDS reads, 16 in flight
-        if (best != 0 && rank == n_eff - 1) s_red[0] = best;
+        for (int k = 0; k < 64; ++k) rank += wb[k] > best;   // broadcast LDS reads, 16 in flight
+        if (best != 0 && rank == n_eff - 1) s_red[12 + wave] = best;
     }
     __syncthreads();
-    const uint64_t thr = s_red[0];
+    SSV_TOPN_STAMP(3);
+    uint64_t thr = s_red[12];
+#pragma unroll
+    for (int k = 1; k < 4; ++k) thr = s_red[12 + k] > thr ? s_red[12 + k] : thr;
     for (int j = tid; j <= J; j += kThreads) {
         const uint64_t key = s_key[j];
         if (key >= thr) {
@@ -160,6 +190,7 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
         }
     }
     __syncthreads();
+    SSV_TOPN_STAMP(4);
     const int n_cand = (int)*reinterpret_cast<unsigned*>(&s_red[1]);
     if (n_cand <= kMaxCand) {
         // rank candidates by counting; ranks below n_eff are the selection
@@ -197,6 +228,7 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
         }
     }
     __syncthreads();
+    SSV_TOPN_STAMP(5);
     // ascending order: pick e goes to position (number of smaller picks); picks are distinct
     if (tid < a.n_sel) {
         int pick = 0x7fffffff, rank = tid;   // threads beyond n_eff write the -1 padding at their own position
@@ -212,6 +244,7 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
         for (int m = m0; m < m1; ++m)
             a.sel_idx[(((int64_t)b * a.T + m) * a.H_kv + g) * a.n_sel + rank] = tid < n_eff ? pick : -1;
     }
+    SSV_TOPN_STAMP(6);
 }
 
 }  // namespace ssv

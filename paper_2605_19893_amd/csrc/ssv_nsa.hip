@@ -465,6 +465,9 @@ int ssv_nsa_version(void) { return 1; }
 
 #ifdef SSV_CLOCKS
 // development builds only: copy the in-kernel time stamps of the last k_stream launch to the host
+int ssv_debug_read_clocks_topn(long long* host_out, int n) {
+    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ssv::g_clk_topn), sizeof(long long) * n) == hipSuccess ? 0 : -1;
+}
 int ssv_debug_read_clocks(long long* host_out, int n) {
     return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ssv::g_clk), sizeof(long long) * n) == hipSuccess ? 0 : -1;
 }
