@@ -269,3 +269,22 @@ def test_lengths_beyond_the_host_bounds_are_clamped(dev_mod, oracle):
     dev.run()
     out2, sel2 = dev.results()
     assert np.all(np.isfinite(out2)) and np.array_equal(out2[1], out[1]) and np.array_equal(sel2[1], sel[1])
+
+
+def test_massive_ties_take_the_smallest_indices(dev_mod, oracle):
+    """Identical keys everywhere: uniform compressed probabilities, every interior block has the same importance,
+    and the tie rule (smaller index wins) decides the whole selection; more than 512 tied candidates also drive
+    the top-n kernel through its serial path."""
+    case = si.make_case("ties", "bf16", 1, 3, 16, 1, 192, 128, si.STD_NSA, [40000], 147, rho=0.2)
+    row = case.k[0, 0, 5].copy()
+    case.k[0, 0, :] = row
+    case.k_cmp[0, 0, :] = row          # the mean of identical rows
+    ref = oracle.nsa_verify(case)
+    J = 40000 // 64
+    for i in range(3):
+        assert ref.sel_idx[0, i, 0].tolist() == list(range(14)) + [J - 1, J]
+    dev = dev_mod.DeviceCase(case)
+    dev.run()
+    out, sel = dev.results()
+    assert np.array_equal(sel, ref.sel_idx)
+    check(case, compare(case, oracle, ref, out, sel))
