@@ -3,10 +3,13 @@
 // input dtype (round-to-nearest-even for bf16).
 //   o_branch = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) Z_s,   out = g_cmp o_cmp + g_slc o_slc + g_win o_win
 //
-// One workgroup per output row.  Wavefronts 0..2 each take one branch: lane = slice, one load of the
-// (m, Z) pair, wave-wide max and sum, and the per-slice weight gate * 2^(m - M) / Z_total goes to LDS.
-// Then all 256 threads accumulate weight * partial accumulator, (256 / (d_v/4)) slices in parallel with
-// independent loads, and a small LDS reduction produces the row.
+// Two layouts.  k_combine_rows (few slices per row, many rows): a group of d_v/4 threads owns one output row (four
+// columns per thread), eight or sixteen rows per workgroup, no cross-thread reduction: every thread of the group
+// first folds the (m, Z) pairs of each branch's slices into the branch maximum and total (the loads of a group hit
+// the same addresses), then accumulates gate * 2^(m - M) / Z_total * partial accumulator over the slices, four
+// independent loads in flight.  k_combine_slices (many slices per row): one workgroup per output row; wavefronts
+// 0..2 each take one branch with one lane per slice (wave-wide max and sum), then all 256 threads accumulate
+// weight * partial accumulator, 256 / (d_v/4) slices in parallel, and a small LDS reduction produces the row.
 #pragma once
 #include "device_common.hpp"
 
@@ -23,6 +26,74 @@ struct CombineArgs {
 
 constexpr int kMaxSlotsPerBranch = 64;
 
+template <bool BF16, int DV>
+__global__ void __launch_bounds__(kThreads) k_combine_rows(const CombineArgs a) {
+    constexpr int TPR = DV / 4;                 // threads across one row, 4 columns each
+    constexpr int RPW = kThreads / TPR;         // rows per workgroup
+    const int tid = threadIdx.x;
+    const int64_t row = (int64_t)blockIdx.x * RPW + tid / TPR;
+    if (row >= a.rows_total) return;
+    const int c = tid % TPR;
+    const int i = (int)((row / a.H) % a.T);
+    const int b = (int)(row / ((int64_t)a.H * a.T));
+    const int Tq = a.n_query ? min(max(a.n_query[b], 0), a.T) : a.T;
+
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (i < Tq) {
+        // slot ranges: cmp [0, n_cmp), win [n_cmp, n_cmp + n_win), slc after; gate order: cmp, slc, win
+        const int lo3[3] = {0, a.n_cmp_chunks + a.n_win_splits, a.n_cmp_chunks};
+        const int cnt3[3] = {a.n_cmp_chunks, a.n_slc_splits, a.n_win_splits};
+#pragma unroll
+        for (int br = 0; br < 3; ++br) {
+            const int lo = lo3[br], cnt = cnt3[br];
+            const float* st_base = a.part_stats + ((int64_t)lo * a.rows_total + row) * 2;
+            // branch maximum and total, one pass with a running maximum (slices that saw no key have Z = 0)
+            float M = -INFINITY, Zt = 0.f;
+            for (int s0 = 0; s0 < cnt; s0 += 4) {
+                float2 st[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    st[u] = *reinterpret_cast<const float2*>(st_base + (int64_t)min(s0 + u, cnt - 1) * a.rows_total * 2);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (s0 + u < cnt && st[u].y > 0.f) {
+                        const float Mn = fmaxf(M, st[u].x);
+                        Zt = Zt * fast_exp2(M - Mn) + st[u].y * fast_exp2(st[u].x - Mn);
+                        M = Mn;
+                    }
+                }
+            }
+            if (!(Zt > 0.f)) continue;
+            const float scale = a.gates[row * 3 + br] / Zt;
+            for (int s0 = 0; s0 < cnt; s0 += 4) {
+                float w[4];
+                f32x4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int s = min(s0 + u, cnt - 1);
+                    const float2 st = *reinterpret_cast<const float2*>(st_base + (int64_t)s * a.rows_total * 2);
+                    w[u] = (s0 + u < cnt && st.y > 0.f) ? scale * fast_exp2(st.x - M) : 0.f;
+                    // slices that contributed nothing never wrote their accumulator: read slice 0's memory instead
+                    // (always mapped) and discard it, so that the load stays unconditional
+                    const int64_t pr = (int64_t)(w[u] != 0.f ? lo + s : 0) * a.rows_total + row;
+                    v[u] = *reinterpret_cast<const f32x4*>(a.part_acc + pr * DV + c * 4);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (w[u] != 0.f) acc += w[u] * v[u];
+            }
+        }
+    }
+    if constexpr (BF16) {
+        __bf16 h[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = (__bf16)acc[e];
+        *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.out) + (row * DV + c * 4) * 2) = *reinterpret_cast<u32x2*>(h);
+    } else {
+        *reinterpret_cast<f32x4*>(reinterpret_cast<char*>(a.out) + (row * DV + c * 4) * 4) = acc;
+    }
+}
+
 __device__ __forceinline__ float wave_max_f32(float v) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
@@ -35,7 +106,7 @@ __device__ __forceinline__ float wave_sum_f32(float v) {
 }
 
 template <bool BF16, int DV>
-__global__ void __launch_bounds__(kThreads) k_combine(const CombineArgs a) {
+__global__ void __launch_bounds__(kThreads) k_combine_slices(const CombineArgs a) {
     constexpr int TPR = DV / 4;                 // threads across one row, 4 columns each
     constexpr int SL = kThreads / TPR;          // slices accumulated in parallel
     __shared__ float s_w[3 * kMaxSlotsPerBranch];

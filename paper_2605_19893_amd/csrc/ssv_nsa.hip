@@ -126,7 +126,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     pl.n_cmp_chunks = env_int("SSV_CMP_CHUNKS", n_c);
     pl.n_win_splits = env_int("SSV_WIN_SPLITS", n_w);
     pl.n_slc_splits = env_int("SSV_SLC_SPLITS", n_s);
-    pl.n_cmp_chunks = std::min(pl.n_cmp_chunks, kMaxSlotsPerBranch);   // one lane per slice in the combine kernel
+    pl.n_cmp_chunks = std::min(pl.n_cmp_chunks, kMaxSlotsPerBranch);   // keeps the per-row slice loops of the combine kernel short
     pl.n_win_splits = std::min(pl.n_win_splits, 32);
     pl.n_slc_splits = std::min(pl.n_slc_splits, 32);
     pl.tiles_per_chunk = ceil_div(ntc, pl.n_cmp_chunks);
@@ -295,10 +295,16 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     ca.part_stats = part_stats; ca.part_acc = part_acc; ca.gates = gates; ca.n_query = n_query; ca.out = out;
     ca.T = p->T; ca.H = p->H; ca.n_cmp_chunks = pl.n_cmp_chunks; ca.n_win_splits = pl.n_win_splits;
     ca.n_slc_splits = pl.n_slc_splits; ca.rows_total = lo.rows_total;
-    const int grid_c = (int)lo.rows_total;   // one workgroup per output row
+    // few slices per row: thread groups own rows; many slices: one workgroup per row, slices in parallel
+    const bool by_rows = pl.n_slots <= env_int("SSV_COMBINE_ROWS_MAX_SLOTS", 12);
+    const int rows_per_wg = kThreads / (DV / 4);
+    const int grid_c = by_rows ? (int)((lo.rows_total + rows_per_wg - 1) / rows_per_wg) : (int)lo.rows_total;
     if (tm.begin(SSV_T_EVENT_PAIR) || tm.end(SSV_T_EVENT_PAIR)) return SSV_ELAUNCH;   // empty pair: the overhead itself
     if (tm.begin(SSV_K_COMBINE)) return SSV_ELAUNCH;
-    for (int r = 0; r < reps; ++r) hipLaunchKernelGGL((k_combine<BF16, DV>), dim3(grid_c), dim3(kThreads), 0, stream, ca);
+    for (int r = 0; r < reps; ++r) {
+        if (by_rows) hipLaunchKernelGGL((k_combine_rows<BF16, DV>), dim3(grid_c), dim3(kThreads), 0, stream, ca);
+        else hipLaunchKernelGGL((k_combine_slices<BF16, DV>), dim3(grid_c), dim3(kThreads), 0, stream, ca);
+    }
     if (hipGetLastError() != hipSuccess || tm.end(SSV_K_COMBINE)) return SSV_ELAUNCH;
     return SSV_OK;
 }
