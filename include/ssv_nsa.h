@@ -51,7 +51,7 @@ extern "C" {
 #define SSV_REUSE   1
 #define SSV_REFRESH_SHARED 2  /* approximate: every group of C queries uses its representative's indices */
 
-#define SSV_MAX_T 64          /* verifier queries per sequence */
+#define SSV_MAX_T 128         /* verifier queries per sequence */
 
 /* kernels of one call, in launch order (indices into kernel_ms of ssv_nsa_verify_timed) */
 #define SSV_K_STREAM_A  0     /* refresh: compressed scan + window;  reuse: compressed + window + selected */
@@ -76,7 +76,7 @@ typedef struct ssv_nsa_params {
     int32_t n_local;      /* forced blocks ending at the block of the query's own slot */
     int32_t dtype;        /* SSV_F32 or SSV_BF16: type of q, k, v, k_cmp, v_cmp, out */
     int32_t mode;         /* SSV_REFRESH, SSV_REFRESH_SHARED: sel_idx is written; SSV_REUSE: sel_idx is read */
-    int32_t group_size;   /* SSV_REFRESH, SSV_REUSE: C, verifier queries per workgroup (C * H_g <= 128); 0 = auto
+    int32_t group_size;   /* SSV_REFRESH, SSV_REUSE: C, verifier queries per workgroup (C <= 64, C * H_g <= 128); 0 = auto
                              (C * H_g <= 64); never changes the result.  SSV_REFRESH_SHARED: queries per index-sharing
                              group (1..T; 0 = the automatic C); the workgroup grouping is then the automatic one */
     float   scale;        /* softmax scale; 0 => 1/sqrt(d_k) */

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libssv_nsa.so")
 SSV_OK, SSV_EINVAL, SSV_EUNSUPPORTED, SSV_EWORKSPACE, SSV_ELAUNCH = 0, -1, -2, -3, -4
 SSV_F32, SSV_BF16 = 0, 1
 SSV_REFRESH, SSV_REUSE, SSV_REFRESH_SHARED = 0, 1, 2
-SSV_MAX_T = 64
+SSV_MAX_T = 128
 SSV_K_STREAM_A, SSV_K_IMPORTANCE, SSV_K_TOPN, SSV_K_STREAM_B, SSV_K_COMBINE = range(5)
 SSV_NUM_KERNELS = 5
 SSV_T_EVENT_PAIR, SSV_NUM_TIMINGS = 5, 6

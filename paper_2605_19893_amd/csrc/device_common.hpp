@@ -13,7 +13,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;   // 4 wavefronts of 64 lanes
 constexpr int kTile = 64;       // KV rows per streamed tile (= one selection block)
-constexpr int kMaxT = 64;
+constexpr int kMaxT = 128;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -215,8 +215,13 @@ struct TransposedTileRegs {
 
 // Number of compressed rows a query may use: complete windows inside the contiguous visible
 // extent E = L + (leading run of visible draft slots), capped by the rows that exist.
-__device__ __forceinline__ int visible_cmp_rows(uint64_t anc, int L, int n_cmp, int l, int d) {
-    const int lead = (~anc == 0ull) ? 64 : __builtin_ctzll(~anc);
+// Set of draft tokens (flattened indices 0..127): a query's ancestors and itself.
+struct AncSet {
+    uint64_t lo, hi;     // tokens 0..63, 64..127
+};
+
+__device__ __forceinline__ int visible_cmp_rows(AncSet anc, int L, int n_cmp, int l, int d) {
+    const int lead = (~anc.lo != 0ull) ? __builtin_ctzll(~anc.lo) : 64 + ((~anc.hi != 0ull) ? __builtin_ctzll(~anc.hi) : 64);
     const int E = L + lead;
     const int full = E >= l ? (E - l) / d + 1 : 0;
     return min(full, n_cmp);
@@ -234,7 +239,7 @@ struct SeqMeta {
 // an inconsistent length array cannot take a load past the end of a cache.
 __device__ __forceinline__ SeqMeta build_tree_meta(int tid, int b, int T, const int32_t* seq_lens, const int32_t* n_query,
                                                    const int32_t* n_cmp, const int32_t* parents, int l, int d, int max_seq_len,
-                                                   int max_n_cmp, int* s_par, int* s_depth, int* s_cmax, uint64_t* s_anc) {
+                                                   int max_n_cmp, int* s_par, int* s_depth, int* s_cmax, AncSet* s_anc) {
     SeqMeta sm;
     sm.L = min(max(seq_lens[b], 0), max_seq_len);
     sm.Tq = n_query ? min(max(n_query[b], 0), T) : T;
@@ -251,16 +256,17 @@ __device__ __forceinline__ SeqMeta build_tree_meta(int tid, int b, int T, const 
         __syncthreads();
     }
     if (tid < kMaxT) {
-        uint64_t anc = 0;
+        AncSet anc = {0ull, 0ull};
         int dep = 0;
         if (tid < sm.Tq) {
             if (!parents) {
-                anc = (tid == 63) ? ~0ull : ((2ull << tid) - 1ull);
+                anc.lo = (tid >= 63) ? ~0ull : ((2ull << tid) - 1ull);
+                anc.hi = (tid < 64) ? 0ull : ((tid == 127) ? ~0ull : ((2ull << (tid - 64)) - 1ull));
                 dep = tid;
             } else {
                 int t = tid;
                 while (t >= 0) {        // strictly decreasing: at most tid + 1 steps
-                    anc |= 1ull << t;
+                    if (t < 64) anc.lo |= 1ull << t; else anc.hi |= 1ull << (t - 64);
                     const int pn = s_par[t];
                     if (pn >= 0) ++dep;
                     t = pn;

@@ -44,7 +44,7 @@ struct ImportanceCfg {
     static constexpr int LDS_K = kTile * KP;
     // LDS bytes: K tile, merged row statistics, per-sequence tree metadata and routed-query list, then the
     // head-summed tile [C][64]
-    static constexpr int lds_bytes(int C) { return LDS_K + 256 * 8 + kMaxT * 24 + 64 + C * kTile * 4; }
+    static constexpr int lds_bytes(int C) { return LDS_K + 256 * 8 + kMaxT * 32 + 64 + C * kTile * 4; }
 };
 
 template <bool BF16, int DK, int NRT>
@@ -54,7 +54,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     extern __shared__ __align__(16) char smem[];
     char* sK = smem;
     float2* s_stat = reinterpret_cast<float2*>(sK + Cfg::LDS_K);   // [128] (M, 1/Z) per workgroup row
-    uint64_t* s_anc = reinterpret_cast<uint64_t*>(s_stat + 256);
+    AncSet* s_anc = reinterpret_cast<AncSet*>(s_stat + 256);
     int* s_par = reinterpret_cast<int*>(s_anc + kMaxT);
     int* s_depth = s_par + kMaxT;
     int* s_cmax = s_depth + kMaxT;

@@ -52,7 +52,7 @@ __host__ __device__ inline size_t stream_lds_bytes(size_t lds_k, size_t lds_vt, 
     n += (size_t)max_sched * 8;          // ownership masks
     n += (size_t)max_sched * 4;          // block ids
     n += (size_t)bitmap_words * 4 * 2;   // bitmap + prefix
-    n += kMaxT * 8 + kMaxT * 4 * 3 + kTile * 4 + 16; // anc, par, depth, cmax, key positions, scalars
+    n += kMaxT * 16 + kMaxT * 4 * 3 + kTile * 4 + 16; // anc, par, depth, cmax, key positions, scalars
     return (n + 15) & ~(size_t)15;
 }
 
@@ -94,7 +94,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     char* sK = smem;
     char* sVT = sK + Cfg::LDS_K;
     uint64_t* s_own = reinterpret_cast<uint64_t*>(sVT + Cfg::LDS_VT);
-    uint64_t* s_anc = s_own + a.max_sched;
+    AncSet* s_anc = reinterpret_cast<AncSet*>(s_own + a.max_sched);
     int* s_id = reinterpret_cast<int*>(s_anc + kMaxT);
     uint32_t* s_bitmap = reinterpret_cast<uint32_t*>(s_id + a.max_sched);
     uint32_t* s_prefix = s_bitmap + a.bitmap_words;
@@ -137,7 +137,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
 
     // ---- per-lane row metadata
     bool rvalid[NRT];
-    uint64_t anc[NRT];
+    AncSet anc[NRT];
     int pos[NRT], cmax[NRT], iq[NRT];
     int64_t grow[NRT];
 #pragma unroll
@@ -147,7 +147,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         const int qi = qg * a.C + iq[t];
         rvalid[t] = iq[t] < nq_grp;
         const int qs = rvalid[t] ? qi : 0;
-        anc[t] = rvalid[t] ? s_anc[qs] : 0ull;
+        anc[t] = rvalid[t] ? s_anc[qs] : AncSet{0ull, 0ull};
         pos[t] = L + s_depth[qs];
         cmax[t] = rvalid[t] ? s_cmax[qs] : 0;
         grow[t] = ((int64_t)b * a.T + qs) * a.H + g * a.H_g + rr % a.H_g;
@@ -342,8 +342,12 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
                 } else {
                     // visibility of the tile's 64 slots as one bit mask: committed slots, then the ancestor bits
                     const int cl = L - base;      // committed slots at the front of the tile (< 64 here; may be <= 0)
-                    const uint64_t vis = cl > 0 ? (((1ull << cl) - 1ull) | (anc[t] << cl))
-                                                : (-cl < 64 ? anc[t] >> (-cl) : 0ull);
+                    uint64_t vis;                 // (uniform branches: cl is the same for the whole workgroup)
+                    if (cl > 0) vis = ((1ull << cl) - 1ull) | (anc[t].lo << cl);
+                    else if (cl == 0) vis = anc[t].lo;
+                    else if (cl > -64) vis = (anc[t].lo >> (-cl)) | (anc[t].hi << (64 + cl));
+                    else if (cl == -64) vis = anc[t].hi;
+                    else vis = cl > -128 ? anc[t].hi >> (-cl - 64) : 0ull;
 #pragma unroll
                     for (int kt = 0; kt < 4; ++kt) vm[t] |= (uint32_t)((vis >> (16 * kt + 4 * G)) & 0xFull) << (4 * kt);
                     if (r_win) {

@@ -56,7 +56,7 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
 }
 
 __host__ __device__ inline size_t topn_lds_bytes(int max_blocks) {
-    return (size_t)max_blocks * 8 + kThreads * 8 + kMaxCand * 8 + 16 * 8 + kMaxNSel * 4 + kMaxT * 20 + 64;
+    return (size_t)max_blocks * 8 + kThreads * 8 + kMaxCand * 8 + 16 * 8 + kMaxNSel * 4 + kMaxT * 28 + 64;
 }
 
 __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
@@ -66,7 +66,7 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     uint64_t* s_cand = s_best + kThreads;                                 // [kMaxCand]
     uint64_t* s_red = s_cand + kMaxCand;                                  // [16]: threshold, counter, argmax scratch
     int* s_pick = reinterpret_cast<int*>(s_red + 16);                     // [kMaxNSel]
-    uint64_t* s_anc = reinterpret_cast<uint64_t*>(s_pick + kMaxNSel);
+    AncSet* s_anc = reinterpret_cast<AncSet*>(s_pick + kMaxNSel);
     int* s_par = reinterpret_cast<int*>(s_anc + kMaxT);
     int* s_depth = s_par + kMaxT;
     int* s_cmax = s_depth + kMaxT;

@@ -64,7 +64,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
             if (j == 2 && strides[a][j] < dims[a]) return SSV_EINVAL;
         }
     const bool shared = p->mode == SSV_REFRESH_SHARED;
-    const int c_max = shared ? p->T : std::min(p->T, 128 / H_g);
+    const int c_max = shared ? p->T : std::min(p->T, std::min(64, 128 / H_g));   // ownership masks hold 64 queries
     if (p->group_size > c_max) return SSV_EINVAL;
     const int max_blocks = (p->max_seq_len + p->T) / p->l_sel + 1;
     if (max_blocks > 16384) return SSV_EUNSUPPORTED;
@@ -226,6 +226,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     }
     const size_t lds_stream = stream_lds_bytes(SC::LDS_K, SC::LDS_VT, sa.max_sched, sa.bitmap_words);
     const int units = p->B * p->H_kv * pl.n_qg;
+    if (lds_stream > 64 * 1024) return SSV_EUNSUPPORTED;     // merged schedules of very large groups do not fit
 
     const int reps = tm.on ? tm.repeats : 1;
     auto launch_stream = [&](int slot_lo, int slot_cnt) -> int {

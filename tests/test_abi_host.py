@@ -57,7 +57,7 @@ def test_supported_shapes():
     (dict(w=0), B.SSV_EINVAL), (dict(avg_seq_len=40000), B.SSV_EINVAL), (dict(group_size=9), B.SSV_EINVAL), (dict(scale=-1.0), B.SSV_EINVAL),
     (dict(k_stride=(1, 1, 100)), B.SSV_EINVAL), (dict(k_stride=(4 * 32832 * 192, 32832 * 192, 196)), B.SSV_EINVAL),
     (dict(mode=B.SSV_REFRESH_SHARED, group_size=9), B.SSV_EINVAL),
-    (dict(T=65), B.SSV_EUNSUPPORTED), (dict(H=96, H_kv=4), B.SSV_EUNSUPPORTED), (dict(l_sel=128), B.SSV_EUNSUPPORTED),
+    (dict(T=129), B.SSV_EUNSUPPORTED), (dict(H=96, H_kv=4), B.SSV_EUNSUPPORTED), (dict(l_sel=128), B.SSV_EUNSUPPORTED),
     (dict(d_k=96), B.SSV_EUNSUPPORTED), (dict(n_sel=40), B.SSV_EUNSUPPORTED),
     (dict(max_seq_len=2 ** 21), B.SSV_EUNSUPPORTED),
 ])

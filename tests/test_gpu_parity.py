@@ -288,3 +288,22 @@ def test_massive_ties_take_the_smallest_indices(dev_mod, oracle):
     out, sel = dev.results()
     assert np.array_equal(sel, ref.sel_idx)
     check(case, compare(case, oracle, ref, out, sel))
+
+
+@pytest.mark.parametrize("shape", ["chain_hg4", "chain_hg16", "tree_bfs", "tree_dfs"])
+def test_up_to_128_verifier_queries(dev_mod, oracle, shape):
+    """Draft budgets above 64 tokens (the paper goes to 128): ancestor sets span two machine words and the draft
+    slots span up to three key tiles."""
+    if shape == "chain_hg4":
+        case = si.make_case("t128_chain", "bf16", 2, 128, 32, 8, 64, 64, si.STD_NSA, [4000 + 21, 2999], 149, rho=0.5,
+                            n_query=[128, 97])
+    elif shape == "chain_hg16":
+        case = si.make_case("t100_chain", "bf16", 1, 100, 16, 1, 192, 128, si.STD_NSA, [3000 + 40], 151, rho=0.5)
+    else:
+        par = si.tree_parents((4, 3, 3, 2), shape[5:])      # 4 + 12 + 36 + 72 = 124 nodes
+        case = si.make_case(f"t124_{shape}", "bf16", 2, len(par), 32, 8, 64, 64, si.STD_NSA, [4096 - 30, 2048 + 7], 153,
+                            rho=0.6, parents=par, n_query=[len(par), 70])
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+    if shape == "tree_dfs":
+        run_shared(dev_mod, oracle, case, 4)

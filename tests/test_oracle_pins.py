@@ -375,3 +375,20 @@ def test_bf16_inputs_are_read_exactly(oracle):
         getattr(as_f32, name)[...] = si.bf16_bits_to_f32(getattr(case, name))
     as_f32.gates[...] = case.gates
     np.testing.assert_allclose(oracle.nsa_verify(case).out, oracle.nsa_verify(as_f32).out, rtol=0, atol=0)
+
+
+def test_more_than_64_verifier_queries_match_brute_force(oracle):
+    """Draft budgets beyond one machine word of ancestor bits: a 70-token chain and a 78-node tree."""
+    nsa = si.NsaParams(l=8, d=4, l_sel=16, n_sel=4, w=24)
+    chain = tiny_case(91, L=90, T=70, nsa=nsa, H=2, H_kv=1)
+    r = oracle.nsa_verify(chain, branches=True)
+    out, sel, br, _ = brute_force_verify(chain)
+    assert np.array_equal(sel, r.sel_idx)
+    np.testing.assert_allclose(r.out, out, rtol=0, atol=1e-12)
+    par = si.tree_parents((2, 2, 3, 2), "dfs")       # 2 + 4 + 12 + 24 = 42 ... extended below
+    par = np.concatenate([par, par[:36] + np.where(par[:36] >= 0, len(par), 0)]).astype(np.int32)   # a second copy of a subtree
+    tree = tiny_case(93, L=75, T=len(par), nsa=nsa, H=2, H_kv=1, parents=par)
+    r = oracle.nsa_verify(tree, branches=True)
+    out, sel, br, _ = brute_force_verify(tree)
+    assert len(par) > 64 and np.array_equal(sel, r.sel_idx)
+    np.testing.assert_allclose(r.out, out, rtol=0, atol=1e-12)
