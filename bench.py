@@ -419,7 +419,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards over sequences and KV heads without communication; see DESIGN.md)", file=sys.stderr)
+              "(sequences and KV heads are independent: more GPUs would each take a share of them, with no exchange)", file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
