@@ -78,9 +78,10 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     pl.share_group = shared ? (p->group_size ? p->group_size : pl.C) : 0;
     pl.n_qg = ceil_div(p->T, pl.C);
     pl.rows_per_wg = pl.C * H_g;
-    // Split plan.  A launch should fill the chip once with resident workgroups (LDS and registers allow
-    // 3 per CU with one row tile per wave, 2 with two), so the key tiles of a (sequence, head, query group)
-    // are cut into about capacity / units slices, but never below min_tiles tiles per slice.
+    // Split plan.  A launch should fill the chip once with resident workgroups (LDS and registers allow two per
+    // CU), so the key tiles of a (sequence, head, query group) are cut into about capacity / units slices, but
+    // never below min_tiles tiles per slice.  Small problems take one workgroup per CU instead (a workgroup that
+    // has its CU to itself runs a tile in 2.3 us instead of 3.3): when that leaves slices of at most four tiles.
     const int units = p->B * p->H_kv * pl.n_qg;
     const int nrt = pl.rows_per_wg > 64 ? 2 : 1;
     const int capacity = env_int("SSV_CAPACITY", 256 * 2);
@@ -101,9 +102,10 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // a mixed-length batch, stays bounded (12-tile slices balanced better but cost 5-10 % at the 128K-context
     // configurations: twice the partial states to write and merge, twice the per-workgroup start-up).
     auto tiles_per_slice = [&](const int* tiles, int n_roles) {
-        const int spu = std::max(n_roles, capacity / units);      // slices per unit one round can hold
         int total = 0;
         for (int r = 0; r < n_roles; ++r) total += tiles[r];
+        int spu = std::max(n_roles, (capacity / 2) / units);      // slices per unit one round can hold, one workgroup per CU
+        if (std::max(mt, ceil_div(total, spu)) > 4) spu = std::max(n_roles, capacity / units);   // two per CU
         int per = std::max(mt, ceil_div(total, spu));
         if (per > 24) return env_int("SSV_LONG_SLICE", 24);
         for (;; ++per) {
@@ -217,7 +219,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     sa.l = p->l; sa.d = p->d; sa.n_sel = p->n_sel; sa.w = p->w; sa.scale_log2 = scale_log2;
     sa.max_seq_len = p->max_seq_len; sa.max_n_cmp = p->max_n_cmp;
     sa.n_cmp_chunks = pl.n_cmp_chunks; sa.n_win_splits = pl.n_win_splits; sa.n_slc_splits = pl.n_slc_splits;
-    sa.min_tiles = pl.min_tiles_per_split;
+    sa.min_tiles = 1;     // inside a launch the used slices share the tiles evenly, down to one tile each
     // rounded so that every LDS array behind them stays 16-byte aligned
     sa.max_sched = (pl.max_sched_entries + 3) & ~3; sa.bitmap_words = (lo.bitmap_words + 1) & ~1; sa.rows_total = lo.rows_total;
     for (int j = 0; j < 3; ++j) {
