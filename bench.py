@@ -99,6 +99,37 @@ def time_calls(torch, devs, steps, warmup):
     return ev0.elapsed_time(ev1) / steps, wall_ms / steps
 
 
+def time_graph_replays(torch, devs, steps, warmup):
+    """The same calls recorded once into HIP graphs (one per input copy) and replayed: what a serving loop that
+    captures its verification step would see."""
+    side = torch.cuda.Stream()
+    graphs = []
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for d in devs:
+            d.run()
+        side.synchronize()
+        for d in devs:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                d.run()
+            graphs.append(g)
+    torch.cuda.synchronize()
+    n = len(graphs)
+    for s in range(warmup):
+        graphs[s % n].replay()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for s in range(steps):
+        graphs[s % n].replay()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return ev0.elapsed_time(ev1) / steps, wall_ms / steps
+
+
 def kernel_breakdown(devs, rounds, repeats):
     """Average launch duration (ms) of every kernel, measured with HIP events inside the library on the call's
     stream.  repeats == 1: one launch per event pair, rotating over the input copies (cold caches); the
@@ -155,6 +186,7 @@ def measure_workload(torch, oracle, case, name, tag, steps, warmup, n_copies, pa
                 d.set_sel_idx(ref.sel_idx)
         cold_ms, cold_wall = time_calls(torch, devs, steps, warmup)
         warm_ms, _ = time_calls(torch, devs[:1], steps, warmup)
+        graph_ms, graph_wall = time_graph_replays(torch, devs, steps, warmup)
         kms = kernel_breakdown(devs, 8, 1)
         kms_rep = kernel_breakdown(devs[:1], 2, 20)
         raw[mname] = kms
@@ -162,6 +194,7 @@ def measure_workload(torch, oracle, case, name, tag, steps, warmup, n_copies, pa
         out_modes[mname] = {
             "plan": devs[0].plan.as_dict(),
             "us_per_call_cold": cold_ms * 1e3, "us_per_call_warm": warm_ms * 1e3, "us_per_call_cold_wallclock": cold_wall * 1e3,
+            "us_per_call_cold_graph_replay": graph_ms * 1e3, "us_per_call_cold_graph_replay_wallclock": graph_wall * 1e3,
             "tokens_per_s_cold": tokens / (cold_ms * 1e-3), "tokens_per_s_warm": tokens / (warm_ms * 1e-3),
             "algorithmic_GBs_cold": ab["total"] / (cold_ms * 1e-3) / 1e9,
             "hbm_frac_whole_call_cold": ab["total"] / (cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -307,3 +307,50 @@ def test_up_to_128_verifier_queries(dev_mod, oracle, shape):
     run_reuse(dev_mod, oracle, case, sel, dev=dev)
     if shape == "tree_dfs":
         run_shared(dev_mod, oracle, case, 4)
+
+
+def test_calls_can_be_captured_in_a_hip_graph(dev_mod, oracle):
+    """A refresh call and a reuse call recorded into a HIP graph and replayed: the library allocates nothing,
+    never synchronises and clears no memory with memset nodes, so every replay (with eager work and synchronisation
+    in between) must reproduce the eager result bit for bit."""
+    import torch
+    from paper_2605_19893_amd import SSV_REFRESH, SSV_REUSE
+    case = si.make_case("graph", "bf16", 2, 6, 32, 2, 192, 128, si.STD_NSA, [3001, 2222], 155, rho=0.5)
+    ref = oracle.nsa_verify(case)
+    dev = dev_mod.DeviceCase(case)
+    dev.run()
+    out_eager, sel_eager = dev.results()
+    check(case, compare(case, oracle, ref, out_eager, sel_eager))
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dev.run()                       # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            dev.run()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        dev.out.zero_()
+        dev.sel_idx.fill_(-7)
+        dev.workspace.fill_(0x55)       # eager work between replays; stale scratch must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        out, sel = dev.results()
+        assert np.array_equal(out, out_eager) and np.array_equal(sel, sel_eager), replay
+    # reuse mode, captured separately (its launch sequence differs)
+    dev.set_mode(SSV_REUSE)
+    dev.set_sel_idx(sel_eager)
+    dev.run()
+    out_reuse, _ = dev.results()
+    graph2 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph2, stream=side):
+            dev.run()
+    torch.cuda.synchronize()
+    for replay in range(2):
+        dev.out.zero_()
+        torch.cuda.synchronize()
+        graph2.replay()
+        out, _ = dev.results()
+        assert np.array_equal(out, out_reuse), replay
