@@ -112,6 +112,70 @@ struct RowTileRegs {
     }
 };
 
+// Row-major tile of 64 rows x ROW_BYTES brought from global memory straight into LDS (gfx950 16-byte
+// buffer->LDS loads: the 64 lanes of one instruction fill 1 KB of LDS linearly from a wave-uniform base, each lane
+// from its own offset into the buffer), no registers and no LDS store instructions in between.  Buffer loads
+// rather than global ones: a global (flat-encoded) LDS load also counts as a possible LDS access of the flat
+// kind, which makes the compiler wait for ALL outstanding LDS reads before every use while one is in flight.  The LDS image has no row
+// padding; instead the 16-byte granule index inside every group of eight granules is XORed with the low three bits
+// of the row, which spreads the sixteen rows an MFMA operand read touches over the banks as padding would.
+//   granule (row r, column c)  ->  LDS granule r * CPR + ((c & ~7) | ((c & 7) ^ (r & 7)))
+// Rows beyond valid_rows repeat the last valid row (the caller masks their scores; nothing is zero-filled).
+template <int ROW_BYTES>
+struct DirectRowTile {
+    static constexpr int CPR = ROW_BYTES / 16;            // granules per row
+    static_assert(CPR % 8 == 0, "rows must be whole groups of eight granules");
+    static constexpr int TOTAL = kTile * CPR;
+    static_assert(TOTAL % kThreads == 0, "tile must divide evenly over the workgroup");
+    static constexpr int ITERS = TOTAL / kThreads;        // load instructions per wavefront
+    static constexpr int BYTES = kTile * ROW_BYTES;
+    uint32_t off[ITERS];     // global byte offset, inside a full tile, of the granule this lane fetches in instruction it
+
+    // LDS granule handled by (wave, it, lane): instruction `it` of wavefront `wave` fills granules [(wave*ITERS+it)*64, +64)
+    __device__ __forceinline__ static void where(int tid, int it, int& r, int& c) {
+        const int p = ((tid >> 6) * ITERS + it) * 64 + (tid & 63);
+        r = p / CPR;
+        const int csw = p % CPR;
+        c = (csw & ~7) | ((csw & 7) ^ (r & 7));
+    }
+    __device__ __forceinline__ void init(uint32_t g_row_bytes, int tid) {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            int r, c;
+            where(tid, it, r, c);
+            off[it] = (uint32_t)r * g_row_bytes + (uint32_t)c * 16u;
+        }
+    }
+    // rsrc: buffer resource over the rows of one (sequence, KV head); tile_off: byte offset of the tile's first row
+    __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rsrc, uint32_t tile_off, char* lds_tile, uint32_t g_row_bytes,
+                                          int valid_rows, int tid) {
+        char* dst = lds_tile + (tid >> 6) * ITERS * 1024;     // wave-uniform
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            uint32_t o = off[it];
+            if (valid_rows < kTile) {        // uniform; only the last tile of a sequence
+                int r, c;
+                where(tid, it, r, c);
+                o = (uint32_t)min(r, valid_rows - 1) * g_row_bytes + (uint32_t)c * 16u;
+            }
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(dst + it * 1024), 16,
+                                                     (int)o, (int)tile_off, 0, 0);
+        }
+    }
+    // Raw buffer resource (stride 0, bounds in bytes) over `bytes` bytes at `base`: loads past the end return zero
+    // instead of faulting.
+    __device__ __forceinline__ static __amdgpu_buffer_rsrc_t make_rsrc(const char* base, int64_t bytes) {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, (int)min(bytes, (int64_t)0x7fffffff), 0x00020000);
+    }
+    // byte offset, inside the tile, of granule column c0 + (kc ^ ...) handled through two per-lane bases: a lane that
+    // reads row `row` and granule G of 64-byte chunk kc finds it at base(kc & 1) + kc * 64, with
+    //   base(0) = row * ROW_BYTES + ((G ^ (row & 3)) * 16) + ((row >> 2) & 1) * 64,   base(1) = base(0) - 2 * ((row >> 2) & 1) * 64
+    __device__ __forceinline__ static int read_base(int row, int G, int odd) {
+        const int hb = (row >> 2) & 1;
+        return row * ROW_BYTES + ((G ^ (row & 3)) * 16) + (odd ? -hb * 64 : hb * 64);
+    }
+};
+
 // Layout of the bf16 V^T tile: row = value column (128 bytes, no padding) = 8 "pairs" of 16 bytes; pair
 // p = 4 u + G holds the two key quads (4 keys x 2 bytes each) 8 u + G and 8 u + 4 + G side by side, which
 // are exactly the eight keys lane group G feeds to one K=32 MFMA step u, so one 16-byte LDS read is a whole

@@ -39,11 +39,11 @@ template <bool BF16, int DK, int DV>
 struct StreamCfg {
     static constexpr int ES = BF16 ? 2 : 4;
     static constexpr int KROW = DK * ES;            // bytes per K row
-    static constexpr int KP = KROW + 16;            // LDS pitch of a K row (bank spread)
+    static constexpr int LDS_KD = kTile * KROW;     // one K tile in LDS (unpadded, granules swizzled); there are two
     static constexpr int KCH = KROW / 64;           // 64-byte chunks per K row
     static constexpr int VP = kTile * ES + (BF16 ? 0 : 16);   // LDS pitch of a V^T row (64 keys); bf16 rows are swizzled
     static constexpr int MT = DV / 16;              // 16-row tiles of O^T
-    static constexpr int LDS_K = kTile * KP;
+    static constexpr int LDS_K = 2 * LDS_KD;
     static constexpr int LDS_VT = DV * VP;
 };
 
@@ -86,13 +86,17 @@ __device__ long long g_clk[4096 * 16];
 // compiled out.
 constexpr int kRolesCmpWin = 3, kRolesSlc = 4, kRolesAll = 7;
 
+// Two workgroups per CU (the LDS of the full-size shapes allows no more), stated to the compiler as exactly two
+// waves per SIMD: left free to aim for three, it trades away the read-ahead of the K fragments for registers that
+// no third wave can use.
+
 template <bool BF16, int DK, int DV, int NRT, int ROLES>
-__global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
+__global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) k_stream(const StreamArgs a) {
     using Cfg = StreamCfg<BF16, DK, DV>;
-    constexpr int ES = Cfg::ES, KP = Cfg::KP, KCH = Cfg::KCH, VP = Cfg::VP, MT = Cfg::MT;
+    constexpr int ES = Cfg::ES, KROWB = Cfg::KROW, KCH = Cfg::KCH, VP = Cfg::VP, MT = Cfg::MT;
     extern __shared__ __align__(16) char smem[];
-    char* sK = smem;
-    char* sVT = sK + Cfg::LDS_K;
+    char* sK0 = smem;                  // two K tiles: the global->LDS loads of tile i+1 land while tile i is read
+    char* sVT = sK0 + Cfg::LDS_K;
     uint64_t* s_own = reinterpret_cast<uint64_t*>(sVT + Cfg::LDS_VT);
     AncSet* s_anc = reinterpret_cast<AncSet*>(s_own + a.max_sched);
     int* s_id = reinterpret_cast<int*>(s_anc + kMaxT);
@@ -255,27 +259,30 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     const int vt_rb = vt_load_base_bf16(n, G);   // this lane's base offset into the swizzled bf16 V^T tile
     SSV_STAMP(3);
 
-    // Software pipeline: the global loads of tile it+AHEAD are issued before tile it is computed and are
-    // committed to LDS AHEAD tiles later (alternating register sets when AHEAD > 1); two barriers per tile
-    // separate the LDS writes from the fragment reads.  Measured with in-kernel clocks, the prefetched loads
-    // have always arrived by the time they are committed at one tile ahead (the tile loop is bound by its own
-    // instruction stream), and two tiles ahead bought nothing for 40 more registers, so AHEAD stays 1.
+    // Software pipeline: the global loads of tile it+1 are issued before tile it is computed.  K goes straight into
+    // the other of two LDS tiles (no registers, no LDS stores); V is staged in registers because it is transposed on
+    // its way into LDS, and is committed one tile later.  Two barriers per tile separate the LDS writes from the
+    // fragment reads.  Measured with in-kernel clocks, the prefetched loads have always arrived by the time they are
+    // needed at one tile ahead (the tile loop is bound by its own instruction stream); two tiles ahead bought nothing.
     constexpr int AHEAD = 1;
-    RowTileRegs<Cfg::KROW> kregs[AHEAD];
+    const __amdgpu_buffer_rsrc_t krsrc = DirectRowTile<Cfg::KROW>::make_rsrc(kbase, (int64_t)max(rows_exist, 0) * krow);
+    DirectRowTile<Cfg::KROW> kdir;
     TransposedTileRegs<BF16, DV> vregs[AHEAD];
     auto tile_of = [&](int it) { return r_slc ? s_id[it] : it; };
-    auto issue_tile = [&](int it, RowTileRegs<Cfg::KROW>& kr, TransposedTileRegs<BF16, DV>& vr) {
+    auto issue_tile = [&](int it, TransposedTileRegs<BF16, DV>& vr) {
         const int base_n = tile_of(it) * kTile;
         const int vr_n = min(kTile, rows_exist - base_n);
-        kr.issue(kbase + (int64_t)base_n * krow, (uint32_t)krow, vr_n, tid);
+        kdir.issue(krsrc, (uint32_t)base_n * (uint32_t)krow, sK0 + ((it - t0) & 1) * Cfg::LDS_KD, (uint32_t)krow, vr_n, tid);
         vr.issue(vbase + (int64_t)base_n * vrow, (uint32_t)vrow, vr_n, tid);
     };
+    kdir.init((uint32_t)krow, tid);
 #pragma unroll
     for (int j = 0; j < AHEAD; ++j) {
-        kregs[j].init((uint32_t)krow, tid);
         vregs[j].init((uint32_t)vrow, tid);
-        if (t0 + j < t1) issue_tile(t0 + j, kregs[j], vregs[j]);
+        if (t0 + j < t1) issue_tile(t0 + j, vregs[j]);
     }
+    // this lane's two base offsets into a K tile (row n of a 16-key tile, granule G of an even / odd 64-byte chunk)
+    const int k_rb_e = DirectRowTile<Cfg::KROW>::read_base(n, G, 0), k_rb_o = DirectRowTile<Cfg::KROW>::read_base(n, G, 1);
     // wave-wide bounds for the "every key of the tile is valid for every row" fast path (rows that do not
     // exist are don't-cares: nothing of theirs is ever written)
     int full_cmax = 0x7fffffff, full_lo = -0x7fffffff;
@@ -289,9 +296,10 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         full_lo = max(full_lo, __shfl_xor(full_lo, off));
     }
     SSV_PHASE_DECL
-    // One tile; (kcur, vcur) hold tile `it` and, once committed to LDS, take tile it + AHEAD.
-    auto tile_step = [&](const int it, RowTileRegs<Cfg::KROW>& kcur, TransposedTileRegs<BF16, DV>& vcur) {
+    // One tile; vcur holds the V rows of tile `it` and, once committed to LDS, takes those of tile it + AHEAD.
+    auto tile_step = [&](const int it, TransposedTileRegs<BF16, DV>& vcur) {
         SSV_PHASE(5);
+        const char* sK = sK0 + ((it - t0) & 1) * Cfg::LDS_KD;
         const int tile = tile_of(it);
         const uint64_t own = r_slc ? s_own[it] : ~0ull;
         const int base = tile * kTile;
@@ -304,16 +312,17 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): separate the wait for the prefetched loads from the LDS stores
         SSV_PHASE(1);
 #endif
-        kcur.template commit<KP>(sK, valid_rows, tid);
         vcur.template commit<VP>(sVT, valid_rows, tid);
         if (has_drafts && tid < kTile) {   // absolute position of every key of the tile (tree drafts: L + depth)
             const int s = base + tid;
             s_kpos[tid] = s < L ? s : (s - L < Tq ? L + s_depth[s - L] : 0x7fffffff);
         }
         SSV_PHASE(2);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's global->LDS loads of the K tile have landed
         __syncthreads();
         SSV_PHASE(3);
-        if (it + AHEAD < t1) issue_tile(it + AHEAD, kcur, vcur);
+        if (it + AHEAD < t1) issue_tile(it + AHEAD, vcur);
+        __builtin_amdgcn_sched_barrier(0);    // the loads stay ahead of the compute below (they have been seen to sink past it)
         SSV_PHASE(4);
 
         // ---- validity of this lane's 16 keys (4 key tiles x 4 registers) for each of its query rows;
@@ -373,26 +382,31 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
             for (int t = 0; t < NRT; ++t)
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt) s[t][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kc = 0; kc < KCH; ++kc) {
-#pragma unroll
-                for (int kt = 0; kt < 4; ++kt) {
-                    const u32x4 kf = lds_read16(sK + (16 * kt + n) * KP + kc * 64 + G * 16);
-#pragma unroll
-                    for (int t = 0; t < NRT; ++t) s[t][kt] = mma_frag<BF16>(kf, qf[t][kc], s[t][kt]);
-                }
-            }
+            auto k_frag = [&](int i) {   // fragment i: 16-key tile i % 4 of 64-byte chunk i / 4
+                const int kc = i >> 2, kt = i & 3;
+                return lds_read16(sK + ((kc & 1) ? k_rb_o : k_rb_e) + 16 * kt * KROWB + kc * 64);
+            };
             if constexpr (BF16) {
-                // issue order: 8 fragment reads ahead, then one read per MFMA group, so that the LDS latency of
-                // every fragment is covered by the MFMAs of the fragments before it
-                constexpr int N_RD = 4 * KCH, LEAD = 8;
-                __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0);
+                // issue order, pinned: 8 fragment reads ahead, then one read after each group of MFMAs, so that the
+                // LDS latency of every fragment is covered by the MFMAs of the fragments before it
+                constexpr int N_RD = 4 * KCH, LEAD = NRT == 1 ? 8 : 4;
+                u32x4 kfb[LEAD];
 #pragma unroll
-                for (int i = 0; i < N_RD - LEAD; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, NRT, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                for (int i = 0; i < LEAD; ++i) kfb[i] = k_frag(i);
+#pragma unroll
+                for (int i = 0; i < N_RD; ++i) {
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int t = 0; t < NRT; ++t) s[t][i & 3] = mma_frag<BF16>(kfb[i % LEAD], qf[t][i >> 2], s[t][i & 3]);
+                    if (i + LEAD < N_RD) kfb[i % LEAD] = k_frag(i + LEAD);
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, LEAD * NRT, 0);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4 * KCH; ++i) {
+                    const u32x4 kf = k_frag(i);
+#pragma unroll
+                    for (int t = 0; t < NRT; ++t) s[t][i & 3] = mma_frag<BF16>(kf, qf[t][i >> 2], s[t][i & 3]);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
             // ---- online softmax in the log2 domain (rows without a valid key keep their state: alpha = 1)
@@ -488,7 +502,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_stream(const StreamArgs a) {
     for (int it = t0; it < t1; it += AHEAD) {
 #pragma unroll
         for (int j = 0; j < AHEAD; ++j)
-            if (it + j < t1) tile_step(it + j, kregs[j], vregs[j]);
+            if (it + j < t1) tile_step(it + j, vregs[j]);
     }
     SSV_PHASE(5);
     SSV_PHASE_WRITE;

@@ -2,6 +2,7 @@
 // and the launch sequences of the refresh (Section 5.1) and reuse (Section 5.2) paths.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -19,6 +20,7 @@ namespace {
 using namespace ssv;
 
 struct Shape { int dtype, d_k, d_v; };
+constexpr int kMaxDevices = 64;   // per-device one-time set-up flags
 constexpr Shape kShapes[] = {{SSV_BF16, 192, 128}, {SSV_BF16, 128, 128}, {SSV_BF16, 64, 64}, {SSV_F32, 64, 64}};
 
 int env_int(const char* name, int dflt) {
@@ -228,7 +230,22 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     }
     const size_t lds_stream = stream_lds_bytes(SC::LDS_K, SC::LDS_VT, sa.max_sched, sa.bitmap_words);
     const int units = p->B * p->H_kv * pl.n_qg;
-    if (lds_stream > 64 * 1024) return SSV_EUNSUPPORTED;     // merged schedules of very large groups do not fit
+    if (lds_stream > 80 * 1024) return SSV_EUNSUPPORTED;     // two workgroups per CU; merged schedules of very large groups do not fit
+    if (lds_stream > 64 * 1024) {
+        // more than the default dynamic LDS limit: raise it once per device for the kernels of this shape (repeating
+        // the call after a lost race between two host threads is harmless)
+        static std::atomic<bool> raised[kMaxDevices];
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SSV_ELAUNCH;
+        if (!raised[dev].load(std::memory_order_acquire)) {
+            const void* fns[] = {(const void*)k_stream<BF16, DK, DV, 1, kRolesAll>, (const void*)k_stream<BF16, DK, DV, 1, kRolesSlc>,
+                                 (const void*)k_stream<BF16, DK, DV, 1, kRolesCmpWin>, (const void*)k_stream<BF16, DK, DV, 2, kRolesAll>,
+                                 (const void*)k_stream<BF16, DK, DV, 2, kRolesSlc>, (const void*)k_stream<BF16, DK, DV, 2, kRolesCmpWin>};
+            for (const void* fn : fns)
+                if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess) return SSV_ELAUNCH;
+            raised[dev].store(true, std::memory_order_release);
+        }
+    }
 
     const int reps = tm.on ? tm.repeats : 1;
     auto launch_stream = [&](int slot_lo, int slot_cnt) -> int {
