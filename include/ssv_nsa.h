@@ -85,6 +85,9 @@ typedef struct ssv_nsa_params {
     int32_t max_n_cmp;    /* host-side upper bound on n_cmp[b] = rows of k_cmp / v_cmp per (sequence, KV head); larger
                              n_cmp[b] are clamped to it */
     int32_t avg_seq_len;  /* host-side hint: mean of seq_lens[b] (balances splits of mixed-length batches); 0 = max_seq_len */
+    int32_t scan_group_size; /* queries per workgroup in the launch of the compressed and window scans (<= 64,
+                             times H_g <= 128); 0 = automatic: group_size if that is given, else up to 128 rows where
+                             the scans keep the chip busy for several rounds; never changes the result */
     int64_t k_stride[3], v_stride[3], kc_stride[3], vc_stride[3];  /* elements: batch, KV head, row */
 } ssv_nsa_params;
 
@@ -101,6 +104,10 @@ typedef struct ssv_nsa_plan {
     int32_t n_slots;          /* partial softmax states per output row = sum of the three above */
     int32_t max_sched_entries;/* capacity of the merged schedule of one group */
     int32_t share_group;      /* SSV_REFRESH_SHARED: queries per index-sharing group; 0 in the other modes */
+    int32_t C_scan;           /* queries per group in the launch of the compressed and window scans (>= C: every
+                                 query of a sequence reads the same rows there, so larger groups only save loads;
+                                 the merged schedule of the selected branch grows with its group) */
+    int32_t n_qg_scan;        /* such groups per (sequence, KV head) */
     int64_t workspace_bytes;
 } ssv_nsa_plan;
 

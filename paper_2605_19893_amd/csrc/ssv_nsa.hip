@@ -35,7 +35,8 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
     ssv_nsa_plan plan;
-    int H_g, nrt, es;
+    int H_g, es;
+    bool one_launch;
     int imp_C, imp_n_qg, n_imp_chunks;   // importance pass: routed queries per workgroup, such workgroups per sequence, slices
     int nc_pitch, max_blocks, bitmap_words;
     int64_t rows_total;
@@ -68,6 +69,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     const bool shared = p->mode == SSV_REFRESH_SHARED;
     const int c_max = shared ? p->T : std::min(p->T, std::min(64, 128 / H_g));   // ownership masks hold 64 queries
     if (p->group_size > c_max) return SSV_EINVAL;
+    if (p->scan_group_size < 0 || p->scan_group_size > std::min(p->T, std::min(64, 128 / H_g))) return SSV_EINVAL;
     const int max_blocks = (p->max_seq_len + p->T) / p->l_sel + 1;
     if (max_blocks > 16384) return SSV_EUNSUPPORTED;
 
@@ -85,7 +87,6 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // never below min_tiles tiles per slice.  Small problems take one workgroup per CU instead (a workgroup that
     // has its CU to itself runs a tile in 2.3 us instead of 3.3): when that leaves slices of at most four tiles.
     const int units = p->B * p->H_kv * pl.n_qg;
-    const int nrt = pl.rows_per_wg > 64 ? 2 : 1;
     const int capacity = env_int("SSV_CAPACITY", 256 * 2);
     const int ntc = std::max(1, ceil_div(p->max_n_cmp, kTile));         // compressed tiles of the longest sequence
     // an average sequence has fewer compressed tiles than the longest one: budget slices for the average, so
@@ -93,6 +94,20 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     const double avg_frac = (p->avg_seq_len > 0 && p->max_seq_len > 0) ? (double)p->avg_seq_len / p->max_seq_len : 1.0;
     const int ntc_avg = std::max(1, (int)std::ceil(ntc * avg_frac));
     const int ntw = (p->w + p->T) / kTile + 2;                          // window tiles
+    // Scan grouping.  The compressed and window scans read the same rows for every query of a sequence, so when the
+    // chip is kept busy for several rounds by them (8 tile steps or more per resident workgroup) their launch takes
+    // groups of up to 128 rows (two row tiles per wave share every K and V fragment read from LDS: measured 18-20 %
+    // faster at 16-40 queries per sequence), balanced over the sequence's queries.  An explicit group_size applies
+    // to both launches unless the scan has one of its own.
+    pl.C_scan = pl.C;
+    if (p->scan_group_size) pl.C_scan = p->scan_group_size;
+    else if (!p->group_size || shared) {
+        const int n_a = ceil_div(p->T, std::max(1, std::min(p->T, 128 / H_g)));
+        const int cand = ceil_div(p->T, n_a);
+        if (cand > pl.C && (int64_t)units * (ntc_avg + ntw) >= 8 * (int64_t)capacity && !env_int("SSV_NO_SCAN_GROUPS", 0)) pl.C_scan = cand;
+    }
+    pl.n_qg_scan = ceil_div(p->T, pl.C_scan);
+    const int units_scan = p->B * p->H_kv * pl.n_qg_scan;
     pl.max_sched_entries = pl.C * p->n_sel;
     // selected tiles, at most; with one shared index set per group the schedule is a single set
     const int nts = shared ? ceil_div(pl.C, pl.share_group) * p->n_sel : pl.max_sched_entries;
@@ -103,11 +118,11 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // Otherwise slices are cut to 24 tiles: several rounds of workgroups, and the longest slice, the long pole of
     // a mixed-length batch, stays bounded (12-tile slices balanced better but cost 5-10 % at the 128K-context
     // configurations: twice the partial states to write and merge, twice the per-workgroup start-up).
-    auto tiles_per_slice = [&](const int* tiles, int n_roles) {
+    auto tiles_per_slice = [&](const int* tiles, int n_roles, int n_units) {
         int total = 0;
         for (int r = 0; r < n_roles; ++r) total += tiles[r];
-        int spu = std::max(n_roles, (capacity / 2) / units);      // slices per unit one round can hold, one workgroup per CU
-        if (std::max(mt, ceil_div(total, spu)) > 4) spu = std::max(n_roles, capacity / units);   // two per CU
+        int spu = std::max(n_roles, (capacity / 2) / n_units);      // slices per unit one round can hold, one workgroup per CU
+        if (std::max(mt, ceil_div(total, spu)) > 4) spu = std::max(n_roles, capacity / n_units);   // two per CU
         int per = std::max(mt, ceil_div(total, spu));
         if (per > 24) return env_int("SSV_LONG_SLICE", 24);
         for (;; ++per) {
@@ -117,13 +132,14 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
         }
     };
     int per_a, per_b;
-    if (p->mode == SSV_REUSE) {
+    lo->one_launch = p->mode == SSV_REUSE && pl.C_scan == pl.C;   // all three branches in one launch
+    if (lo->one_launch) {
         const int tiles[3] = {ntc_avg, ntw, nts};
-        per_a = per_b = tiles_per_slice(tiles, 3);
+        per_a = per_b = tiles_per_slice(tiles, 3, units);
     } else {
         const int tiles_a[2] = {ntc_avg, ntw};
-        per_a = tiles_per_slice(tiles_a, 2);
-        per_b = tiles_per_slice(&nts, 1);
+        per_a = tiles_per_slice(tiles_a, 2, units_scan);
+        per_b = tiles_per_slice(&nts, 1, units);
     }
     const int n_c = std::max(1, ceil_div(ntc, per_a)), n_w = std::max(1, ceil_div(ntw, per_a));
     const int n_s = std::max(1, ceil_div(nts, per_b));
@@ -137,7 +153,6 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     pl.n_slots = pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits;
 
     lo->H_g = H_g;
-    lo->nrt = nrt;
     // importance pass: every query is routed, or one representative per group of C (shared-index variant), then
     // packed 64 rows to a workgroup; 4 workgroups per CU are resident (120 VGPRs, about 30 KB LDS): one round of
     // at most 1024
@@ -229,7 +244,6 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         sa.kc_s[j] = p->kc_stride[j] * es; sa.vc_s[j] = p->vc_stride[j] * es;
     }
     const size_t lds_stream = stream_lds_bytes(SC::LDS_K, SC::LDS_VT, sa.max_sched, sa.bitmap_words);
-    const int units = p->B * p->H_kv * pl.n_qg;
     if (lds_stream > 80 * 1024) return SSV_EUNSUPPORTED;     // two workgroups per CU; merged schedules of very large groups do not fit
     if (lds_stream > 64 * 1024) {
         // more than the default dynamic LDS limit: raise it once per device for the kernels of this shape (repeating
@@ -248,14 +262,15 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     }
 
     const int reps = tm.on ? tm.repeats : 1;
-    auto launch_stream = [&](int slot_lo, int slot_cnt) -> int {
-        sa.slot_lo = slot_lo; sa.slot_cnt = slot_cnt; sa.n_wg = units * slot_cnt;
+    auto launch_stream = [&](int slot_lo, int slot_cnt, int C, int n_qg) -> int {
+        sa.C = C; sa.n_qg = n_qg;
+        sa.slot_lo = slot_lo; sa.slot_cnt = slot_cnt; sa.n_wg = p->B * p->H_kv * n_qg * slot_cnt;
         const int grid = ceil_div(sa.n_wg, 8) * 8;
         const bool all = slot_cnt == pl.n_slots, only_slc = slot_lo > 0;
         for (int r = 0; r < reps; ++r) {
 #define SSV_LAUNCH_STREAM(NRT_, ROLES_) \
     hipLaunchKernelGGL((k_stream<BF16, DK, DV, NRT_, ROLES_>), dim3(grid), dim3(kThreads), lds_stream, stream, sa)
-            if (lo.nrt == 2) {
+            if (C * lo.H_g > 64) {
                 if (all) SSV_LAUNCH_STREAM(2, kRolesAll);
                 else if (only_slc) SSV_LAUNCH_STREAM(2, kRolesSlc);
                 else SSV_LAUNCH_STREAM(2, kRolesCmpWin);
@@ -269,11 +284,18 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         return hipGetLastError() == hipSuccess ? 0 : -1;
     };
 
-    if (p->mode == SSV_REUSE) {
-        if (tm.begin(SSV_K_STREAM_A) || launch_stream(0, pl.n_slots) || tm.end(SSV_K_STREAM_A)) return SSV_ELAUNCH;
+    const int n_scan_slots = pl.n_cmp_chunks + pl.n_win_splits;
+    if (lo.one_launch) {
+        if (tm.begin(SSV_K_STREAM_A) || launch_stream(0, pl.n_slots, pl.C, pl.n_qg) || tm.end(SSV_K_STREAM_A)) return SSV_ELAUNCH;
     } else {
-        if (tm.begin(SSV_K_STREAM_A) || launch_stream(0, pl.n_cmp_chunks + pl.n_win_splits) || tm.end(SSV_K_STREAM_A))
+        if (tm.begin(SSV_K_STREAM_A) || launch_stream(0, n_scan_slots, pl.C_scan, pl.n_qg_scan) || tm.end(SSV_K_STREAM_A))
             return SSV_ELAUNCH;
+    }
+    if (p->mode == SSV_REUSE) {
+        if (!lo.one_launch &&
+            (tm.begin(SSV_K_STREAM_B) || launch_stream(n_scan_slots, pl.n_slc_splits, pl.C, pl.n_qg) || tm.end(SSV_K_STREAM_B)))
+            return SSV_ELAUNCH;
+    } else {
 
         ImportanceArgs ia{};
         ia.q = sa.q; ia.kc = sa.kc; ia.seq_lens = seq_lens; ia.n_cmp = n_cmp; ia.n_query = n_query; ia.parents = parents;
@@ -306,7 +328,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
             hipLaunchKernelGGL(k_topn, dim3(p->B * p->T * p->H_kv), dim3(kThreads), lds_topn, stream, ta);
         if (hipGetLastError() != hipSuccess || tm.end(SSV_K_TOPN)) return SSV_ELAUNCH;
 
-        if (tm.begin(SSV_K_STREAM_B) || launch_stream(pl.n_cmp_chunks + pl.n_win_splits, pl.n_slc_splits) ||
+        if (tm.begin(SSV_K_STREAM_B) || launch_stream(n_scan_slots, pl.n_slc_splits, pl.C, pl.n_qg) ||
             tm.end(SSV_K_STREAM_B))
             return SSV_ELAUNCH;
     }

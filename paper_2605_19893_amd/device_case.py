@@ -51,9 +51,11 @@ class DeviceCase:
         self.workspace = None
         self.set_group_size(group_size, mode)
 
-    def set_group_size(self, group_size: int, mode=None) -> None:
-        """Change C (verifier queries per workgroup); the workspace grows if the new plan needs more."""
+    def set_group_size(self, group_size: int, mode=None, scan_group_size: int = 0) -> None:
+        """Change C (verifier queries per workgroup) and the group size of the scan launch; the workspace grows if
+        the new plan needs more."""
         self.params.group_size = group_size
+        self.params.scan_group_size = scan_group_size
         mode = self.params.mode if mode is None else mode
         # the split plan (and with it the scratch size) depends on the mode: size the workspace for all of them
         need = 0

@@ -33,8 +33,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_matches_header():
     # 20 four-byte fields followed by 12 int64 strides; 11 ints, padding and an int64 in the plan
-    assert ctypes.sizeof(B.SsvNsaParams) == 20 * 4 + 12 * 8
-    assert ctypes.sizeof(B.SsvNsaPlan) == 12 * 4 + 8
+    assert ctypes.sizeof(B.SsvNsaParams) == 22 * 4 + 12 * 8
+    assert ctypes.sizeof(B.SsvNsaPlan) == 14 * 4 + 8
 
 
 def test_error_strings():
@@ -104,7 +104,10 @@ def test_plan_fills_the_chip_and_respects_limits():
         assert pl.n_slots == pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits
         assert pl.n_cmp_chunks * pl.tiles_per_chunk * 64 >= p.max_n_cmp
         assert pl.max_sched_entries == pl.C * p.n_sel
-        units = p.B * p.H_kv * pl.n_qg
+        # scan launch: larger, balanced groups only where the scans keep the chip busy for several rounds
+        assert pl.C_scan * pl.n_qg_scan >= p.T and pl.C <= pl.C_scan <= 128 // H_g
+        assert (pl.C_scan, pl.n_qg_scan) == {"cfg1": (4, 2), "cfg2": (4, 1), "cfg3": (8, 5), "cfg4": (8, 2)}[name]
+        units = p.B * p.H_kv * pl.n_qg_scan
         wgs = units * (pl.n_cmp_chunks + pl.n_win_splits)
         # either one resident round (at most 2 workgroups per CU) or several rounds of slices of at most 24 tiles
         assert wgs >= min(256, units * ((p.max_n_cmp + 63) // 64) // 2), (name, wgs)
@@ -115,6 +118,20 @@ def test_plan_fills_the_chip_and_respects_limits():
     assert (pl.C, pl.n_qg, pl.rows_per_wg) == (2, 4, 32)
     pl = B.ssv_nsa_plan_query(std_params(group_size=8))
     assert (pl.C, pl.n_qg, pl.rows_per_wg) == (8, 1, 128)
+    # an explicit group size applies to both launches
+    pl = B.ssv_nsa_plan_query(std_params(B=4, T=40, max_seq_len=131072, max_n_cmp=8191, group_size=2))
+    assert (pl.C, pl.C_scan, pl.n_qg_scan) == (2, 2, 20)
+    pl = B.ssv_nsa_plan_query(std_params(group_size=2, scan_group_size=8))
+    assert (pl.C, pl.n_qg, pl.C_scan, pl.n_qg_scan) == (2, 4, 8, 1)
+    pl = B.ssv_nsa_plan_query(std_params(scan_group_size=3))
+    assert (pl.C, pl.n_qg, pl.C_scan, pl.n_qg_scan) == (4, 2, 3, 3)
+    for bad in (-1, 9):
+        with pytest.raises(B.SsvError) as e:
+            B.ssv_nsa_plan_query(std_params(scan_group_size=bad))
+        assert e.value.code == B.SSV_EINVAL
+    # 12 queries: two balanced scan groups of 6
+    pl = B.ssv_nsa_plan_query(std_params(B=32, T=12, max_seq_len=131072, max_n_cmp=8191))
+    assert (pl.C, pl.n_qg, pl.C_scan, pl.n_qg_scan) == (4, 3, 6, 2)
 
 
 def test_shared_index_plan_keeps_the_automatic_grouping():

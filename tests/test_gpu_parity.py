@@ -228,6 +228,43 @@ def test_group_size_can_change_on_a_live_case(dev_mod, oracle):
     assert all(np.array_equal(outs[0], s) for s in outs[1:])
 
 
+@pytest.mark.parametrize("shape", ["chain", "tree_bfs", "tree_dfs"])
+def test_scan_launch_with_its_own_grouping(dev_mod, oracle, shape):
+    """The compressed and window scans grouped differently from the selected branch (larger, smaller, ragged last
+    group, two row tiles per wave), in refresh, reuse and shared-index mode: the partial states of the two launches
+    meet per output row, so every combination gives the oracle's result and the same indices."""
+    from paper_2605_19893_amd import SSV_REFRESH, SSV_REUSE, SSV_REFRESH_SHARED
+    if shape == "chain":
+        case = si.make_case("scan_groups_chain", "bf16", 2, 11, 64, 4, 192, 128, si.STD_NSA, [5000, 2300], 171, rho=0.6,
+                            n_query=[11, 7], poison_pad=True)
+    else:
+        par = si.tree_parents((3, 2, 2), shape[5:])   # 21 queries
+        case = si.make_case(f"scan_groups_{shape}", "bf16", 2, len(par), 32, 2, 192, 128, si.STD_NSA, [4100, 1500], 173,
+                            rho=0.6, parents=par)
+    ref = oracle.nsa_verify(case)
+    dev = dev_mod.DeviceCase(case)
+    sels = []
+    H_g = case.H // case.H_kv
+    for C, C_scan in ((0, 128 // H_g), (2, 8), (4, 3), (3, 5), (8, 1)):
+        dev.set_group_size(C, SSV_REFRESH, scan_group_size=C_scan)
+        assert dev.plan.C_scan == C_scan and dev.plan.n_qg_scan == -(-case.T // C_scan)
+        print(f"[run] {case.name} refresh plan={dev.plan.as_dict()}", flush=True)
+        dev.run()
+        out, sel = dev.results()
+        check(case, compare(case, oracle, ref, out, sel))
+        sels.append(sel)
+        dev.set_mode(SSV_REUSE)     # two launches here as well
+        dev.run()
+        out2, _ = dev.results()
+        check(case, compare(case, oracle, oracle.nsa_verify(case, sel_idx=sel), out2, sel, reuse_sel=sel))
+    assert all(np.array_equal(sels[0], s) for s in sels[1:])
+    G = 3
+    dev.set_group_size(G, SSV_REFRESH_SHARED, scan_group_size=128 // H_g)
+    dev.run()
+    out, sel = dev.results()
+    check(case, compare(case, oracle, oracle.nsa_verify_shared(case, G), out, sel, routed_by=oracle.group_representatives(case, G)))
+
+
 def test_library_flattening_reorders_a_tree_without_changing_results(dev_mod, oracle):
     """A BFS-ordered draft tree re-flattened to DFS with ssv_tree_flatten (Section 4.1): queries, gates and draft
     K/V rows are permuted with the returned order; every node keeps its output and index set.  All 21 draft slots
