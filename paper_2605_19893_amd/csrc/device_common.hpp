@@ -36,6 +36,33 @@ __device__ __forceinline__ f32x4 mma_frag(u32x4 a, u32x4 b, f32x4 c) {
     }
 }
 
+// Wait until at most N of this wavefront's vector memory loads are outstanding (they return in order).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | 0x0F70 | ((N >> 4) << 14));   // expcnt and lgkmcnt fields left at "no wait"
+}
+
+// The same for a wave-uniform run-time count (a branch tree over the immediates); counts of 32 and more wait for 31.
+__device__ __forceinline__ void wait_vmcnt_upto(int n) {
+    n = __builtin_amdgcn_readfirstlane(n);
+#define SSV_W4(b) \
+    switch (n & 3) { case 0: wait_vmcnt<(b)>(); break; case 1: wait_vmcnt<(b) + 1>(); break; \
+                     case 2: wait_vmcnt<(b) + 2>(); break; default: wait_vmcnt<(b) + 3>(); break; }
+    if (n >= 32) { wait_vmcnt<31>(); return; }
+    switch (n >> 2) {
+        case 0: SSV_W4(0) break;
+        case 1: SSV_W4(4) break;
+        case 2: SSV_W4(8) break;
+        case 3: SSV_W4(12) break;
+        case 4: SSV_W4(16) break;
+        case 5: SSV_W4(20) break;
+        case 6: SSV_W4(24) break;
+        default: SSV_W4(28) break;
+    }
+#undef SSV_W4
+}
+
 // Exchange with the lane 16 (32) positions away, without going through LDS: the gfx950 swap instructions return
 // the operand with its odd 16-lane (upper 32-lane) rows replaced by the even (lower) ones, and the reverse, so
 // combining the two results leaves op(x[l], x[l ^ 16]) (op(x[l], x[l ^ 32])) in every lane.

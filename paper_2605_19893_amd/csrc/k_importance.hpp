@@ -11,6 +11,13 @@
 // The tile product is taken in the orientation D[query row][key] (Q as the A operand): a lane then
 // holds four heads of one key, so the head sum is three in-register adds plus at most two
 // cross-lane exchanges.
+//
+// Work split: a workgroup holds the (at most 64) rows of its routed queries; every wavefront keeps ALL of
+// them in registers as A operands and takes its own strip of 16 keys of every 64-key tile, whose K rows it loads
+// from global memory directly in B-operand layout.  So K never passes through LDS (with 16 rows per
+// wavefront, every wavefront had to read the whole tile from LDS: four times the tile per step, which
+// bound the kernel), the main loop has no barrier, and the head-summed probabilities go from registers to
+// global memory.
 #pragma once
 #include "k_stream.hpp"
 
@@ -39,27 +46,35 @@ template <bool BF16, int DK>
 struct ImportanceCfg {
     static constexpr int ES = BF16 ? 2 : 4;
     static constexpr int KROW = DK * ES;
-    static constexpr int KP = KROW + 16;
     static constexpr int KCH = KROW / 64;
-    static constexpr int LDS_K = kTile * KP;
-    // LDS bytes: K tile, merged row statistics, per-sequence tree metadata and routed-query list, then the
-    // head-summed tile [C][64]
-    static constexpr int lds_bytes(int C) { return LDS_K + 256 * 8 + kMaxT * 32 + 64 + C * kTile * 4; }
+    static constexpr int RT = 4;            // 16-row tiles per workgroup: 64 rows
+    static constexpr int DEPTH = 3;         // LDS slots per wavefront for K strips (DEPTH - 1 in flight)
+    static constexpr int LDS_RING = 4 * DEPTH * KCH * 1024;   // dynamic LDS bytes
 };
 
-template <bool BF16, int DK, int NRT>
+#ifdef SSV_CLOCKS
+__device__ long long g_clk_imp[4096 * 16];
+#define SSV_IMP_T(i) do { if (tid == 0 && wg < 4096) clk_[i] = wall_clock64(); } while (0)
+#else
+#define SSV_IMP_T(i) do { } while (0)
+#endif
+
+constexpr int kImpRows = 64;   // rows (routed queries x heads of the group) per workgroup
+
+// HGM: 16 = one query per 16-row tile (H_g = 16); 4 = H_g of 4 or 8 (the four rows a lane holds in the result layout are
+// heads of one query); 1 = H_g of 1 or 2.
+template <bool BF16, int DK, int HGM>
 __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs a) {
     using Cfg = ImportanceCfg<BF16, DK>;
-    constexpr int ES = Cfg::ES, KP = Cfg::KP, KCH = Cfg::KCH;
-    extern __shared__ __align__(16) char smem[];
-    char* sK = smem;
-    float2* s_stat = reinterpret_cast<float2*>(sK + Cfg::LDS_K);   // [128] (M, 1/Z) per workgroup row
-    AncSet* s_anc = reinterpret_cast<AncSet*>(s_stat + 256);
-    int* s_par = reinterpret_cast<int*>(s_anc + kMaxT);
-    int* s_depth = s_par + kMaxT;
-    int* s_cmax = s_depth + kMaxT;
-    int* s_qi = s_cmax + kMaxT;                                    // verifier query behind every routed query of this workgroup
-    float* s_cs = reinterpret_cast<float*>(s_qi + kMaxT + 16);     // [C][64] head-summed probabilities
+    constexpr bool WIDE = HGM >= 4;
+    constexpr int ES = Cfg::ES, KCH = Cfg::KCH, RT = Cfg::RT, RC = WIDE ? 1 : 4, DEPTH = Cfg::DEPTH;
+    static_assert(DEPTH == 3 && 2 * KCH + 2 < 64, "the waits below are written for two strips in flight");
+    extern __shared__ __align__(16) char smem[];   // [wavefront][DEPTH][KCH][1 KB]: the strips in flight
+    __shared__ float2 s_part[4 * kImpRows];   // partial (M, Z) of every row, one per wavefront
+    __shared__ __align__(16) float s_mp[kImpRows];   // M + log2 Z of every row: p = exp2(s - that)
+    __shared__ AncSet s_anc[kMaxT];
+    __shared__ int s_par[kMaxT], s_depth[kMaxT], s_cmax[kMaxT];
+    __shared__ int s_qi[kImpRows];              // verifier query behind every routed query of this workgroup
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, G = lane >> 4;
@@ -67,19 +82,62 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     const int n_pad = gridDim.x;
     const int wg = (blockIdx.x & 7) * (n_pad >> 3) + (blockIdx.x >> 3);
     if (wg >= a.n_wg) return;
+#ifdef SSV_CLOCKS
+    long long clk_[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+    SSV_IMP_T(0);
     const int qg = wg % a.n_qg;
     const int chunk = (wg / a.n_qg) % a.n_imp_chunks;
     const int bg = wg / (a.n_qg * a.n_imp_chunks);
     const int b = bg / a.H_kv, g = bg % a.H_kv;
 
+    // A operands: row n of every row tile of the workgroup, all 64-byte chunks.  When every query is routed the
+    // rows are known before the sequence's metadata, and their loads overlap its latency (queries past the
+    // sequence's count are loaded too, they exist in the buffer; nothing of theirs is used).
+    u32x4 qf[RT][KCH];
+    auto load_q = [&](auto query_of, int nq) {
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+            const int rr = t * 16 + n;
+            const int j = rr / a.H_g;
+            // rows past the group's queries repeat its first query: whatever they produce is never stored, and
+            // unconditional loads are not waited for here
+            const int64_t grow = ((int64_t)b * a.T + query_of(j < nq ? j : 0)) * a.H + g * a.H_g + rr % a.H_g;
+#pragma unroll
+            for (int kc = 0; kc < KCH; ++kc) qf[t][kc] = *reinterpret_cast<const u32x4*>(a.q + grow * (DK * ES) + kc * 64 + G * 16);
+        }
+    };
+    // Softmax statistics of the compressed scan: one row per lane, every wavefront taking every fourth slice; the
+    // loads of a batch of four slices are unconditional (clamped index) so that they are in flight together.
+    int64_t srow = 0;
+    float2 st0[4];
+    auto stats_row = [&](auto query_of, int nq) {
+        const int j = lane / a.H_g;
+        return ((int64_t)b * a.T + query_of(j < nq ? j : 0)) * a.H + g * a.H_g + lane % a.H_g;
+    };
+    auto stats_load = [&](int s0, float2 (&st)[4]) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int sl = min(s0 + 4 * u, a.n_cmp_chunks - 1);
+            st[u] = *reinterpret_cast<const float2*>(a.part_stats + ((int64_t)sl * a.rows_total + srow) * 2);
+        }
+    };
+    if (!a.share) {
+        const auto query_of = [&](int j) { return qg * a.C + j; };
+        const int nq = min(a.C, a.T - qg * a.C);
+        load_q(query_of, nq);
+        srow = stats_row(query_of, nq);
+        stats_load(wave, st0);
+    }
+    SSV_IMP_T(8);
     const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, a.max_seq_len, a.max_n_cmp, s_par, s_depth,
-                                       s_cmax,
-                                       s_anc);
-    const int L = sm.L, Tq = sm.Tq;
+                                       s_cmax, s_anc);
+    SSV_IMP_T(9);
+    const int Tq = sm.Tq;
     const int n_routed = a.share ? (Tq + a.share - 1) / a.share : Tq;
     const int nq_grp = min(a.C, n_routed - qg * a.C);
     if (nq_grp <= 0) return;
-    if (tid < a.C) {
+    if (tid < kImpRows) {
         int qi = 0;
         if (tid < nq_grp) {
             const int r = qg * a.C + tid;
@@ -89,142 +147,233 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     }
     __syncthreads();
 
+    SSV_IMP_T(10);
     int cm = 0;
     for (int j = 0; j < nq_grp; ++j) cm = max(cm, s_cmax[s_qi[j]]);
     const int ntiles = (cm + kTile - 1) / kTile;
     int t0, t1;
     even_slice(ntiles, a.n_imp_chunks, 1, chunk, t0, t1);
-    if (t0 >= t1) return;
+    if (t0 >= t1) return;       // (uniform; cm > 0 from here on, so the sequence has compressed rows)
+    SSV_IMP_T(1);
 
-    // merged softmax statistics of every row of this workgroup: M = max_s m_s, Z = sum_s Z_s 2^(m_s - M).
-    // Two threads per row, each taking every other slice; the loads of a batch of eight slices are
-    // unconditional (clamped index) so that they are in flight together.
+    // This wavefront's strip: keys 16 wave + n of every tile, 16 bytes per 64-byte chunk and lane (B-operand layout);
+    // rows past the last compressed row repeat it (their probabilities are masked by the visibility limit).  The
+    // strips go from global memory straight into a ring of DEPTH wavefront-private LDS slots (buffer loads with
+    // the LDS destination: lane-linear, so every lane later reads back exactly the 16 bytes it fetched), DEPTH - 1
+    // strips ahead of the one in use: the registers are taken by the A operands.
+    const __amdgpu_buffer_rsrc_t krsrc =
+        DirectRowTile<Cfg::KROW>::make_rsrc(a.kc + b * a.kc_s[0] + g * a.kc_s[1], (int64_t)sm.n_cmp * a.kc_s[2]);
+    const uint32_t krow = (uint32_t)a.kc_s[2];
+    char* ring = smem + wave * (DEPTH * KCH * 1024);
+    auto issue_strip = [&](int tile) {
+        const uint32_t voff = (uint32_t)min(tile * kTile + 16 * wave + n, sm.n_cmp - 1) * krow + G * 16;
+        char* dst = ring + ((tile - t0) % DEPTH) * (KCH * 1024);
+#pragma unroll
+        for (int kc = 0; kc < KCH; ++kc)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (__attribute__((address_space(3))) void*)(dst + kc * 1024), 16, (int)voff,
+                                                     kc * 64, 0, 0);
+    };
+    // the first strips, the (shared-index variant) queries and the statistics below are all in flight together
+#pragma unroll
+    for (int i = 0; i < DEPTH - 1; ++i)
+        if (t0 + i < t1) issue_strip(t0 + i);
+    if (a.share) {
+        const auto query_of = [&](int j) { return s_qi[j]; };
+        load_q(query_of, nq_grp);
+        srow = stats_row(query_of, nq_grp);
+        stats_load(wave, st0);
+    }
+
+    // merged statistics of every row of this workgroup: M = max_s m_s, Z = sum_s Z_s 2^(m_s - M)
     const int rows_wg = nq_grp * a.H_g;
     {
-        const int rr = tid & 127, half = tid >> 7;
+        const int rr = lane;
         const bool ok = rr < rows_wg;
-        const int64_t grow = ((int64_t)b * a.T + s_qi[ok ? rr / a.H_g : 0]) * a.H + g * a.H_g + rr % a.H_g;
         float M = -INFINITY, Z = 0.f;
-        for (int s0 = half; s0 < a.n_cmp_chunks; s0 += 16) {
-            float2 st[8];
+        auto merge4 = [&](int s0, const float2 (&st)[4]) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int sl = min(s0 + 2 * u, a.n_cmp_chunks - 1);
-                st[u] = *reinterpret_cast<const float2*>(a.part_stats + ((int64_t)sl * a.rows_total + grow) * 2);
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                if (s0 + 2 * u < a.n_cmp_chunks && st[u].y > 0.f) {
+            for (int u = 0; u < 4; ++u) {
+                if (s0 + 4 * u < a.n_cmp_chunks && st[u].y > 0.f) {
                     const float Mn = fmaxf(M, st[u].x);
                     Z = Z * fast_exp2(M - Mn) + st[u].y * fast_exp2(st[u].x - Mn);
                     M = Mn;
                 }
             }
+        };
+        merge4(wave, st0);
+        for (int s0 = wave + 16; s0 < a.n_cmp_chunks; s0 += 16) {
+            float2 st[4];
+            stats_load(s0, st);
+            merge4(s0, st);
         }
-        float2* s_half = s_stat + 128;     // second half of the pair, merged below
-        if (half) s_half[rr] = make_float2(M, Z);
+        SSV_IMP_T(11);
+        s_part[wave * kImpRows + rr] = make_float2(M, Z);
         __syncthreads();
-        if (!half) {
-            const float2 o = s_half[rr];
-            const float Mn = fmaxf(M, o.x);
+        SSV_IMP_T(12);
+        if (wave == 0) {
+            float Mn = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float2 o = s_part[u * kImpRows + rr];
+                if (o.y > 0.f) Mn = fmaxf(Mn, o.x);
+            }
             float Zt = 0.f;
-            if (Z > 0.f) Zt += Z * fast_exp2(M - Mn);
-            if (o.y > 0.f) Zt += o.y * fast_exp2(o.x - Mn);
-            s_stat[rr] = make_float2(Zt > 0.f ? Mn : 0.f, (ok && Zt > 0.f) ? 1.f / Zt : 0.f);
-        }
-    }
-
-    // A operand: this lane's query rows (row n of each row tile), all 64-byte chunks
-    u32x4 qf[NRT][KCH];
 #pragma unroll
-    for (int t = 0; t < NRT; ++t) {
-        const int rr = (wave + 4 * t) * 16 + n;
-        const int j = rr / a.H_g;
-        const bool ok = j < nq_grp;
-        const int64_t grow = ((int64_t)b * a.T + s_qi[ok ? j : 0]) * a.H + g * a.H_g + rr % a.H_g;
-#pragma unroll
-        for (int kc = 0; kc < KCH; ++kc) {
-            qf[t][kc] = u32x4{0, 0, 0, 0};
-            if (ok) qf[t][kc] = *reinterpret_cast<const u32x4*>(a.q + grow * (DK * ES) + kc * 64 + G * 16);
+            for (int u = 0; u < 4; ++u) {
+                const float2 o = s_part[u * kImpRows + rr];
+                if (o.y > 0.f) Zt += o.y * fast_exp2(o.x - Mn);
+            }
+            s_mp[rr] = (ok && Zt > 0.f) ? Mn + __builtin_amdgcn_logf(Zt) : INFINITY;   // (the builtin is log2)
         }
     }
     __syncthreads();
+    SSV_IMP_T(2);
 
-    // statistics and visibility limits of the four rows (4 G + r) this lane holds in the result layout
-    float rowM[NRT][4], rowIZ[NRT][4];
-    int rowC[NRT][4];
+    // of the four rows (16 t + 4 G + r) this lane holds in the result layout: the softmax offset, the visibility
+    // limit and the colsum row of their query
+    float rowMp[RT][4];
+    int rowC[RT][RC], rowQ[RT][RC];
 #pragma unroll
-    for (int t = 0; t < NRT; ++t)
+    for (int t = 0; t < RT; ++t) {
+        const float4 mp = *reinterpret_cast<const float4*>(s_mp + t * 16 + 4 * G);
+        rowMp[t][0] = mp.x; rowMp[t][1] = mp.y; rowMp[t][2] = mp.z; rowMp[t][3] = mp.w;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int rr = (wave + 4 * t) * 16 + 4 * G + r;
-            const int j = rr / a.H_g;
+        for (int r = 0; r < RC; ++r) {
+            const int j = (t * 16 + 4 * G + r) / a.H_g;
             const bool ok = j < nq_grp;
-            const float2 st = s_stat[ok ? rr : 0];
-            rowM[t][r] = st.x;
-            rowIZ[t][r] = ok ? st.y : 0.f;
-            rowC[t][r] = ok ? s_cmax[s_qi[j]] : 0;
+            const int qi = s_qi[ok ? j : 0];
+            rowC[t][r] = ok ? s_cmax[qi] : 0;
+            rowQ[t][r] = ok ? (b * a.T + qi) * a.H_kv + g : -1;
         }
+    }
+    // HGM == 16: lane group G ends up with the head sum of row tile (= query) G
+    int myC = 0, myQ = -1;
+    if constexpr (HGM == 16) {
+#pragma unroll
+        for (int t = 0; t < RT; ++t)
+            if (G == t) { myC = rowC[t][0]; myQ = rowQ[t][0]; }     // (the same in every lane for a given t)
+    }
 
-    const char* kbase = a.kc + b * a.kc_s[0] + g * a.kc_s[1];
-    RowTileRegs<Cfg::KROW> kregs;     // the loads of the next tile are in flight while this one is computed
-    kregs.init((uint32_t)a.kc_s[2], tid);
-    kregs.issue(kbase + (int64_t)t0 * kTile * a.kc_s[2], (uint32_t)a.kc_s[2], min(kTile, sm.n_cmp - t0 * kTile), tid);
-    for (int tile = t0; tile < t1; ++tile) {
-        const int base = tile * kTile;
-        __syncthreads();
-        kregs.template commit<KP>(sK, min(kTile, sm.n_cmp - base), tid);
-        __syncthreads();
-        if (tile + 1 < t1)
-            kregs.issue(kbase + (int64_t)(base + kTile) * a.kc_s[2], (uint32_t)a.kc_s[2], min(kTile, sm.n_cmp - base - kTile), tid);
+    auto load_strip = [&](int tile, u32x4 (&kf)[KCH]) {
+        const char* src = ring + ((tile - t0) % DEPTH) * (KCH * 1024) + lane * 16;
 #pragma unroll
-        for (int t = 0; t < NRT; ++t) {
-            const int rt = wave + 4 * t;
-            if (rt * 16 >= rows_wg) continue;
+        for (int kc = 0; kc < KCH; ++kc) kf[kc] = lds_read16(src + kc * 1024);
+    };
+    // One strip: 16 keys x 64 rows.  The stores it issues are the same in every step (their predicates do not
+    // depend on the tile: every key of a processed tile lies inside the colsum row).
+    auto strip_step = [&](int tile, const u32x4 (&kf)[KCH]) {
+        f32x4 s[RT];
 #pragma unroll
-            for (int kt = 0; kt < 4; ++kt) {
-                f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < RT; ++t) s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int kc = 0; kc < KCH; ++kc) {
-                    const u32x4 kf = lds_read16(sK + (16 * kt + n) * KP + kc * 64 + G * 16);
-                    s = mma_frag<BF16>(qf[t][kc], kf, s);   // D[row 4G+r][key n]
+        for (int kc = 0; kc < KCH; ++kc)
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+                s[t] = mma_frag<BF16>(qf[t][kc], kf[kc], s[t]);   // D[row 4G+r][key n]; absent rows are zero operands
+        const int c = tile * kTile + 16 * wave + n;
+        if constexpr (WIDE) {
+            float hs[RT];     // head sums of this lane's four rows of each row tile (one query), unmasked
+#pragma unroll
+            for (int t = 0; t < RT; ++t) {
+                float p[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) p[r] = fast_exp2(__builtin_fmaf(s[t][r], a.scale_log2, -rowMp[t][r]));
+                hs[t] = (p[0] + p[1]) + (p[2] + p[3]);
+            }
+            if constexpr (HGM == 16) {
+                // Sum over the four lane groups and hand row tile t to lane group t in one butterfly: the swap of
+                // (x, y) leaves x's pair of 16-lane rows in the even rows and y's in the odd ones (lower and upper
+                // 32 lanes for the second stage).
+                const auto e01 = __builtin_amdgcn_permlane16_swap(__float_as_uint(hs[0]), __float_as_uint(hs[1]), false, false);
+                const auto e23 = __builtin_amdgcn_permlane16_swap(__float_as_uint(hs[2]), __float_as_uint(hs[3]), false, false);
+                const float r01 = __uint_as_float(e01[0]) + __uint_as_float(e01[1]);
+                const float r23 = __uint_as_float(e23[0]) + __uint_as_float(e23[1]);
+                const auto f = __builtin_amdgcn_permlane32_swap(__float_as_uint(r01), __float_as_uint(r23), false, false);
+                const float v = __uint_as_float(f[0]) + __uint_as_float(f[1]);
+                if (myQ >= 0) a.colsum[(int64_t)myQ * a.nc_pitch + c] = c < myC ? v : 0.f;
+            } else {
+                const int gpq = a.H_g >> 2;                     // lane groups per query: 1 or 2
+#pragma unroll
+                for (int t = 0; t < RT; ++t) {
+                    float v = hs[t];
+                    if (gpq == 2) v = xor16_add(v);
+                    if ((G % gpq) == 0 && rowQ[t][0] >= 0) a.colsum[(int64_t)rowQ[t][0] * a.nc_pitch + c] = c < rowC[t][0] ? v : 0.f;
                 }
-                const int c = base + 16 * kt + n;
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < RT; ++t) {
                 float p[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    p[r] = c < rowC[t][r] ? fast_exp2(s[r] * a.scale_log2 - rowM[t][r]) * rowIZ[t][r] : 0.f;
-                // head sum; rows 16 rt + 4 G + r, H_g heads per query
-                const int key = 16 * kt + n;
-                if (a.H_g >= 4) {
-                    float v = (p[0] + p[1]) + (p[2] + p[3]);
-                    if (a.H_g >= 8) v = xor16_add(v);
-                    if (a.H_g >= 16) v = xor32_add(v);
-                    const int gpq = a.H_g >> 2;                  // lane groups per query
-                    if ((G % gpq) == 0) {
-                        const int j = (rt * 16 + 4 * G) / a.H_g;
-                        if (j < nq_grp) s_cs[j * kTile + key] = v;
-                    }
-                } else if (a.H_g == 2) {
-                    const int j = (rt * 16 + 4 * G) >> 1;
-                    if (j < nq_grp) s_cs[j * kTile + key] = p[0] + p[1];
-                    if (j + 1 < nq_grp) s_cs[(j + 1) * kTile + key] = p[2] + p[3];
+                    p[r] = c < rowC[t][r] ? fast_exp2(__builtin_fmaf(s[t][r], a.scale_log2, -rowMp[t][r])) : 0.f;
+                if (a.H_g == 2) {
+                    if (rowQ[t][0] >= 0) a.colsum[(int64_t)rowQ[t][0] * a.nc_pitch + c] = p[0] + p[1];
+                    if (rowQ[t][2] >= 0) a.colsum[(int64_t)rowQ[t][2] * a.nc_pitch + c] = p[2] + p[3];
                 } else {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int j = rt * 16 + 4 * G + r;
-                        if (j < nq_grp) s_cs[j * kTile + key] = p[r];
-                    }
+                    for (int r = 0; r < 4; ++r)
+                        if (rowQ[t][r] >= 0) a.colsum[(int64_t)rowQ[t][r] * a.nc_pitch + c] = p[r];
                 }
             }
         }
-        __syncthreads();
-        for (int i = tid; i < nq_grp * kTile; i += kThreads) {
-            const int j = i / kTile, key = i % kTile;
-            if (base + key < a.nc_pitch)
-                a.colsum[(((int64_t)b * a.T + s_qi[j]) * a.H_kv + g) * a.nc_pitch + base + key] = s_cs[i];
-        }
+    };
+    // store instructions per step that are issued for certain (a store whose predicate is false in every lane may or
+    // may not be issued: it is not counted)
+    int ns = 0;
+    if constexpr (HGM == 16) {
+        ns = 1;      // lane group 0 always has a query
+    } else if constexpr (WIDE) {
+        const int gpq = a.H_g >> 2;
+#pragma unroll
+        for (int t = 0; t < RT; ++t) ns += __builtin_amdgcn_ballot_w64((G % gpq) == 0 && rowQ[t][0] >= 0) != 0ull;
+    } else {
+#pragma unroll
+        for (int t = 0; t < RT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (a.H_g == 1 || !(r & 1)) ns += __builtin_amdgcn_ballot_w64(rowQ[t][r] >= 0) != 0ull;
     }
+    SSV_IMP_T(3);
+
+    // Software pipeline over the tiles of the slice.  Loads and stores share one in-order counter: the strip of a
+    // tile has landed once no more operations are outstanding than were issued after it: the KCH loads of each
+    // younger strip and the stores of the two steps since it was issued (counting too few of them only waits
+    // longer).
+    auto step = [&](int tile) {
+        u32x4 kf[KCH];
+        load_strip(tile, kf);
+        strip_step(tile, kf);
+    };
+    int tile = t0;
+    for (; tile + 2 < t1; ++tile) {
+        issue_strip(tile + 2);
+        __builtin_amdgcn_sched_barrier(0);
+#ifdef SSV_CLOCKS
+        const long long w0_ = wall_clock64();
+#endif
+        if (tile - t0 < 2) wait_vmcnt<2 * KCH>();
+        else if (ns == 1) wait_vmcnt<2 * KCH + 2>();
+        else wait_vmcnt_upto(2 * KCH + 2 * ns);
+#ifdef SSV_CLOCKS
+        clk_[5] += wall_clock64() - w0_;
+#endif
+        step(tile);
+    }
+    if (tile + 1 < t1) {
+        wait_vmcnt<KCH>();
+        step(tile);
+        ++tile;
+    }
+    wait_vmcnt<0>();
+    step(tile);
+    SSV_IMP_T(4);
+#ifdef SSV_CLOCKS
+    if (tid == 0 && wg < 4096) {
+        clk_[6] = t1 - t0;
+        for (int i = 0; i < 16; ++i) g_clk_imp[wg * 16 + i] = clk_[i];
+    }
+#endif
 }
 
 }  // namespace ssv

@@ -66,6 +66,10 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
             if (strides[a][j] < 0 || (strides[a][j] * es) % 16) return SSV_EINVAL;
             if (j == 2 && strides[a][j] < dims[a]) return SSV_EINVAL;
         }
+    // K rows are fetched through 32-bit buffer offsets from the start of a (sequence, KV head)
+    if ((int64_t)(p->max_seq_len + p->T) * p->k_stride[2] * es >= (1ll << 31) ||
+        (int64_t)p->max_n_cmp * p->kc_stride[2] * es >= (1ll << 31))
+        return SSV_EUNSUPPORTED;
     const bool shared = p->mode == SSV_REFRESH_SHARED;
     const int c_max = shared ? p->T : std::min(p->T, std::min(64, 128 / H_g));   // ownership masks hold 64 queries
     if (p->group_size > c_max) return SSV_EINVAL;
@@ -154,18 +158,19 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
 
     lo->H_g = H_g;
     // importance pass: every query is routed, or one representative per group of C (shared-index variant), then
-    // packed 64 rows to a workgroup; 4 workgroups per CU are resident (120 VGPRs, about 30 KB LDS): one round of
-    // at most 1024
+    // packed 64 rows to a workgroup; 2 workgroups per CU are resident (72 KB of LDS each for the K strips in
+    // flight): one round of at most 512 (more, shorter workgroups measured slower: every workgroup pays about 10 us
+    // of start-up before its first tile)
     if (shared) {
         const int routed = ceil_div(p->T, pl.share_group);
         lo->imp_C = std::max(1, std::min(routed, 64 / H_g));
         lo->imp_n_qg = ceil_div(routed, lo->imp_C);
     } else {
-        lo->imp_C = pl.C;
-        lo->imp_n_qg = pl.n_qg;
+        lo->imp_C = std::min(pl.C, std::max(1, 64 / H_g));
+        lo->imp_n_qg = ceil_div(p->T, lo->imp_C);
     }
     const int imp_units = p->B * p->H_kv * lo->imp_n_qg;
-    lo->n_imp_chunks = std::max(1, std::min(ceil_div(ntc, env_int("SSV_IMP_MIN_TILES", 1)), std::max(1, 1024 / imp_units)));
+    lo->n_imp_chunks = std::max(1, std::min(ceil_div(ntc, env_int("SSV_IMP_MIN_TILES", 1)), std::max(1, env_int("SSV_IMP_WGS", 512) / imp_units)));
     lo->es = es;
     lo->nc_pitch = (int)align_up((size_t)std::max(1, p->max_n_cmp), kTile);
     lo->max_blocks = max_blocks;
@@ -308,8 +313,9 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         const int grid_i = ceil_div(ia.n_wg, 8) * 8;
         if (tm.begin(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
         for (int r = 0; r < reps; ++r) {
-            if (ia.C * lo.H_g > 64) hipLaunchKernelGGL((k_importance<BF16, DK, 2>), dim3(grid_i), dim3(kThreads), IC::lds_bytes(ia.C), stream, ia);
-            else hipLaunchKernelGGL((k_importance<BF16, DK, 1>), dim3(grid_i), dim3(kThreads), IC::lds_bytes(ia.C), stream, ia);
+            if (lo.H_g == 16) hipLaunchKernelGGL((k_importance<BF16, DK, 16>), dim3(grid_i), dim3(kThreads), IC::LDS_RING, stream, ia);
+            else if (lo.H_g >= 4) hipLaunchKernelGGL((k_importance<BF16, DK, 4>), dim3(grid_i), dim3(kThreads), IC::LDS_RING, stream, ia);
+            else hipLaunchKernelGGL((k_importance<BF16, DK, 1>), dim3(grid_i), dim3(kThreads), IC::LDS_RING, stream, ia);
         }
         if (hipGetLastError() != hipSuccess || tm.end(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
 
@@ -515,6 +521,9 @@ int ssv_nsa_version(void) { return 1; }
 // development builds only: copy the in-kernel time stamps of the last k_stream launch to the host
 int ssv_debug_read_clocks_topn(long long* host_out, int n) {
     return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ssv::g_clk_topn), sizeof(long long) * n) == hipSuccess ? 0 : -1;
+}
+int ssv_debug_read_clocks_imp(long long* host_out, int n) {
+    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ssv::g_clk_imp), sizeof(long long) * n) == hipSuccess ? 0 : -1;
 }
 int ssv_debug_read_clocks(long long* host_out, int n) {
     return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ssv::g_clk), sizeof(long long) * n) == hipSuccess ? 0 : -1;

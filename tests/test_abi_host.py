@@ -60,6 +60,9 @@ def test_supported_shapes():
     (dict(T=129), B.SSV_EUNSUPPORTED), (dict(H=96, H_kv=4), B.SSV_EUNSUPPORTED), (dict(l_sel=128), B.SSV_EUNSUPPORTED),
     (dict(d_k=96), B.SSV_EUNSUPPORTED), (dict(n_sel=40), B.SSV_EUNSUPPORTED),
     (dict(max_seq_len=2 ** 21), B.SSV_EUNSUPPORTED),
+    # rows of one (sequence, KV head) spread over 2 GiB or more: beyond the 32-bit offsets of the K loads
+    (dict(max_seq_len=2 ** 19, k_stride=(4 * 2 ** 20 * 2048, 2 ** 20 * 2048, 2048)), B.SSV_EUNSUPPORTED),
+    (dict(max_n_cmp=2 ** 15, kc_stride=(4 * 2 ** 15 * 2 ** 15, 2 ** 15 * 2 ** 15, 2 ** 15)), B.SSV_EUNSUPPORTED),
 ])
 def test_bad_parameters_are_rejected_without_a_launch(over, code):
     p = std_params(**over)
