@@ -16,6 +16,7 @@
 // O^T = V^T . P^T without a round trip through LDS.
 #pragma once
 #include "device_common.hpp"
+#include "k_topn.hpp"
 
 namespace ssv {
 
@@ -33,7 +34,18 @@ struct StreamArgs {
     int max_sched, bitmap_words;
     int64_t rows_total;
     int64_t k_s[3], v_s[3], kc_s[3], vc_s[3];   // strides in bytes
+    // selected-branch launch of the refresh path that also does the top-n selection (fused_topn != 0): every
+    // workgroup selects for the queries of its group from the head-summed probabilities, one query per wavefront,
+    // and the first slice of each group writes the sets out
+    const float* colsum;     // [B, T, H_kv, nc_pitch]
+    int32_t* sel_out;        // [B, T, H_kv, n_sel]
+    int fused_topn, nc_pitch, l_sel, n_init, n_local, max_blocks, share;
 };
+
+// LDS the fused selection needs (it uses the tile buffers, which are idle until the schedule exists)
+__host__ __device__ inline size_t fused_topn_lds_bytes(int max_blocks, int C, int n_sel) {
+    return 4 * wave_topn_lds_bytes(max_blocks) + (size_t)C * n_sel * 4;
+}
 
 template <bool BF16, int DK, int DV>
 struct StreamCfg {
@@ -157,6 +169,32 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
         grow[t] = ((int64_t)b * a.T + qs) * a.H + g * a.H_g + rr % a.H_g;
     }
 
+    // ---- fused top-n selection (Section 5.1: routing, then attention over the selected blocks)
+    int32_t* s_sel = nullptr;     // [C][n_sel] index sets of the group's queries, in the (still idle) tile buffers
+    if constexpr (ROLES == kRolesSlc) {
+        if (a.fused_topn) {
+            s_sel = reinterpret_cast<int32_t*>(smem + 4 * wave_topn_lds_bytes(a.max_blocks));
+            const WaveTopnScratch ws = wave_topn_scratch(smem + wave * wave_topn_lds_bytes(a.max_blocks), a.max_blocks);
+            for (int j = wave; j < a.C; j += 4) {
+                const int x = qg * a.C + j;
+                if (x >= a.T) break;
+                int32_t* out = s_sel + j * a.n_sel;
+                if (x >= Tq) {
+                    if (lane < a.n_sel) out[lane] = -1;
+                } else {
+                    // the approximate shared-index variant selects for the representative of the query's sharing group
+                    const int i = a.share ? group_representative(s_depth, (x / a.share) * a.share, min((x / a.share + 1) * a.share, Tq)) : x;
+                    wave_topn(a.colsum + (((int64_t)b * a.T + i) * a.H_kv + g) * a.nc_pitch, min(s_cmax[i], a.nc_pitch),
+                              min((L + i) / a.l_sel, a.max_blocks - 1), a.l, a.d, a.l_sel, a.n_sel, a.n_init, a.n_local, ws, lane, out);
+                }
+                wave_lds_sync();
+                if (part == 0 && lane < a.n_sel) a.sel_out[(((int64_t)b * a.T + x) * a.H_kv + g) * a.n_sel + lane] = out[lane];
+            }
+            __syncthreads();
+        }
+    }
+    SSV_STAMP(6);
+
     // ---- tile range of this workgroup
     int t0 = 0, t1 = 0;           // CMP / WIN: tile indices; SLC: schedule entries
     if (nq_grp > 0) {
@@ -183,7 +221,7 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
             const int n_ent = nq_grp * a.n_sel;
             for (int i = tid; i < n_ent; i += kThreads) {
                 const int j = i / a.n_sel, e = i % a.n_sel;
-                const int id = a.sel_idx[(((int64_t)b * a.T + qg * a.C + j) * a.H_kv + g) * a.n_sel + e];
+                const int id = s_sel ? s_sel[i] : a.sel_idx[(((int64_t)b * a.T + qg * a.C + j) * a.H_kv + g) * a.n_sel + e];
                 if (id >= 0 && id < nblk) atomicOr(&s_bitmap[id >> 5], 1u << (id & 31));
             }
             __syncthreads();
@@ -205,7 +243,7 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
             __syncthreads();
             for (int i = tid; i < n_ent; i += kThreads) {
                 const int j = i / a.n_sel, e = i % a.n_sel;
-                const int id = a.sel_idx[(((int64_t)b * a.T + qg * a.C + j) * a.H_kv + g) * a.n_sel + e];
+                const int id = s_sel ? s_sel[i] : a.sel_idx[(((int64_t)b * a.T + qg * a.C + j) * a.H_kv + g) * a.n_sel + e];
                 if (id >= 0 && id < nblk) {
                     const uint32_t wd = s_bitmap[id >> 5];
                     const int rank = s_prefix[id >> 5] + __popc(wd & ((1u << (id & 31)) - 1u));

@@ -59,6 +59,204 @@ __host__ __device__ inline size_t topn_lds_bytes(int max_blocks) {
     return (size_t)max_blocks * 8 + kThreads * 8 + kMaxCand * 8 + 16 * 8 + kMaxNSel * 4 + kMaxT * 28 + 64;
 }
 
+// ---- The same selection by ONE wavefront, for callers that have several queries to select for at once (the
+// selected-branch launch selects for the queries of its own group, each wavefront taking a query, instead of
+// waiting for a separate launch).  Importances are kept in LDS as their 32-bit patterns (the index is the
+// position), keys are composed on the fly, and the result is the one k_topn writes: the same importances, summed
+// in the same order, the same (importance, index) order.
+
+struct WaveTopnScratch {             // one per wavefront, in LDS
+    uint32_t* bits;                  // [J + 1] importance bit patterns (forced blocks: +inf)
+    uint64_t* best;                  // [64]
+    uint64_t* cand;                  // [kWaveMaxCand]
+    int* pick;                       // [kMaxNSel]
+};
+constexpr int kWaveMaxCand = 256;
+__host__ __device__ inline size_t wave_topn_lds_bytes(int max_blocks) {   // per wavefront, 16-byte multiple
+    return (((size_t)max_blocks * 4 + 15) & ~(size_t)15) + 64 * 8 + kWaveMaxCand * 8 + kMaxNSel * 4;
+}
+__device__ __forceinline__ WaveTopnScratch wave_topn_scratch(char* base, int max_blocks) {
+    WaveTopnScratch w;
+    w.bits = reinterpret_cast<uint32_t*>(base);
+    w.best = reinterpret_cast<uint64_t*>(base + (((size_t)max_blocks * 4 + 15) & ~(size_t)15));
+    w.cand = w.best + 64;
+    w.pick = reinterpret_cast<int*>(w.cand + kWaveMaxCand);
+    return w;
+}
+// LDS written by some lanes of a wavefront is read by others: the LDS unit takes a wavefront's operations in order,
+// so only the compiler has to be kept from reordering them.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+__device__ __forceinline__ uint64_t topn_key(uint32_t bits, int j) {
+    return ((uint64_t)bits << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
+}
+
+// cs: colsum row of the (representative) query; ncv: its visible compressed rows; J: block of its own slot.
+// Writes the n_sel entries (ascending, -1 padding) to out[] (LDS or global).
+__device__ __forceinline__ void wave_topn(const float* cs, int ncv, int J, int l, int d, int l_sel, int n_sel, int n_init,
+                                          int n_local, const WaveTopnScratch& w, int lane, int32_t* out) {
+    const int a_ratio = l_sel / d, b_ratio = l / d;
+    const int n_eff = min(n_sel, J + 1);
+    const int n_terms = a_ratio + b_ratio - 1;
+    const int j_last_scored = J - max(n_local, 0);
+    uint64_t best = 0;
+    for (int j = max(j_last_scored + 1, 0) + lane; j <= J; j += 64) {     // forced trailing local blocks
+        w.bits[j] = 0x7F800000u;
+        const uint64_t key = topn_key(0x7F800000u, j);
+        best = key > best ? key : best;
+    }
+    constexpr int NB = 4;     // blocks per lane whose column loads are issued together
+    if (a_ratio == 4 && b_ratio == 2) {
+        // the standard geometry: block j takes columns 4j-1 .. 4j+3 with weights 1 2 2 2 1; one 16-byte and one
+        // 4-byte load per block, eight blocks per lane in flight (same terms in the same order as the general form)
+        constexpr int NF = 8;
+        for (int j0 = lane; j0 <= j_last_scored; j0 += 64 * NF) {
+            f32x4 x[NF];
+            float xm[NF];
+#pragma unroll
+            for (int v = 0; v < NF; ++v) {
+                const int j = j0 + v * 64;
+                const int c0 = j <= j_last_scored ? 4 * j : 0;
+                // (a row holds nc_pitch columns, a multiple of 64: a block starting past it has no visible column)
+                x[v] = *reinterpret_cast<const f32x4*>(cs + (c0 < ncv ? c0 : 0));
+                xm[v] = cs[(c0 >= 1 && c0 - 1 < ncv) ? c0 - 1 : 0];
+            }
+#pragma unroll
+            for (int v = 0; v < NF; ++v) {
+                const int j = j0 + v * 64;
+                if (j > j_last_scored) continue;
+                const int c0 = 4 * j;
+                float imp = 0.f;
+                if (c0 >= 1 && c0 - 1 < ncv) imp += 1.f * xm[v];
+                if (c0 < ncv) imp += 2.f * x[v][0];
+                if (c0 + 1 < ncv) imp += 2.f * x[v][1];
+                if (c0 + 2 < ncv) imp += 2.f * x[v][2];
+                if (c0 + 3 < ncv) imp += 1.f * x[v][3];
+                const uint32_t bits = j < n_init ? 0x7F800000u : __float_as_uint(imp);
+                w.bits[j] = bits;
+                const uint64_t key = topn_key(bits, j);
+                best = key > best ? key : best;
+            }
+        }
+    } else
+    for (int j0 = lane; j0 <= j_last_scored; j0 += 64 * NB) {
+        float imp[NB];
+        if (n_terms <= kMaxImpTerms) {
+            float x[NB][kMaxImpTerms];
+#pragma unroll
+            for (int v = 0; v < NB; ++v)
+#pragma unroll
+                for (int u = 0; u < kMaxImpTerms; ++u) {
+                    const int c = a_ratio * (j0 + v * 64) + u - (b_ratio - 1);
+                    x[v][u] = cs[(u < n_terms && c >= 0 && c < ncv) ? c : 0];
+                }
+#pragma unroll
+            for (int v = 0; v < NB; ++v) {
+                imp[v] = 0.f;
+#pragma unroll
+                for (int u = 0; u < kMaxImpTerms; ++u) {
+                    const int delta = u - (b_ratio - 1);
+                    const int c = a_ratio * (j0 + v * 64) + delta;
+                    const int pairs = min(min(a_ratio, b_ratio), min(delta + b_ratio, a_ratio - delta));
+                    if (u < n_terms && c >= 0 && c < ncv) imp[v] += (float)pairs * x[v][u];
+                }
+            }
+        } else {
+            for (int v = 0; v < NB; ++v) {
+                imp[v] = 0.f;
+                const int j = j0 + v * 64;
+                for (int m = 0; m < a_ratio && j <= J; ++m)
+                    for (int n2 = 0; n2 < b_ratio; ++n2) {
+                        const int c = a_ratio * j + m - n2;
+                        if (c >= 0 && c < ncv) imp[v] += cs[c];
+                    }
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < NB; ++v) {
+            const int j = j0 + v * 64;
+            if (j <= j_last_scored) {
+                const uint32_t bits = j < n_init ? 0x7F800000u : __float_as_uint(imp[v]);
+                w.bits[j] = bits;
+                const uint64_t key = topn_key(bits, j);
+                best = key > best ? key : best;
+            }
+        }
+    }
+    w.best[lane] = best;
+    wave_lds_sync();
+    // threshold: the n_eff-th largest of the 64 per-lane bests (distinct keys; lanes without blocks hold 0); with
+    // fewer than n_eff of them it stays 0 and every block is a candidate
+    uint64_t thr = 0;
+    {
+        int rank = 0;
+#pragma unroll 16
+        for (int k = 0; k < 64; ++k) rank += w.best[k] > best;
+        const uint64_t hit = __builtin_amdgcn_ballot_w64(best != 0 && rank == n_eff - 1);
+        if (hit) {
+            const int src = __builtin_ctzll(hit);
+            thr = ((uint64_t)(uint32_t)__shfl((int)(best >> 32), src) << 32) | (uint32_t)__shfl((int)(uint32_t)best, src);
+        }
+    }
+    int n_cand = 0;
+    for (int jb = 0; jb <= J; jb += 64) {
+        const int j = jb + lane;
+        const uint64_t key = j <= J ? topn_key(w.bits[j], j) : 0ull;
+        const bool is = j <= J && key >= thr;
+        const uint64_t m = __builtin_amdgcn_ballot_w64(is);
+        const int pos = n_cand + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        if (is && pos < kWaveMaxCand) w.cand[pos] = key;
+        n_cand += __popcll(m);
+    }
+    wave_lds_sync();
+    if (n_cand <= kWaveMaxCand) {
+        for (int e = lane; e < n_cand; e += 64) {      // rank candidates by counting; ranks below n_eff are the selection
+            const uint64_t key = w.cand[e];
+            int rank = 0;
+            int f = 0;
+            for (; f + 8 <= n_cand; f += 8) {
+                uint64_t c[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) c[u] = w.cand[f + u];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) rank += c[u] > key;
+            }
+            for (; f < n_cand; ++f) rank += w.cand[f] > key;
+            if (rank < n_eff) w.pick[rank] = (int)(0xFFFFFFFFu - (uint32_t)key);
+        }
+    } else {
+        // massive ties: serial argmax, one winner per round; the owner (index mod 64) retires it and rescans
+        for (int round = 0; round < n_eff; ++round) {
+            const uint64_t top = wave_max_u64(best);
+            const int j_top = (int)(0xFFFFFFFFu - (uint32_t)top);
+            if (lane == 0) w.pick[round] = j_top;
+            if ((j_top & 63) == lane) {
+                w.bits[j_top] = 0xFFFFFFFFu;      // retired (no importance has this pattern)
+                best = 0;
+                for (int j = lane; j <= J; j += 64) {
+                    const uint32_t bits = w.bits[j];
+                    const uint64_t key = topn_key(bits, j);
+                    if (bits != 0xFFFFFFFFu && key > best) best = key;
+                }
+            }
+        }
+    }
+    wave_lds_sync();
+    // ascending order: pick e goes to position (number of smaller picks); picks are distinct
+    if (lane < n_sel) {
+        int pick = -1, rank = lane;       // lanes beyond n_eff write the -1 padding at their own position
+        if (lane < n_eff) {
+            pick = w.pick[lane];
+            rank = 0;
+            for (int f = 0; f < n_eff; ++f) rank += w.pick[f] < pick;
+        }
+        out[rank] = pick;
+    }
+}
+
 __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     extern __shared__ __align__(16) char smem[];
     uint64_t* s_key = reinterpret_cast<uint64_t*>(smem);                  // [max_blocks]

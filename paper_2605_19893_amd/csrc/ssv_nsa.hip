@@ -319,21 +319,32 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         }
         if (hipGetLastError() != hipSuccess || tm.end(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
 
-        TopnArgs ta{};
-        ta.colsum = colsum; ta.seq_lens = seq_lens; ta.n_cmp = n_cmp; ta.n_query = n_query; ta.parents = parents;
-        ta.sel_idx = sel_idx; ta.B = p->B; ta.T = p->T; ta.H_kv = p->H_kv;
-        ta.max_seq_len = p->max_seq_len; ta.max_n_cmp = p->max_n_cmp;
-        ta.l = p->l; ta.d = p->d; ta.l_sel = p->l_sel; ta.n_sel = p->n_sel; ta.n_init = p->n_init; ta.n_local = p->n_local;
-        ta.nc_pitch = lo.nc_pitch; ta.max_blocks = lo.max_blocks; ta.share = ia.share;
-        const size_t lds_topn = topn_lds_bytes(lo.max_blocks);
-        if (lds_topn > 64 * 1024 &&
-            hipFuncSetAttribute((const void*)k_topn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_topn) != hipSuccess)
-            return SSV_ELAUNCH;
-        if (tm.begin(SSV_K_TOPN)) return SSV_ELAUNCH;
-        for (int r = 0; r < reps; ++r)
-            hipLaunchKernelGGL(k_topn, dim3(p->B * p->T * p->H_kv), dim3(kThreads), lds_topn, stream, ta);
-        if (hipGetLastError() != hipSuccess || tm.end(SSV_K_TOPN)) return SSV_ELAUNCH;
-
+        // Top-n selection: inside the selected-branch launch (every workgroup selects for its own group's queries,
+        // one query per wavefront, in the tile buffers that are idle until the schedule exists) when the importance
+        // arrays of four queries fit there; else as a launch of its own.
+        sa.colsum = colsum; sa.sel_out = sel_idx; sa.nc_pitch = lo.nc_pitch; sa.l_sel = p->l_sel; sa.n_init = p->n_init;
+        sa.n_local = p->n_local; sa.max_blocks = lo.max_blocks; sa.share = pl.share_group;
+        // Every slice of a group repeats the group's selections, which costs nothing while the launch leaves CUs idle
+        // (at most one workgroup per CU) and is slower than the separate launch once the chip is full.
+        const int n_wg_b = p->B * p->H_kv * pl.n_qg * pl.n_slc_splits;
+        sa.fused_topn = fused_topn_lds_bytes(lo.max_blocks, pl.C, p->n_sel) <= (size_t)(SC::LDS_K + SC::LDS_VT) &&
+                        n_wg_b <= env_int("SSV_FUSED_TOPN_MAX_WGS", 256) && !env_int("SSV_SEPARATE_TOPN", 0);
+        if (!sa.fused_topn) {
+            TopnArgs ta{};
+            ta.colsum = colsum; ta.seq_lens = seq_lens; ta.n_cmp = n_cmp; ta.n_query = n_query; ta.parents = parents;
+            ta.sel_idx = sel_idx; ta.B = p->B; ta.T = p->T; ta.H_kv = p->H_kv;
+            ta.max_seq_len = p->max_seq_len; ta.max_n_cmp = p->max_n_cmp;
+            ta.l = p->l; ta.d = p->d; ta.l_sel = p->l_sel; ta.n_sel = p->n_sel; ta.n_init = p->n_init; ta.n_local = p->n_local;
+            ta.nc_pitch = lo.nc_pitch; ta.max_blocks = lo.max_blocks; ta.share = ia.share;
+            const size_t lds_topn = topn_lds_bytes(lo.max_blocks);
+            if (lds_topn > 64 * 1024 &&
+                hipFuncSetAttribute((const void*)k_topn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_topn) != hipSuccess)
+                return SSV_ELAUNCH;
+            if (tm.begin(SSV_K_TOPN)) return SSV_ELAUNCH;
+            for (int r = 0; r < reps; ++r)
+                hipLaunchKernelGGL(k_topn, dim3(p->B * p->T * p->H_kv), dim3(kThreads), lds_topn, stream, ta);
+            if (hipGetLastError() != hipSuccess || tm.end(SSV_K_TOPN)) return SSV_ELAUNCH;
+        }
         if (tm.begin(SSV_K_STREAM_B) || launch_stream(n_scan_slots, pl.n_slc_splits, pl.C, pl.n_qg) ||
             tm.end(SSV_K_STREAM_B))
             return SSV_ELAUNCH;

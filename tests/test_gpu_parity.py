@@ -265,6 +265,39 @@ def test_scan_launch_with_its_own_grouping(dev_mod, oracle, shape):
     check(case, compare(case, oracle, oracle.nsa_verify_shared(case, G), out, sel, routed_by=oracle.group_representatives(case, G)))
 
 
+@pytest.mark.parametrize("where", ["separate_launch", "inside_selected_launch"])
+def test_both_homes_of_the_top_n_selection(dev_mod, oracle, where, monkeypatch):
+    """The top-n selection runs inside the selected-branch launch (one wavefront per query) when that launch
+    leaves CUs idle, else as a launch of its own; both are forced here on the same cases (the library reads the
+    switches at every call): chain with ragged query counts, tree, shared-index variant, massive ties, a geometry
+    other than the standard one, fp32."""
+    if where == "separate_launch":
+        monkeypatch.setenv("SSV_SEPARATE_TOPN", "1")
+    else:
+        monkeypatch.setenv("SSV_FUSED_TOPN_MAX_WGS", "1000000")
+    case = si.make_case("topn_home_chain", "bf16", 2, 11, 64, 4, 192, 128, si.STD_NSA, [5000, 2300], 181, rho=0.6,
+                        n_query=[11, 7], poison_pad=True)
+    for C in (0, 8, 3):
+        dev, ref, out, sel = run_refresh(dev_mod, oracle, case, group_size=C)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+    par = si.tree_parents((3, 2, 2), "dfs")
+    case = si.make_case("topn_home_tree", "bf16", 2, len(par), 32, 2, 192, 128, si.STD_NSA, [4100, 1500], 183, rho=0.6,
+                        parents=par)
+    run_refresh(dev_mod, oracle, case)
+    run_shared(dev_mod, oracle, case, 3)
+    # every key equal: all importances tie, the smallest indices win (the list of candidates overflows)
+    case = si.make_case("topn_home_ties", "f32", 1, 3, 4, 2, 64, 64, si.STD_NSA, [40000], 185, rho=0.0)
+    case.k[:] = 0.25
+    case.k_cmp[:] = 0.25
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
+    assert np.array_equal(sel, ref.sel_idx)
+    # l = 64, d = 16, l' = 64: seven compressed columns per block (the general form of the importance sum)
+    nsa = si.NsaParams(l=64, d=16, l_sel=64, n_sel=8, w=128)
+    case = si.make_case("topn_home_geometry", "f32", 2, 5, 8, 2, 64, 64, nsa, [3000, 1111], 187, rho=0.4)
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
+    assert np.array_equal(sel, ref.sel_idx)
+
+
 def test_library_flattening_reorders_a_tree_without_changing_results(dev_mod, oracle):
     """A BFS-ordered draft tree re-flattened to DFS with ssv_tree_flatten (Section 4.1): queries, gates and draft
     K/V rows are permuted with the returned order; every node keeps its output and index set.  All 21 draft slots
