@@ -132,9 +132,9 @@ def time_graph_replays(torch, devs, steps, warmup):
 
 def kernel_breakdown(devs, rounds, repeats):
     """Average launch duration (ms) of every kernel, measured with HIP events inside the library on the call's
-    stream.  repeats == 1: one launch per event pair, rotating over the input copies (cold caches); the
-    duration of an empty event pair, measured in the same call, is reported next to it.  repeats > 1: that
-    many back-to-back launches per pair on one copy (the event overhead amortises, but inputs of small
+    stream.  repeats == 1: one launch per kernel with start/stop events bound to the launch (the dispatch's own
+    begin and end, what a kernel trace reports), rotating over the input copies (cold caches).  repeats > 1: that
+    many back-to-back launches per event pair on one copy (the event overhead amortises, but inputs of small
     workloads stay cache-resident)."""
     from paper_2605_19893_amd import binding as B
     acc = np.zeros(B.SSV_NUM_TIMINGS)
@@ -158,6 +158,9 @@ def read_traffic(tag):
                     parts = line.split()
                     out[int(parts[1].rstrip(":"))] = int(parts[2]) + int(parts[3])
     return out
+
+
+COLD_ONLY = False   # --cold-only: profiling runs in which every launch of the trace sees cold inputs
 
 
 def measure_workload(torch, oracle, case, name, tag, steps, warmup, n_copies, parity=True, group_size=0):
@@ -185,13 +188,14 @@ def measure_workload(torch, oracle, case, name, tag, steps, warmup, n_copies, pa
             if mode == B.SSV_REUSE:
                 d.set_sel_idx(ref.sel_idx)
         cold_ms, cold_wall = time_calls(torch, devs, steps, warmup)
-        warm_ms, _ = time_calls(torch, devs[:1], steps, warmup)
-        graph_ms, graph_wall = time_graph_replays(torch, devs, steps, warmup)
+        nan = float("nan")
+        warm_ms, _ = (nan, nan) if COLD_ONLY else time_calls(torch, devs[:1], steps, warmup)
+        graph_ms, graph_wall = (nan, nan) if COLD_ONLY else time_graph_replays(torch, devs, steps, warmup)
         kms = kernel_breakdown(devs, 8, 1)
-        kms_rep = kernel_breakdown(devs[:1], 2, 20)
+        kms_rep = np.zeros_like(kms) if COLD_ONLY else kernel_breakdown(devs[:1], 2, 20)
         raw[mname] = kms
         nk = B.SSV_NUM_KERNELS
-        out_modes[mname] = {
+        out_modes[mname] = {k_: (None if isinstance(v_, float) and v_ != v_ else v_) for k_, v_ in {
             "plan": devs[0].plan.as_dict(),
             "us_per_call_cold": cold_ms * 1e3, "us_per_call_warm": warm_ms * 1e3, "us_per_call_cold_wallclock": cold_wall * 1e3,
             "us_per_call_cold_graph_replay": graph_ms * 1e3, "us_per_call_cold_graph_replay_wallclock": graph_wall * 1e3,
@@ -201,21 +205,20 @@ def measure_workload(torch, oracle, case, name, tag, steps, warmup, n_copies, pa
             "kernel_us_cold_single_launch": {B.kernel_name(i): float(kms[i] * 1e3) for i in range(nk) if kms[i] > 0},
             "event_pair_overhead_us": float(kms[B.SSV_T_EVENT_PAIR] * 1e3),
             "kernel_us_20_back_to_back_launches": {B.kernel_name(i): float(kms_rep[i] * 1e3) for i in range(nk) if kms_rep[i] > 0},
-        }
+        }.items()}
     res["modes"] = out_modes
     # roofline of the dominant kernel of the refresh path: algorithmic bytes of that launch over its average
-    # duration (one launch per event pair, cold inputs, minus the duration of an empty event pair)
+    # duration (one launch with its own start/stop events, cold inputs)
     kms = raw["refresh"]
     dom = int(np.argmax(kms[:B.SSV_NUM_KERNELS]))
     kbytes = {B.SSV_K_STREAM_A: ab["compressed"] + ab["window_union"],
               B.SSV_K_IMPORTANCE: ab["compressed"] * case.d_k // (case.d_k + case.d_v),
               B.SSV_K_STREAM_B: ab["selected_union"]}.get(dom, 0)
-    dur_ms = max(kms[dom] - kms[B.SSV_T_EVENT_PAIR], 1e-6)
+    dur_ms = max(kms[dom], 1e-6)
     achieved = kbytes / (dur_ms * 1e-3) / 1e9
     res["roofline"] = {"bound": "hbm", "kernel": B.kernel_name(dom), "achieved": achieved, "peak": HBM_PEAK_GBS,
                        "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(tag).get(dom),
-                       "algorithmic_bytes_per_launch": int(kbytes), "avg_launch_us": float(dur_ms * 1e3),
-                       "avg_launch_us_including_event_pair": float(kms[dom] * 1e3)}
+                       "algorithmic_bytes_per_launch": int(kbytes), "avg_launch_us": float(dur_ms * 1e3)}
     del devs
     torch.cuda.empty_cache()
     return res, ref
@@ -441,6 +444,9 @@ def main():
     ap.add_argument("--rho", type=float, default=0.5)
     ap.add_argument("--no-extra", action="store_true", help="skip the configuration-2 measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold-only", action="store_true",
+                    help="skip the warm-input, back-to-back and graph-replay measurements (for kernel traces: every "
+                         "launch then runs on cold inputs, like the timed calls)")
     ap.add_argument("--only", default="", help="measure only this workload (cfg1, cfg2, cfg3 or cfg4; for profiling runs), "
                     "'shared': the shared-index study alone, at T = 8 and T = 32, or 'kernel-workload': the paper's "
                     "isolated-kernel workload (32/8 heads of dimension 64, draft lengths 4 and 64, contexts 8K-64K), "
@@ -450,6 +456,8 @@ def main():
                     help="kept for the profiling commands: the plain 1 GiB device-to-device copy (a known-size reference for HBM "
                          "byte counters) now runs in every invocation")
     args = ap.parse_args()
+    global COLD_ONLY
+    COLD_ONLY = args.cold_only
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(sequences and KV heads are independent: more GPUs would each take a share of them, with no exchange)", file=sys.stderr)

@@ -137,12 +137,14 @@ int ssv_nsa_verify(const void* q, const void* k, const void* v, const void* k_cm
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Same computation, timed per kernel: every kernel of the call is launched `repeats` (1..1000) times back to
- * back between one pair of HIP events on `stream` (all kernels are idempotent, so the results are those of
- * ssv_nsa_verify); the call synchronises `stream` before returning and writes the average duration of one launch
- * of each kernel, in milliseconds, to kernel_ms[SSV_NUM_TIMINGS] (host; 0 for kernels the mode does not launch);
+ * Same computation, timed per kernel (all kernels are idempotent, so the results are those of ssv_nsa_verify); the
+ * call synchronises `stream` before returning and writes the average duration of one launch of each kernel, in
+ * milliseconds, to kernel_ms[SSV_NUM_TIMINGS] (host; 0 for kernels the mode does not launch).
+ * repeats == 1: every kernel is launched once with start and stop events bound to the launch itself, which read
+ * the dispatch's own begin and end (the duration a kernel trace shows for it).  repeats in 2..1000: every kernel
+ * is launched that many times back to back between one pair of events on `stream`.
  * kernel_ms[SSV_T_EVENT_PAIR] is the duration of an event pair with nothing in between, i.e. what the event
- * mechanism itself adds to every measured interval.
+ * mechanism adds to an interval measured the second way.
  * Measurement aid for the roofline figures (Section 7.3 reports such a per-kernel breakdown).
  */
 int ssv_nsa_verify_timed(const void* q, const void* k, const void* v, const void* k_cmp, const void* v_cmp,

@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/ssv_nsa.h: argument validation, launch planning,
 // and the launch sequences of the refresh (Section 5.1) and reuse (Section 5.2) paths.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <atomic>
 #include <cmath>
@@ -194,13 +195,20 @@ struct Timer {
     hipStream_t stream = nullptr;
     hipEvent_t ev[SSV_NUM_TIMINGS][2] = {};
     bool used[SSV_NUM_TIMINGS] = {};
-    int begin(int k) {
+    // One launch per kernel: its start and stop events are bound to the launch itself and read the dispatch's own
+    // begin and end, which is the duration a kernel trace reports.  Several launches: one event pair around them.
+    bool per_dispatch() const { return on && repeats == 1; }
+    int begin(int k, bool bracket_only = false) {
         if (!on) return 0;
         if (hipEventCreate(&ev[k][0]) != hipSuccess || hipEventCreate(&ev[k][1]) != hipSuccess) return -1;
         used[k] = true;
+        if (per_dispatch() && !bracket_only) return 0;
         return hipEventRecord(ev[k][0], stream) == hipSuccess ? 0 : -1;
     }
-    int end(int k) { return !on || hipEventRecord(ev[k][1], stream) == hipSuccess ? 0 : -1; }
+    int end(int k, bool bracket_only = false) {
+        if (!on || (per_dispatch() && !bracket_only)) return 0;
+        return hipEventRecord(ev[k][1], stream) == hipSuccess ? 0 : -1;
+    }
     int finish(float* ms) {
         int rc = 0;
         if (!on) return 0;
@@ -217,6 +225,15 @@ struct Timer {
         return rc;
     }
 };
+
+// Launch of timed kernel K_: with its own start/stop events when every kernel is launched once, plainly otherwise.
+#define SSV_LAUNCH(K_, KERNEL_, GRID_, LDS_, ARGS_)                                                                      \
+    do {                                                                                                                 \
+        if (tm.per_dispatch())                                                                                           \
+            hipExtLaunchKernelGGL(KERNEL_, dim3(GRID_), dim3(kThreads), (uint32_t)(LDS_), stream, tm.ev[K_][0], tm.ev[K_][1], 0, ARGS_); \
+        else                                                                                                             \
+            hipLaunchKernelGGL(KERNEL_, dim3(GRID_), dim3(kThreads), LDS_, stream, ARGS_);                               \
+    } while (0)
 
 template <bool BF16, int DK, int DV>
 int launch_all(const void* q, const void* k, const void* v, const void* kc, const void* vc, const float* gates,
@@ -267,14 +284,13 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     }
 
     const int reps = tm.on ? tm.repeats : 1;
-    auto launch_stream = [&](int slot_lo, int slot_cnt, int C, int n_qg) -> int {
+    auto launch_stream = [&](int K, int slot_lo, int slot_cnt, int C, int n_qg) -> int {
         sa.C = C; sa.n_qg = n_qg;
         sa.slot_lo = slot_lo; sa.slot_cnt = slot_cnt; sa.n_wg = p->B * p->H_kv * n_qg * slot_cnt;
         const int grid = ceil_div(sa.n_wg, 8) * 8;
         const bool all = slot_cnt == pl.n_slots, only_slc = slot_lo > 0;
         for (int r = 0; r < reps; ++r) {
-#define SSV_LAUNCH_STREAM(NRT_, ROLES_) \
-    hipLaunchKernelGGL((k_stream<BF16, DK, DV, NRT_, ROLES_>), dim3(grid), dim3(kThreads), lds_stream, stream, sa)
+#define SSV_LAUNCH_STREAM(NRT_, ROLES_) SSV_LAUNCH(K, (k_stream<BF16, DK, DV, NRT_, ROLES_>), grid, lds_stream, sa)
             if (C * lo.H_g > 64) {
                 if (all) SSV_LAUNCH_STREAM(2, kRolesAll);
                 else if (only_slc) SSV_LAUNCH_STREAM(2, kRolesSlc);
@@ -291,14 +307,14 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
 
     const int n_scan_slots = pl.n_cmp_chunks + pl.n_win_splits;
     if (lo.one_launch) {
-        if (tm.begin(SSV_K_STREAM_A) || launch_stream(0, pl.n_slots, pl.C, pl.n_qg) || tm.end(SSV_K_STREAM_A)) return SSV_ELAUNCH;
+        if (tm.begin(SSV_K_STREAM_A) || launch_stream(SSV_K_STREAM_A, 0, pl.n_slots, pl.C, pl.n_qg) || tm.end(SSV_K_STREAM_A)) return SSV_ELAUNCH;
     } else {
-        if (tm.begin(SSV_K_STREAM_A) || launch_stream(0, n_scan_slots, pl.C_scan, pl.n_qg_scan) || tm.end(SSV_K_STREAM_A))
+        if (tm.begin(SSV_K_STREAM_A) || launch_stream(SSV_K_STREAM_A, 0, n_scan_slots, pl.C_scan, pl.n_qg_scan) || tm.end(SSV_K_STREAM_A))
             return SSV_ELAUNCH;
     }
     if (p->mode == SSV_REUSE) {
         if (!lo.one_launch &&
-            (tm.begin(SSV_K_STREAM_B) || launch_stream(n_scan_slots, pl.n_slc_splits, pl.C, pl.n_qg) || tm.end(SSV_K_STREAM_B)))
+            (tm.begin(SSV_K_STREAM_B) || launch_stream(SSV_K_STREAM_B, n_scan_slots, pl.n_slc_splits, pl.C, pl.n_qg) || tm.end(SSV_K_STREAM_B)))
             return SSV_ELAUNCH;
     } else {
 
@@ -313,9 +329,9 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         const int grid_i = ceil_div(ia.n_wg, 8) * 8;
         if (tm.begin(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
         for (int r = 0; r < reps; ++r) {
-            if (lo.H_g == 16) hipLaunchKernelGGL((k_importance<BF16, DK, 16>), dim3(grid_i), dim3(kThreads), IC::LDS_RING, stream, ia);
-            else if (lo.H_g >= 4) hipLaunchKernelGGL((k_importance<BF16, DK, 4>), dim3(grid_i), dim3(kThreads), IC::LDS_RING, stream, ia);
-            else hipLaunchKernelGGL((k_importance<BF16, DK, 1>), dim3(grid_i), dim3(kThreads), IC::LDS_RING, stream, ia);
+            if (lo.H_g == 16) SSV_LAUNCH(SSV_K_IMPORTANCE, (k_importance<BF16, DK, 16>), grid_i, IC::LDS_RING, ia);
+            else if (lo.H_g >= 4) SSV_LAUNCH(SSV_K_IMPORTANCE, (k_importance<BF16, DK, 4>), grid_i, IC::LDS_RING, ia);
+            else SSV_LAUNCH(SSV_K_IMPORTANCE, (k_importance<BF16, DK, 1>), grid_i, IC::LDS_RING, ia);
         }
         if (hipGetLastError() != hipSuccess || tm.end(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
 
@@ -342,10 +358,10 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
                 return SSV_ELAUNCH;
             if (tm.begin(SSV_K_TOPN)) return SSV_ELAUNCH;
             for (int r = 0; r < reps; ++r)
-                hipLaunchKernelGGL(k_topn, dim3(p->B * p->T * p->H_kv), dim3(kThreads), lds_topn, stream, ta);
+                SSV_LAUNCH(SSV_K_TOPN, k_topn, p->B * p->T * p->H_kv, lds_topn, ta);
             if (hipGetLastError() != hipSuccess || tm.end(SSV_K_TOPN)) return SSV_ELAUNCH;
         }
-        if (tm.begin(SSV_K_STREAM_B) || launch_stream(n_scan_slots, pl.n_slc_splits, pl.C, pl.n_qg) ||
+        if (tm.begin(SSV_K_STREAM_B) || launch_stream(SSV_K_STREAM_B, n_scan_slots, pl.n_slc_splits, pl.C, pl.n_qg) ||
             tm.end(SSV_K_STREAM_B))
             return SSV_ELAUNCH;
     }
@@ -358,11 +374,11 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     const bool by_rows = pl.n_slots <= env_int("SSV_COMBINE_ROWS_MAX_SLOTS", 12);
     const int rows_per_wg = kThreads / (DV / 4);
     const int grid_c = by_rows ? (int)((lo.rows_total + rows_per_wg - 1) / rows_per_wg) : (int)lo.rows_total;
-    if (tm.begin(SSV_T_EVENT_PAIR) || tm.end(SSV_T_EVENT_PAIR)) return SSV_ELAUNCH;   // empty pair: the overhead itself
+    if (tm.begin(SSV_T_EVENT_PAIR, true) || tm.end(SSV_T_EVENT_PAIR, true)) return SSV_ELAUNCH;   // empty pair: the overhead itself
     if (tm.begin(SSV_K_COMBINE)) return SSV_ELAUNCH;
     for (int r = 0; r < reps; ++r) {
-        if (by_rows) hipLaunchKernelGGL((k_combine_rows<BF16, DV>), dim3(grid_c), dim3(kThreads), 0, stream, ca);
-        else hipLaunchKernelGGL((k_combine_slices<BF16, DV>), dim3(grid_c), dim3(kThreads), 0, stream, ca);
+        if (by_rows) SSV_LAUNCH(SSV_K_COMBINE, (k_combine_rows<BF16, DV>), grid_c, 0, ca);
+        else SSV_LAUNCH(SSV_K_COMBINE, (k_combine_slices<BF16, DV>), grid_c, 0, ca);
     }
     if (hipGetLastError() != hipSuccess || tm.end(SSV_K_COMBINE)) return SSV_ELAUNCH;
     return SSV_OK;
