@@ -203,31 +203,21 @@ struct DirectRowTile {
     }
 };
 
-// Layout of the bf16 V^T tile: row = value column (128 bytes, no padding) = 8 "pairs" of 16 bytes; pair
-// p = 4 u + G holds the two key quads (4 keys x 2 bytes each) 8 u + G and 8 u + 4 + G side by side, which
-// are exactly the eight keys lane group G feeds to one K=32 MFMA step u, so one 16-byte LDS read is a whole
-// MFMA operand.  The pair index is XOR-swizzled with sw(c) = (c ^ (c >> 3)) & 7 of the column so that both
-// access patterns spread over the banks: the operand load (8 lanes = 8 consecutive columns, same pair) and
-// the transposing store (16 lanes = 16 columns that are 8 apart, same pair: 2-way at worst).  Because XOR
-// distributes, a lane needs one base offset and every unrolled access is (base ^ constant) + constant:
-//   store, lane (key quad kq = 8 u + 4 h + G, chunk ch), column 8 ch + cc:
-//       (ch * 1024 + ((4 u ^ G ^ (ch & 7)) * 16) + 8 h) ^ (cc * 16)  +  cc * 128
-//   load,  lane (n, G), column 16 mt + n, pair 4 u + G:
-//       (n * 128 + ((G ^ (n & 7) ^ (n >> 3)) & 7) * 16) ^ (16 * ((4 u) ^ ((2 mt) & 7)))  +  mt * 2048
-constexpr int kVtPitchBf16 = 128;
-__device__ __forceinline__ int vt_store_base_bf16(int kq, int ch) {
-    const int u = kq >> 3, h = (kq >> 2) & 1, G = kq & 3;
-    return ch * 8 * kVtPitchBf16 + (((4 * u) ^ G ^ (ch & 7)) & 7) * 16 + 8 * h;
-}
-__device__ __forceinline__ int vt_load_base_bf16(int n, int G) {
-    return n * kVtPitchBf16 + ((G ^ (n & 7) ^ (n >> 3)) & 7) * 16;
+// Transposing LDS read of gfx950 (ds_read_b64_tr_b16), per group of 16 lanes: the 16 lanes supply the addresses of
+// sixteen 8-byte chunks (4 bf16 each); lane i of the group receives element (i & 3) of the chunks supplied by lanes
+// (i >> 2), (i >> 2) + 4, + 8, + 12 (measured on the device).  With lane i pointing at key row (i >> 2) of four
+// consecutive keys, 8-byte column chunk (i & 3) of a 16-column tile, lane n receives column n of the four keys: the
+// A operand of O^T = V^T P^T straight from a row-major V tile.
+__device__ __forceinline__ u32x2 lds_read_tr16(const char* p) {
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+    return __builtin_bit_cast(u32x2, v);
 }
 
-// Transposing load: 64 rows x DV values (row-major in global memory) become LDS rows indexed by
-// the value column, each holding the 64 keys contiguously (pitch PITCH), which is the operand
-// layout the P.V MFMA needs (the contraction index, the key, must run along a lane's registers).
-// Each work item reads four consecutive key rows of one 16-byte column chunk and writes, per
-// value column, the four keys as one 8-byte (bf16) or 16-byte (fp32) LDS store.
+// A V tile on its way from global memory to LDS: 64 rows x DV values, staged in registers for one tile step.  Each
+// work item reads four consecutive key rows of one 16-byte column chunk.  bf16 tiles are stored as they are
+// (commit_rows) and transposed by the LDS reads; fp32 tiles are transposed here (commit): LDS rows indexed by the
+// value column, each holding the 64 keys contiguously (pitch PITCH), one 16-byte store per column and key quad.
 template <bool BF16, int DV>
 struct TransposedTileRegs {
     static constexpr int ES = BF16 ? 2 : 4;
@@ -266,6 +256,24 @@ struct TransposedTileRegs {
             }
         }
     }
+    // The rows as they are (bf16): row r at r * PITCH, for the transposing LDS reads of gfx950 (vt_read_tr below).
+    // PITCH is the row plus 32 bytes, which spreads the eight rows one read pass touches over all banks.
+    template <int PITCH>
+    __device__ __forceinline__ void commit_rows(char* lds, int valid_rows, int tid) {
+        static_assert(BF16 && PITCH == DV * 2 + 32, "row-major V tile: bf16 only, padded pitch");
+        if (ITEMS < kThreads && tid >= ITEMS) return;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int item = it * kThreads + tid;
+            const int kq = item / CPR, ch = item % CPR;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                u32x4 v = r[it][j];
+                if (valid_rows < kTile && 4 * kq + j >= valid_rows) v = u32x4{0, 0, 0, 0};   // uniform test first; rare
+                *reinterpret_cast<u32x4*>(lds + (4 * kq + j) * PITCH + ch * 16) = v;
+            }
+        }
+    }
     template <int PITCH>
     __device__ __forceinline__ void commit(char* lds, int valid_rows, int tid) {
         if (ITEMS < kThreads && tid >= ITEMS) return;
@@ -278,22 +286,8 @@ struct TransposedTileRegs {
                 for (int j = 0; j < 4; ++j)
                     if (4 * kq + j >= valid_rows) r[it][j] = u32x4{0, 0, 0, 0};
             }
-            if constexpr (BF16) {
-                static_assert(PITCH == kVtPitchBf16, "the swizzled bf16 V^T tile has no padding");
-                const int wb = vt_store_base_bf16(kq, ch);
-#pragma unroll
-                for (int e2 = 0; e2 < 4; ++e2) {    // 32-bit word e2 of the chunk holds columns 2 e2 and 2 e2 + 1
-                    const uint32_t w0 = r[it][0][e2], w1 = r[it][1][e2], w2 = r[it][2][e2], w3 = r[it][3][e2];
-                    u32x2 lo, hi;
-                    lo[0] = (w0 & 0xFFFFu) | (w1 << 16);
-                    lo[1] = (w2 & 0xFFFFu) | (w3 << 16);
-                    hi[0] = (w0 >> 16) | (w1 & 0xFFFF0000u);
-                    hi[1] = (w2 >> 16) | (w3 & 0xFFFF0000u);
-                    const int cc = 2 * e2;
-                    *reinterpret_cast<u32x2*>(lds + (wb ^ (cc * 16)) + cc * PITCH) = lo;
-                    *reinterpret_cast<u32x2*>(lds + (wb ^ ((cc + 1) * 16)) + (cc + 1) * PITCH) = hi;
-                }
-            } else {
+            static_assert(!BF16, "bf16 tiles stay row-major (commit_rows)");
+            {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const u32x4 o = {r[it][0][e], r[it][1][e], r[it][2][e], r[it][3][e]};

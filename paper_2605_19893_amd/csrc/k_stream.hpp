@@ -53,10 +53,11 @@ struct StreamCfg {
     static constexpr int KROW = DK * ES;            // bytes per K row
     static constexpr int LDS_KD = kTile * KROW;     // one K tile in LDS (unpadded, granules swizzled); there are two
     static constexpr int KCH = KROW / 64;           // 64-byte chunks per K row
-    static constexpr int VP = kTile * ES + (BF16 ? 0 : 16);   // LDS pitch of a V^T row (64 keys); bf16 rows are swizzled
+    static constexpr int VP = kTile * ES + 16;      // fp32: LDS pitch of a V^T row (64 keys)
+    static constexpr int VR = DV * ES + 32;         // bf16: LDS pitch of a V row (the tile stays row-major)
     static constexpr int MT = DV / 16;              // 16-row tiles of O^T
     static constexpr int LDS_K = 2 * LDS_KD;
-    static constexpr int LDS_VT = DV * VP;
+    static constexpr int LDS_VT = BF16 ? kTile * VR : DV * VP;
 };
 
 __host__ __device__ inline size_t stream_lds_bytes(size_t lds_k, size_t lds_vt, int max_sched, int bitmap_words) {
@@ -105,7 +106,7 @@ constexpr int kRolesCmpWin = 3, kRolesSlc = 4, kRolesAll = 7;
 template <bool BF16, int DK, int DV, int NRT, int ROLES>
 __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_eu(2, 2))) k_stream(const StreamArgs a) {
     using Cfg = StreamCfg<BF16, DK, DV>;
-    constexpr int ES = Cfg::ES, KROWB = Cfg::KROW, KCH = Cfg::KCH, VP = Cfg::VP, MT = Cfg::MT;
+    constexpr int ES = Cfg::ES, KROWB = Cfg::KROW, KCH = Cfg::KCH, VP = Cfg::VP, VR = Cfg::VR, MT = Cfg::MT;
     extern __shared__ __align__(16) char smem[];
     char* sK0 = smem;                  // two K tiles: the global->LDS loads of tile i+1 land while tile i is read
     char* sVT = sK0 + Cfg::LDS_K;
@@ -294,7 +295,9 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
         vrow = a.v_s[2];
     }
     const int rows_exist = r_cmp ? sm.n_cmp : n_slots_kv;
-    const int vt_rb = vt_load_base_bf16(n, G);   // this lane's base offset into the swizzled bf16 V^T tile
+    // bf16: this lane's address into the row-major V tile for the transposing reads: key row 4 G + (n >> 2) of each
+    // run of 16 keys, 8-byte chunk (n & 3) of each 16-column tile
+    const int vt_rb = (4 * G + (n >> 2)) * VR + (n & 3) * 8;
     SSV_STAMP(3);
 
     // Software pipeline: the global loads of tile it+1 are issued before tile it is computed.  K goes straight into
@@ -350,7 +353,8 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): separate the wait for the prefetched loads from the LDS stores
         SSV_PHASE(1);
 #endif
-        vcur.template commit<VP>(sVT, valid_rows, tid);
+        if constexpr (BF16) vcur.template commit_rows<VR>(sVT, valid_rows, tid);
+        else vcur.template commit<VP>(sVT, valid_rows, tid);
         if (has_drafts && tid < kTile) {   // absolute position of every key of the tile (tree drafts: L + depth)
             const int s = base + tid;
             s_kpos[tid] = s < L ? s : (s - L < Tq ? L + s_depth[s - L] : 0x7fffffff);
@@ -506,17 +510,20 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
                     }
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
-                        const u32x4 vf = lds_read16(sVT + (vt_rb ^ (16 * ((4 * u) ^ ((2 * mt) & 7)))) + mt * 16 * VP);
+                        // keys 32 u + 4 G + e and 32 u + 16 + 4 G + e (e = 0..3) of column 16 mt + n: the order of pb
+                        const u32x2 v0 = lds_read_tr16(sVT + vt_rb + (32 * u) * VR + mt * 32);
+                        const u32x2 v1 = lds_read_tr16(sVT + vt_rb + (32 * u + 16) * VR + mt * 32);
+                        const u32x4 vf = {v0[0], v0[1], v1[0], v1[1]};
 #pragma unroll
                         for (int t = 0; t < NRT; ++t) acc[t][mt] = mma_frag<true>(vf, pb[t], acc[t][mt]);
                     }
                     {
-                        constexpr int LEAD = 4;
-                        __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0);
+                        constexpr int LEAD = 4;      // fragments (two reads each) ahead of their MFMAs
+                        __builtin_amdgcn_sched_group_barrier(0x100, 2 * LEAD, 0);
 #pragma unroll
                         for (int i = 0; i < MT - LEAD; ++i) {
                             __builtin_amdgcn_sched_group_barrier(0x008, NRT, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
                         }
                         __builtin_amdgcn_sched_group_barrier(0x008, LEAD * NRT, 0);
                     }
