@@ -267,16 +267,18 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     }
     const size_t lds_stream = stream_lds_bytes(SC::LDS_K, SC::LDS_VT, sa.max_sched, sa.bitmap_words);
     if (lds_stream > 80 * 1024) return SSV_EUNSUPPORTED;     // two workgroups per CU; merged schedules of very large groups do not fit
-    if (lds_stream > 64 * 1024) {
-        // more than the default dynamic LDS limit: raise it once per device for the kernels of this shape (repeating
-        // the call after a lost race between two host threads is harmless)
+    {
+        // kernels that may ask for more than 64 KB of dynamic LDS: raise their limit once per device (repeating the
+        // calls after a lost race between two host threads is harmless)
         static std::atomic<bool> raised[kMaxDevices];
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SSV_ELAUNCH;
         if (!raised[dev].load(std::memory_order_acquire)) {
             const void* fns[] = {(const void*)k_stream<BF16, DK, DV, 1, kRolesAll>, (const void*)k_stream<BF16, DK, DV, 1, kRolesSlc>,
                                  (const void*)k_stream<BF16, DK, DV, 1, kRolesCmpWin>, (const void*)k_stream<BF16, DK, DV, 2, kRolesAll>,
-                                 (const void*)k_stream<BF16, DK, DV, 2, kRolesSlc>, (const void*)k_stream<BF16, DK, DV, 2, kRolesCmpWin>};
+                                 (const void*)k_stream<BF16, DK, DV, 2, kRolesSlc>, (const void*)k_stream<BF16, DK, DV, 2, kRolesCmpWin>,
+                                 (const void*)k_importance<BF16, DK, 16>, (const void*)k_importance<BF16, DK, 4>,
+                                 (const void*)k_importance<BF16, DK, 1>};
             for (const void* fn : fns)
                 if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess) return SSV_ELAUNCH;
             raised[dev].store(true, std::memory_order_release);
