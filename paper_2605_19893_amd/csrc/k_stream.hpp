@@ -301,10 +301,10 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
     SSV_STAMP(3);
 
     // Software pipeline: the global loads of tile it+1 are issued before tile it is computed.  K goes straight into
-    // the other of two LDS tiles (no registers, no LDS stores); V is staged in registers because it is transposed on
-    // its way into LDS, and is committed one tile later.  Two barriers per tile separate the LDS writes from the
-    // fragment reads.  Measured with in-kernel clocks, the prefetched loads have always arrived by the time they are
-    // needed at one tile ahead (the tile loop is bound by its own instruction stream); two tiles ahead bought nothing.
+    // the other of two LDS tiles (no registers, no LDS stores); V is staged in registers for one tile step (LDS has
+    // no room for a second V tile at two workgroups per CU) and stored to LDS at the start of its own step.  Two
+    // barriers per tile separate the LDS writes from the fragment reads.  Measured with in-kernel clocks, the
+    // prefetched loads have nearly always arrived by the time they are needed at one tile ahead.
     constexpr int AHEAD = 1;
     const __amdgpu_buffer_rsrc_t krsrc = DirectRowTile<Cfg::KROW>::make_rsrc(kbase, (int64_t)max(rows_exist, 0) * krow);
     DirectRowTile<Cfg::KROW> kdir;

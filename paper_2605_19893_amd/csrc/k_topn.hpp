@@ -67,20 +67,18 @@ __host__ __device__ inline size_t topn_lds_bytes(int max_blocks) {
 
 struct WaveTopnScratch {             // one per wavefront, in LDS
     uint32_t* bits;                  // [J + 1] importance bit patterns (forced blocks: +inf)
-    uint64_t* best;                  // [64]
-    uint64_t* cand;                  // [kWaveMaxCand]
+    uint64_t* cand;                  // [kWaveMaxCand + 8]
     int* pick;                       // [kMaxNSel]
 };
 constexpr int kWaveMaxCand = 256;
 __host__ __device__ inline size_t wave_topn_lds_bytes(int max_blocks) {   // per wavefront, 16-byte multiple
-    return (((size_t)max_blocks * 4 + 15) & ~(size_t)15) + 64 * 8 + kWaveMaxCand * 8 + kMaxNSel * 4;
+    return (((size_t)max_blocks * 4 + 15) & ~(size_t)15) + (kWaveMaxCand + 8) * 8 + kMaxNSel * 4;
 }
 __device__ __forceinline__ WaveTopnScratch wave_topn_scratch(char* base, int max_blocks) {
     WaveTopnScratch w;
     w.bits = reinterpret_cast<uint32_t*>(base);
-    w.best = reinterpret_cast<uint64_t*>(base + (((size_t)max_blocks * 4 + 15) & ~(size_t)15));
-    w.cand = w.best + 64;
-    w.pick = reinterpret_cast<int*>(w.cand + kWaveMaxCand);
+    w.cand = reinterpret_cast<uint64_t*>(base + (((size_t)max_blocks * 4 + 15) & ~(size_t)15));
+    w.pick = reinterpret_cast<int*>(w.cand + kWaveMaxCand + 8);
     return w;
 }
 // LDS written by some lanes of a wavefront is read by others: the LDS unit takes a wavefront's operations in order,
@@ -103,7 +101,8 @@ __device__ __forceinline__ void wave_topn(const float* cs, int ncv, int J, int l
     const int n_terms = a_ratio + b_ratio - 1;
     const int j_last_scored = J - max(n_local, 0);
     uint64_t best = 0;
-    for (int j = max(j_last_scored + 1, 0) + lane; j <= J; j += 64) {     // forced trailing local blocks
+    for (int j = max(j_last_scored + 1, 0); j <= J; ++j) {     // forced trailing local blocks, each with its owner lane
+        if ((j & 63) != lane) continue;
         w.bits[j] = 0x7F800000u;
         const uint64_t key = topn_key(0x7F800000u, j);
         best = key > best ? key : best;
@@ -186,45 +185,50 @@ __device__ __forceinline__ void wave_topn(const float* cs, int ncv, int J, int l
             }
         }
     }
-    w.best[lane] = best;
-    wave_lds_sync();
-    // threshold: the n_eff-th largest of the 64 per-lane bests (distinct keys; lanes without blocks hold 0); with
-    // fewer than n_eff of them it stays 0 and every block is a candidate
-    uint64_t thr = 0;
+    // Threshold on the importance bits alone: the largest value (to 23 bits) that at least n_eff of the 64 per-lane
+    // bests reach, found by bisection with wave-wide votes.  The lanes' bests are distinct blocks, so at least n_eff
+    // blocks reach it and every winner does; blocks that reach it are the candidates (lanes without blocks hold 0,
+    // and with fewer than n_eff bests the threshold stays 0: every block is a candidate).
+    uint32_t thr_bits = 0;
     {
-        int rank = 0;
-#pragma unroll 16
-        for (int k = 0; k < 64; ++k) rank += w.best[k] > best;
-        const uint64_t hit = __builtin_amdgcn_ballot_w64(best != 0 && rank == n_eff - 1);
-        if (hit) {
-            const int src = __builtin_ctzll(hit);
-            thr = ((uint64_t)(uint32_t)__shfl((int)(best >> 32), src) << 32) | (uint32_t)__shfl((int)(uint32_t)best, src);
+        const uint32_t mine = (uint32_t)(best >> 32);
+        for (int bit = 30; bit >= 8; --bit) {
+            const uint32_t trial = thr_bits | (1u << bit);
+            if (__popcll(__builtin_amdgcn_ballot_w64(mine >= trial)) >= n_eff) thr_bits = trial;
         }
     }
+    wave_lds_sync();      // the importance bits written above are read by other lanes below
     int n_cand = 0;
-    for (int jb = 0; jb <= J; jb += 64) {
-        const int j = jb + lane;
-        const uint64_t key = j <= J ? topn_key(w.bits[j], j) : 0ull;
-        const bool is = j <= J && key >= thr;
-        const uint64_t m = __builtin_amdgcn_ballot_w64(is);
-        const int pos = n_cand + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-        if (is && pos < kWaveMaxCand) w.cand[pos] = key;
-        n_cand += __popcll(m);
+    constexpr int NC = 8;     // blocks per lane whose LDS reads are in flight together
+    for (int jb = 0; jb <= J; jb += 64 * NC) {
+        uint32_t bits[NC];
+#pragma unroll
+        for (int u = 0; u < NC; ++u) bits[u] = w.bits[min(jb + 64 * u + lane, J)];
+#pragma unroll
+        for (int u = 0; u < NC; ++u) {
+            const int j = jb + 64 * u + lane;
+            if (jb + 64 * u > J) break;               // uniform
+            const bool is = j <= J && bits[u] >= thr_bits;
+            const uint64_t m = __builtin_amdgcn_ballot_w64(is);
+            const int pos = n_cand + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            if (is && pos < kWaveMaxCand) w.cand[pos] = topn_key(bits[u], j);
+            n_cand += __popcll(m);
+        }
     }
+    // pad the list to a multiple of 8 with keys that are larger than none (the counting loop below reads in eights)
+    if (lane < 8 && n_cand + lane < kWaveMaxCand + 8) w.cand[min(n_cand, kWaveMaxCand) + lane] = 0ull;
     wave_lds_sync();
     if (n_cand <= kWaveMaxCand) {
         for (int e = lane; e < n_cand; e += 64) {      // rank candidates by counting; ranks below n_eff are the selection
             const uint64_t key = w.cand[e];
             int rank = 0;
-            int f = 0;
-            for (; f + 8 <= n_cand; f += 8) {
+            for (int f = 0; f < n_cand; f += 8) {
                 uint64_t c[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) c[u] = w.cand[f + u];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) rank += c[u] > key;
             }
-            for (; f < n_cand; ++f) rank += w.cand[f] > key;
             if (rank < n_eff) w.pick[rank] = (int)(0xFFFFFFFFu - (uint32_t)key);
         }
     } else {
@@ -232,7 +236,8 @@ __device__ __forceinline__ void wave_topn(const float* cs, int ncv, int J, int l
         for (int round = 0; round < n_eff; ++round) {
             const uint64_t top = wave_max_u64(best);
             const int j_top = (int)(0xFFFFFFFFu - (uint32_t)top);
-            if (lane == 0) w.pick[round] = j_top;
+            if (lane == 0) w.pick[round] = top ? j_top : 0;
+            if (!top) continue;       // (cannot happen: there are at least n_eff blocks)
             if ((j_top & 63) == lane) {
                 w.bits[j_top] = 0xFFFFFFFFu;      // retired (no importance has this pattern)
                 best = 0;
@@ -251,7 +256,11 @@ __device__ __forceinline__ void wave_topn(const float* cs, int ncv, int J, int l
         if (lane < n_eff) {
             pick = w.pick[lane];
             rank = 0;
-            for (int f = 0; f < n_eff; ++f) rank += w.pick[f] < pick;
+            int p[kMaxNSel];
+#pragma unroll
+            for (int f = 0; f < kMaxNSel; ++f) p[f] = w.pick[f];      // (entries past n_eff are not used)
+#pragma unroll
+            for (int f = 0; f < kMaxNSel; ++f) rank += (f < n_eff && p[f] < pick) ? 1 : 0;
         }
         out[rank] = pick;
     }
