@@ -13,11 +13,12 @@
 // cross-lane exchanges.
 //
 // Work split: a workgroup holds the (at most 64) rows of its routed queries; every wavefront keeps ALL of
-// them in registers as A operands and takes its own strip of 16 keys of every 64-key tile, whose K rows it loads
-// from global memory directly in B-operand layout.  So K never passes through LDS (with 16 rows per
-// wavefront, every wavefront had to read the whole tile from LDS: four times the tile per step, which
-// bound the kernel), the main loop has no barrier, and the head-summed probabilities go from registers to
-// global memory.
+// them in registers as A operands and takes its own strip of 16 keys of every 64-key tile, whose K rows it streams
+// from global memory, in B-operand layout, through a private ring of LDS slots (buffer loads with the LDS
+// destination: the registers are taken by the A operands, and a lane reads back exactly the 16 bytes it
+// fetched).  So no wavefront reads another's K from LDS (with 16 rows per wavefront every wavefront read the
+// whole tile: four times the tile per step), the main loop has no barrier, and the head-summed probabilities go
+// from registers to global memory.
 #pragma once
 #include "k_stream.hpp"
 
