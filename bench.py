@@ -419,7 +419,7 @@ def compress_study(torch, si, steps, warmup):
     return res
 
 
-def cpu_baseline(oracle, case, budget_s=8.0):
+def cpu_baseline(oracle, case, budget_s=12.0):
     """The oracle as it stands, timed on this machine's host cores on the same workload."""
     threads = oracle.default_threads()
     tokens = int(case.n_query.sum())
@@ -429,7 +429,7 @@ def cpu_baseline(oracle, case, budget_s=8.0):
         oracle.nsa_verify(case)
         reps += 1
         el = time.perf_counter() - t0
-        if el >= budget_s or reps >= 200:
+        if el >= budget_s or reps >= 2000:
             break
     return {"value": tokens * reps / el, "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "sample": f"the full headline workload ({tokens} verifier queries x all heads), {reps} repetitions, "
