@@ -54,10 +54,14 @@ extern "C" {
 #define SSV_MAX_T 128         /* verifier queries per sequence */
 
 /* kernels of one call, in launch order (indices into kernel_ms of ssv_nsa_verify_timed) */
-#define SSV_K_STREAM_A  0     /* refresh: compressed scan + window;  reuse: compressed + window + selected */
+#define SSV_K_STREAM_A  0     /* refresh: compressed scan + window;  reuse: compressed + window (+ selected, unless
+                                 SSV_K_STREAM_B is launched) */
 #define SSV_K_IMPORTANCE 1    /* refresh only: normalised compressed probabilities summed over the group's heads */
-#define SSV_K_TOPN      2     /* refresh only: block importance + top-n selection */
-#define SSV_K_STREAM_B  3     /* refresh only: selected-block attention over the merged schedule */
+#define SSV_K_TOPN      2     /* refresh only: block importance + top-n selection; not launched (time 0) when the
+                                 selection runs inside SSV_K_STREAM_B, which it does when that launch has at most
+                                 one workgroup per CU */
+#define SSV_K_STREAM_B  3     /* selected-block attention over the merged schedule: refresh, and reuse when the scans
+                                 of SSV_K_STREAM_A use larger query groups than the selected branch (plan.C_scan > C) */
 #define SSV_K_COMBINE   4     /* merge of split partial states + gated combination */
 #define SSV_NUM_KERNELS 5
 #define SSV_T_EVENT_PAIR 5    /* ssv_nsa_verify_timed only: duration of an empty event pair (measurement overhead) */
