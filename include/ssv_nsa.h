@@ -16,16 +16,18 @@
  *
  * Conventions
  *  - Every data pointer is DEVICE memory owned by the caller; `p`, return codes and
- *    `kernel_ms` are HOST.  The library allocates nothing; scratch comes from `workspace`.
+ *    `kernel_ms` are HOST.  The library allocates nothing; scratch comes from `workspace`.  Nothing in the call path reads
+ *    the process environment: every choice is a field of the parameter struct, 0 meaning automatic.
  *  - All work is enqueued on `stream` (a hipStream_t passed as void*); ssv_nsa_verify never
  *    synchronises.  Nothing is launched when an error code is returned.
  *  - Per sequence b: L = seq_lens[b] committed tokens occupy KV slots 0..L-1 (slot =
  *    position); draft token i (flattened order) occupies slot L+i.  parents[b*T+i] is -1
  *    (child of the last committed token) or the index (< i) of the parent draft token.
  *    Draft token i sees the L committed tokens, itself and its ancestors.
- *  - Layout: q [B,T,H,d_k] and out [B,T,H,d_v] contiguous; k, v, k_cmp, v_cmp addressed as
- *    base + b*stride[0] + kv_head*stride[1] + row*stride[2] (+ contiguous feature), strides
- *    in elements; gates [B,T,H,3] float32 in the order (compressed, selected, window);
+ *  - Layout: q [B,T,H,d_k] and out [B,T,H,d_v], contiguous unless q_stride / out_stride say
+ *    otherwise (elements: batch, query, head; the feature dimension is contiguous); k, v, k_cmp,
+ *    v_cmp addressed as base + b*stride[0] + kv_head*stride[1] + row*stride[2] (+ contiguous
+ *    feature), strides in elements; gates [B,T,H,3] float32 in the order (compressed, selected, window);
  *    sel_idx [B,T,H_kv,n_sel] int32, ascending, padded with -1.
  */
 #ifndef SSV_NSA_H
@@ -53,6 +55,18 @@ extern "C" {
 
 #define SSV_MAX_T 128         /* verifier queries per sequence */
 
+/* ssv_nsa_params.exec: how the call is executed (never changes what is computed beyond rounding) */
+#define SSV_EXEC_FUSED   0    /* grouped queries, merged schedule, branches fused: the path this library is built for */
+#define SSV_EXEC_UNFUSED 1    /* the execution the fused path replaces (Section 5, the original NSA kernel structure; the
+                                 baseline side of the ratios of Section 7.3): every verifier query on its own (no
+                                 grouping, no merged schedule), one launch per branch, each branch output normalised and
+                                 written to scratch in the storage type, then read back by a separate gate kernel */
+
+/* ssv_nsa_params.topn_home: where the top-n selection of a refresh call runs */
+#define SSV_TOPN_AUTO     0   /* inside the selected-branch launch when that launch has at most one workgroup per CU */
+#define SSV_TOPN_SEPARATE 1   /* always a launch of its own */
+#define SSV_TOPN_IN_SLC   2   /* inside the selected-branch launch whenever its scratch fits the tile buffers */
+
 /* kernels of one call, in launch order (indices into kernel_ms of ssv_nsa_verify_timed) */
 #define SSV_K_STREAM_A  0     /* refresh: compressed scan + window;  reuse: compressed + window (+ selected, unless
                                  SSV_K_STREAM_B is launched) */
@@ -63,9 +77,16 @@ extern "C" {
 #define SSV_K_STREAM_B  3     /* selected-block attention over the merged schedule: refresh, and reuse when the scans
                                  of SSV_K_STREAM_A use larger query groups than the selected branch (plan.C_scan > C) */
 #define SSV_K_COMBINE   4     /* merge of split partial states + gated combination */
-#define SSV_NUM_KERNELS 5
-#define SSV_T_EVENT_PAIR 5    /* ssv_nsa_verify_timed only: duration of an empty event pair (measurement overhead) */
-#define SSV_NUM_TIMINGS 6
+#define SSV_K_STREAM_W  5     /* SSV_EXEC_UNFUSED only: the window branch as a launch of its own (SSV_K_STREAM_A then is
+                                 the compressed branch alone) */
+#define SSV_K_OUT_CMP   6     /* SSV_EXEC_UNFUSED only: merge of the compressed branch's partial states, branch output
+                                 written to scratch; SSV_K_OUT_SLC, SSV_K_OUT_WIN: the same for the other two
+                                 branches; SSV_K_COMBINE then is the gate kernel that reads the three back */
+#define SSV_K_OUT_SLC   7
+#define SSV_K_OUT_WIN   8
+#define SSV_NUM_KERNELS 9
+#define SSV_T_EVENT_PAIR 9    /* ssv_nsa_verify_timed only: duration of an empty event pair (measurement overhead) */
+#define SSV_NUM_TIMINGS 10
 
 typedef struct ssv_nsa_params {
     int32_t B;            /* sequences in the batch */
@@ -93,6 +114,13 @@ typedef struct ssv_nsa_params {
                              times H_g <= 128); 0 = automatic: group_size if that is given, else up to 128 rows where
                              the scans keep the chip busy for several rounds; never changes the result */
     int64_t k_stride[3], v_stride[3], kc_stride[3], vc_stride[3];  /* elements: batch, KV head, row */
+    int64_t q_stride[3], out_stride[3];  /* elements: batch, query, head; all zero = contiguous [B,T,H,d] */
+    int32_t exec;         /* SSV_EXEC_FUSED or SSV_EXEC_UNFUSED (SSV_REFRESH and SSV_REUSE only; group_size and
+                             scan_group_size must be 0 or 1 there) */
+    int32_t topn_home;    /* SSV_TOPN_AUTO, SSV_TOPN_SEPARATE or SSV_TOPN_IN_SLC; never changes the result */
+    int32_t max_slice_tiles; /* upper bound on the 64-row tiles one workgroup streams when a launch needs several
+                             rounds of workgroups (2..64; 0 = automatic: 24); never changes the result */
+    int32_t reserved;     /* must be 0 */
 } ssv_nsa_params;
 
 /* How one call is cut into workgroups (host-side planning; filled by ssv_nsa_plan). */
@@ -112,6 +140,9 @@ typedef struct ssv_nsa_plan {
                                  query of a sequence reads the same rows there, so larger groups only save loads;
                                  the merged schedule of the selected branch grows with its group) */
     int32_t n_qg_scan;        /* such groups per (sequence, KV head) */
+    int32_t topn_in_slc;      /* refresh: 1 if the top-n selection runs inside the selected-branch launch, else 0 */
+    int32_t n_imp_chunks;     /* refresh: workgroups splitting the importance pass over k_cmp of one query group */
+    int32_t n_launches;       /* kernel launches of one call */
     int64_t workspace_bytes;
 } ssv_nsa_plan;
 
@@ -241,7 +272,8 @@ int ssv_guard_observe(ssv_guard_state* state, double accepted_tokens, double ste
 #define SSV_TREE_DFS 1
 int ssv_tree_flatten(const int32_t* parents, int32_t n, int32_t order, int32_t* perm, int32_t* new_parents);
 
-/* Validates p (host only, no GPU needed) and describes the launch plan.  Returns SSV_OK or an error code. */
+/* Validates p (host only, no GPU needed) and describes the launch plan.  Returns SSV_OK or an error code; a p that
+ * this call accepts is accepted by ssv_nsa_workspace_bytes and ssv_nsa_verify too (the same checks run in all three). */
 int ssv_nsa_plan_query(const ssv_nsa_params* p, ssv_nsa_plan* plan);
 
 /* Scratch bytes ssv_nsa_verify needs for p; 0 if p is invalid. */

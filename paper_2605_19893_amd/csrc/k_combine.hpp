@@ -22,7 +22,18 @@ struct CombineArgs {
     int T, H;
     int n_cmp_chunks, n_win_splits, n_slc_splits;
     int64_t rows_total;
+    int64_t out_s[3];     // bytes: sequence, query, head
+    // k_combine_rows only: branches [br_lo, br_hi) in gate order (compressed, selected, window) are merged; with
+    // use_gates == 0 their normalised sum is written as it is (one branch: that branch's output)
+    int br_lo, br_hi, use_gates;
 };
+
+// byte offset of output row (b, i, h)
+__device__ __forceinline__ int64_t out_row_offset(const CombineArgs& a, int64_t row) {
+    const int h = (int)(row % a.H), i = (int)((row / a.H) % a.T);
+    const int64_t b = row / ((int64_t)a.H * a.T);
+    return b * a.out_s[0] + i * a.out_s[1] + h * a.out_s[2];
+}
 
 constexpr int kMaxSlotsPerBranch = 64;
 
@@ -45,6 +56,7 @@ __global__ void __launch_bounds__(kThreads) k_combine_rows(const CombineArgs a) 
         const int cnt3[3] = {a.n_cmp_chunks, a.n_slc_splits, a.n_win_splits};
 #pragma unroll
         for (int br = 0; br < 3; ++br) {
+            if (br < a.br_lo || br >= a.br_hi) continue;
             const int lo = lo3[br], cnt = cnt3[br];
             const float* st_base = a.part_stats + ((int64_t)lo * a.rows_total + row) * 2;
             // branch maximum and total, one pass with a running maximum (slices that saw no key have Z = 0)
@@ -64,7 +76,7 @@ __global__ void __launch_bounds__(kThreads) k_combine_rows(const CombineArgs a) 
                 }
             }
             if (!(Zt > 0.f)) continue;
-            const float scale = a.gates[row * 3 + br] / Zt;
+            const float scale = (a.use_gates ? a.gates[row * 3 + br] : 1.f) / Zt;
             for (int s0 = 0; s0 < cnt; s0 += 4) {
                 float w[4];
                 f32x4 v[4];
@@ -88,9 +100,9 @@ __global__ void __launch_bounds__(kThreads) k_combine_rows(const CombineArgs a) 
         __bf16 h[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) h[e] = (__bf16)acc[e];
-        *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.out) + (row * DV + c * 4) * 2) = *reinterpret_cast<u32x2*>(h);
+        *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.out) + out_row_offset(a, row) + c * 8) = *reinterpret_cast<u32x2*>(h);
     } else {
-        *reinterpret_cast<f32x4*>(reinterpret_cast<char*>(a.out) + (row * DV + c * 4) * 4) = acc;
+        *reinterpret_cast<f32x4*>(reinterpret_cast<char*>(a.out) + out_row_offset(a, row) + c * 16) = acc;
     }
 }
 
@@ -164,10 +176,61 @@ __global__ void __launch_bounds__(kThreads) k_combine_slices(const CombineArgs a
             __bf16 h[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) h[e] = (__bf16)o[e];
-            *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.out) + (row * DV + c * 4) * 2) = *reinterpret_cast<u32x2*>(h);
+            *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.out) + out_row_offset(a, row) + c * 8) = *reinterpret_cast<u32x2*>(h);
         } else {
-            *reinterpret_cast<f32x4*>(reinterpret_cast<char*>(a.out) + (row * DV + c * 4) * 4) = o;
+            *reinterpret_cast<f32x4*>(reinterpret_cast<char*>(a.out) + out_row_offset(a, row) + c * 16) = o;
         }
+    }
+}
+
+// Gate kernel of the unfused execution (the structure the fused path replaces, Section 5): the three branch
+// outputs were written to scratch in the storage type, [rows, d_v] each; this launch reads them back and writes
+// out = g_cmp o_cmp + g_slc o_slc + g_win o_win.  One thread per four output columns.
+struct GateArgs {
+    const void *o_cmp, *o_slc, *o_win;
+    const float* gates;
+    const int32_t* n_query;
+    void* out;
+    int T, H;
+    int64_t rows_total;
+    int64_t out_s[3];
+};
+
+template <bool BF16, int DV>
+__global__ void __launch_bounds__(kThreads) k_gate(const GateArgs a) {
+    constexpr int TPR = DV / 4, RPW = kThreads / TPR;
+    const int tid = threadIdx.x;
+    const int64_t row = (int64_t)blockIdx.x * RPW + tid / TPR;
+    if (row >= a.rows_total) return;
+    const int c = tid % TPR;
+    const int h = (int)(row % a.H), i = (int)((row / a.H) % a.T);
+    const int64_t b = row / ((int64_t)a.H * a.T);
+    const int Tq = a.n_query ? min(max(a.n_query[b], 0), a.T) : a.T;
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (i < Tq) {
+        const void* src[3] = {a.o_cmp, a.o_slc, a.o_win};
+#pragma unroll
+        for (int br = 0; br < 3; ++br) {
+            const float gate = a.gates[row * 3 + br];
+            f32x4 v;
+            if constexpr (BF16) {
+                const u32x2 raw = *reinterpret_cast<const u32x2*>(reinterpret_cast<const char*>(src[br]) + (row * DV + c * 4) * 2);
+                v = f32x4{__uint_as_float(raw[0] << 16), __uint_as_float(raw[0] & 0xFFFF0000u),
+                          __uint_as_float(raw[1] << 16), __uint_as_float(raw[1] & 0xFFFF0000u)};
+            } else {
+                v = *reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(src[br]) + (row * DV + c * 4) * 4);
+            }
+            acc += gate * v;
+        }
+    }
+    char* dst = reinterpret_cast<char*>(a.out) + b * a.out_s[0] + i * a.out_s[1] + h * a.out_s[2];
+    if constexpr (BF16) {
+        __bf16 hh[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) hh[e] = (__bf16)acc[e];
+        *reinterpret_cast<u32x2*>(dst + c * 8) = *reinterpret_cast<u32x2*>(hh);
+    } else {
+        *reinterpret_cast<f32x4*>(dst + c * 16) = acc;
     }
 }
 

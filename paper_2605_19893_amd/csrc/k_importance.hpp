@@ -41,6 +41,7 @@ struct ImportanceArgs {
     int nc_pitch;
     int64_t rows_total;
     int64_t kc_s[3];           // bytes
+    int64_t q_s[3];            // bytes: sequence, query, head
 };
 
 template <bool BF16, int DK>
@@ -53,12 +54,6 @@ struct ImportanceCfg {
     static constexpr int LDS_RING = 4 * DEPTH * KCH * 1024;   // dynamic LDS bytes
 };
 
-#ifdef SSV_CLOCKS
-__device__ long long g_clk_imp[4096 * 16];
-#define SSV_IMP_T(i) do { if (tid == 0 && wg < 4096) clk_[i] = wall_clock64(); } while (0)
-#else
-#define SSV_IMP_T(i) do { } while (0)
-#endif
 
 constexpr int kImpRows = 64;   // rows (routed queries x heads of the group) per workgroup
 
@@ -83,10 +78,6 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     const int n_pad = gridDim.x;
     const int wg = (blockIdx.x & 7) * (n_pad >> 3) + (blockIdx.x >> 3);
     if (wg >= a.n_wg) return;
-#ifdef SSV_CLOCKS
-    long long clk_[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#endif
-    SSV_IMP_T(0);
     const int qg = wg % a.n_qg;
     const int chunk = (wg / a.n_qg) % a.n_imp_chunks;
     const int bg = wg / (a.n_qg * a.n_imp_chunks);
@@ -103,9 +94,9 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
             const int j = rr / a.H_g;
             // rows past the group's queries repeat its first query: whatever they produce is never stored, and
             // unconditional loads are not waited for here
-            const int64_t grow = ((int64_t)b * a.T + query_of(j < nq ? j : 0)) * a.H + g * a.H_g + rr % a.H_g;
+            const int64_t qoff = b * a.q_s[0] + query_of(j < nq ? j : 0) * a.q_s[1] + (g * a.H_g + rr % a.H_g) * a.q_s[2];
 #pragma unroll
-            for (int kc = 0; kc < KCH; ++kc) qf[t][kc] = *reinterpret_cast<const u32x4*>(a.q + grow * (DK * ES) + kc * 64 + G * 16);
+            for (int kc = 0; kc < KCH; ++kc) qf[t][kc] = *reinterpret_cast<const u32x4*>(a.q + qoff + kc * 64 + G * 16);
         }
     };
     // Softmax statistics of the compressed scan: one row per lane, every wavefront taking every fourth slice; the
@@ -130,10 +121,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
         srow = stats_row(query_of, nq);
         stats_load(wave, st0);
     }
-    SSV_IMP_T(8);
     const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, a.max_seq_len, a.max_n_cmp, s_par, s_depth,
                                        s_cmax, s_anc);
-    SSV_IMP_T(9);
     const int Tq = sm.Tq;
     const int n_routed = a.share ? (Tq + a.share - 1) / a.share : Tq;
     const int nq_grp = min(a.C, n_routed - qg * a.C);
@@ -148,14 +137,12 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     }
     __syncthreads();
 
-    SSV_IMP_T(10);
     int cm = 0;
     for (int j = 0; j < nq_grp; ++j) cm = max(cm, s_cmax[s_qi[j]]);
     const int ntiles = (cm + kTile - 1) / kTile;
     int t0, t1;
     even_slice(ntiles, a.n_imp_chunks, 1, chunk, t0, t1);
     if (t0 >= t1) return;       // (uniform; cm > 0 from here on, so the sequence has compressed rows)
-    SSV_IMP_T(1);
 
     // This wavefront's strip: keys 16 wave + n of every tile, 16 bytes per 64-byte chunk and lane (B-operand layout);
     // rows past the last compressed row repeat it (their probabilities are masked by the visibility limit).  The
@@ -207,10 +194,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
             stats_load(s0, st);
             merge4(s0, st);
         }
-        SSV_IMP_T(11);
         s_part[wave * kImpRows + rr] = make_float2(M, Z);
         __syncthreads();
-        SSV_IMP_T(12);
         if (wave == 0) {
             float Mn = -INFINITY;
 #pragma unroll
@@ -228,7 +213,6 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
         }
     }
     __syncthreads();
-    SSV_IMP_T(2);
 
     // of the four rows (16 t + 4 G + r) this lane holds in the result layout: the softmax offset, the visibility
     // limit and the colsum row of their query
@@ -270,7 +254,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
         for (int kc = 0; kc < KCH; ++kc)
 #pragma unroll
             for (int t = 0; t < RT; ++t)
-                s[t] = mma_frag<BF16>(qf[t][kc], kf[kc], s[t]);   // D[row 4G+r][key n]; absent rows are zero operands
+                s[t] = mma_frag<BF16>(qf[t][kc], kf[kc], s[t]);   // D[row 4G+r][key n]; rows past the group repeat its first query and are never stored
         const int c = tile * kTile + 16 * wave + n;
         if constexpr (WIDE) {
             float hs[RT];     // head sums of this lane's four rows of each row tile (one query), unmasked
@@ -335,7 +319,6 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
             for (int r = 0; r < 4; ++r)
                 if (a.H_g == 1 || !(r & 1)) ns += __builtin_amdgcn_ballot_w64(rowQ[t][r] >= 0) != 0ull;
     }
-    SSV_IMP_T(3);
 
     // Software pipeline over the tiles of the slice.  Loads and stores share one in-order counter: the strip of a
     // tile has landed once no more operations are outstanding than were issued after it: the KCH loads of each
@@ -350,15 +333,9 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     for (; tile + 2 < t1; ++tile) {
         issue_strip(tile + 2);
         __builtin_amdgcn_sched_barrier(0);
-#ifdef SSV_CLOCKS
-        const long long w0_ = wall_clock64();
-#endif
         if (tile - t0 < 2) wait_vmcnt<2 * KCH>();
         else if (ns == 1) wait_vmcnt<2 * KCH + 2>();
         else wait_vmcnt_upto(2 * KCH + 2 * ns);
-#ifdef SSV_CLOCKS
-        clk_[5] += wall_clock64() - w0_;
-#endif
         step(tile);
     }
     if (tile + 1 < t1) {
@@ -368,13 +345,6 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance(const ImportanceArgs
     }
     wait_vmcnt<0>();
     step(tile);
-    SSV_IMP_T(4);
-#ifdef SSV_CLOCKS
-    if (tid == 0 && wg < 4096) {
-        clk_[6] = t1 - t0;
-        for (int i = 0; i < 16; ++i) g_clk_imp[wg * 16 + i] = clk_[i];
-    }
-#endif
 }
 
 }  // namespace ssv

@@ -33,7 +33,8 @@ struct StreamArgs {
     int n_wg;                // real workgroups (the grid is padded to a multiple of 8)
     int max_sched, bitmap_words;
     int64_t rows_total;
-    int64_t k_s[3], v_s[3], kc_s[3], vc_s[3];   // strides in bytes
+    int64_t k_s[3], v_s[3], kc_s[3], vc_s[3];   // strides in bytes: sequence, KV head, row
+    int64_t q_s[3];                             // strides in bytes: sequence, query, head
     // selected-branch launch of the refresh path that also does the top-n selection (fused_topn != 0): every
     // workgroup selects for the queries of its group from the head-summed probabilities, one query per wavefront,
     // and the first slice of each group writes the sets out
@@ -80,24 +81,10 @@ __device__ __forceinline__ void even_slice(int n, int parts, int min_items, int 
     hi = (part + 1) * n / used;
 }
 
-// Optional in-kernel time stamps (development builds only, -DSSV_CLOCKS): 16 stamps per workgroup.
-#ifdef SSV_CLOCKS
-__device__ long long g_clk[4096 * 16];
-#define SSV_STAMP(i) do { if (threadIdx.x == 0 && wg < 4096) g_clk[wg * 16 + (i)] = wall_clock64(); } while (0)
-#define SSV_PHASE_DECL long long ph_[6] = {0, 0, 0, 0, 0, 0}; long long pt_ = wall_clock64();
-#define SSV_PHASE(i) do { const long long n_ = wall_clock64(); ph_[i] += n_ - pt_; pt_ = n_; } while (0)
-#define SSV_PHASE_WRITE do { if (threadIdx.x == 0 && wg < 4096) { for (int i_ = 0; i_ < 6; ++i_) g_clk[wg * 16 + 8 + i_] = ph_[i_]; } } while (0)
-#else
-#define SSV_PHASE_DECL
-#define SSV_PHASE(i) do { } while (0)
-#define SSV_PHASE_WRITE do { } while (0)
-#define SSV_STAMP(i) do { } while (0)
-#endif
-
 // ROLES: which branches this instantiation can run (bit 0 CMP, bit 1 WIN, bit 2 SLC).  The refresh path
-// launches <CMP|WIN> and then <SLC>, the reuse path launches all three at once; code of absent roles is
-// compiled out.
-constexpr int kRolesCmpWin = 3, kRolesSlc = 4, kRolesAll = 7;
+// launches <CMP|WIN> and then <SLC>, the reuse path launches all three at once, the unfused execution launches
+// each branch on its own; code of absent roles is compiled out.
+constexpr int kRolesCmp = 1, kRolesWin = 2, kRolesCmpWin = 3, kRolesSlc = 4, kRolesAll = 7;
 
 // Two workgroups per CU (the LDS of the full-size shapes allows no more), stated to the compiler as exactly two
 // waves per SIMD: left free to aim for three, it trades away the read-ahead of the K fragments for registers that
@@ -134,7 +121,6 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
     const int slot = a.slot_lo + (wg / a.n_qg) % a.slot_cnt;
     const int bg = wg / (a.n_qg * a.slot_cnt);
     const int b = bg / a.H_kv, g = bg % a.H_kv;
-    SSV_STAMP(0);
 
     int role, part;
     if (slot < a.n_cmp_chunks) { role = ROLE_CMP; part = slot; }
@@ -148,7 +134,6 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
                                        s_cmax,
                                        s_anc);
     const int L = sm.L, Tq = sm.Tq;
-    SSV_STAMP(1);
     const int nq_grp = min(a.C, Tq - qg * a.C);   // verifier queries of this group that exist
     const int n_slots_kv = L + Tq;                // raw KV rows that exist for this sequence
 
@@ -156,7 +141,7 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
     bool rvalid[NRT];
     AncSet anc[NRT];
     int pos[NRT], cmax[NRT], iq[NRT];
-    int64_t grow[NRT];
+    int64_t grow[NRT], qoff[NRT];
 #pragma unroll
     for (int t = 0; t < NRT; ++t) {
         const int rr = (wave + 4 * t) * 16 + n;
@@ -168,6 +153,7 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
         pos[t] = L + s_depth[qs];
         cmax[t] = rvalid[t] ? s_cmax[qs] : 0;
         grow[t] = ((int64_t)b * a.T + qs) * a.H + g * a.H_g + rr % a.H_g;
+        qoff[t] = b * a.q_s[0] + qs * a.q_s[1] + (g * a.H_g + rr % a.H_g) * a.q_s[2];
     }
 
     // ---- fused top-n selection (Section 5.1: routing, then attention over the selected blocks)
@@ -194,7 +180,6 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
             __syncthreads();
         }
     }
-    SSV_STAMP(6);
 
     // ---- tile range of this workgroup
     int t0 = 0, t1 = 0;           // CMP / WIN: tile indices; SLC: schedule entries
@@ -258,7 +243,6 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
         }
     }
 
-    SSV_STAMP(2);
     // ---- query fragments (B operand of S^T = K Q^T), kept in registers for the whole slice
     u32x4 qf[NRT][KCH];
 #pragma unroll
@@ -267,7 +251,7 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
         for (int kc = 0; kc < KCH; ++kc) {
             qf[t][kc] = u32x4{0, 0, 0, 0};
             if (rvalid[t] && t0 < t1)
-                qf[t][kc] = *reinterpret_cast<const u32x4*>(a.q + grow[t] * (DK * ES) + kc * 64 + G * 16);
+                qf[t][kc] = *reinterpret_cast<const u32x4*>(a.q + qoff[t] + kc * 64 + G * 16);
         }
 
     f32x4 acc[NRT][MT];
@@ -298,7 +282,6 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
     // bf16: this lane's address into the row-major V tile for the transposing reads: key row 4 G + (n >> 2) of each
     // run of 16 keys, 8-byte chunk (n & 3) of each 16-column tile
     const int vt_rb = (4 * G + (n >> 2)) * VR + (n & 3) * 8;
-    SSV_STAMP(3);
 
     // Software pipeline: the global loads of tile it+1 are issued before tile it is computed.  K goes straight into
     // the other of two LDS tiles (no registers, no LDS stores); V is staged in registers for one tile step (LDS has
@@ -336,10 +319,8 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
         full_cmax = min(full_cmax, __shfl_xor(full_cmax, off));
         full_lo = max(full_lo, __shfl_xor(full_lo, off));
     }
-    SSV_PHASE_DECL
     // One tile; vcur holds the V rows of tile `it` and, once committed to LDS, takes those of tile it + AHEAD.
     auto tile_step = [&](const int it, TransposedTileRegs<BF16, DV>& vcur) {
-        SSV_PHASE(5);
         const char* sK = sK0 + ((it - t0) & 1) * Cfg::LDS_KD;
         const int tile = tile_of(it);
         const uint64_t own = r_slc ? s_own[it] : ~0ull;
@@ -348,24 +329,16 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
         const bool has_drafts = !r_cmp && base + kTile > L;   // uniform: the tile holds draft slots
 
         if (it > t0) __syncthreads();   // every wave has finished reading the previous tile
-        SSV_PHASE(0);
-#ifdef SSV_CLOCKS
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): separate the wait for the prefetched loads from the LDS stores
-        SSV_PHASE(1);
-#endif
         if constexpr (BF16) vcur.template commit_rows<VR>(sVT, valid_rows, tid);
         else vcur.template commit<VP>(sVT, valid_rows, tid);
         if (has_drafts && tid < kTile) {   // absolute position of every key of the tile (tree drafts: L + depth)
             const int s = base + tid;
             s_kpos[tid] = s < L ? s : (s - L < Tq ? L + s_depth[s - L] : 0x7fffffff);
         }
-        SSV_PHASE(2);
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's global->LDS loads of the K tile have landed
         __syncthreads();
-        SSV_PHASE(3);
         if (it + AHEAD < t1) issue_tile(it + AHEAD, vcur);
         __builtin_amdgcn_sched_barrier(0);    // the loads stay ahead of the compute below (they have been seen to sink past it)
-        SSV_PHASE(4);
 
         // ---- validity of this lane's 16 keys (4 key tiles x 4 registers) for each of its query rows;
         //      bit 4 kt + r <-> key base + 16 kt + 4 G + r
@@ -549,9 +522,6 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
         for (int j = 0; j < AHEAD; ++j)
             if (it + j < t1) tile_step(it + j, vregs[j]);
     }
-    SSV_PHASE(5);
-    SSV_PHASE_WRITE;
-    SSV_STAMP(4);
 
     // ---- partial state of this slice: (m, Z) per row and the un-normalised accumulator
 #pragma unroll
@@ -568,7 +538,6 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
                 *reinterpret_cast<f32x4*>(a.part_acc + pr * DV + 16 * mt + 4 * G) = acc[t][mt];
         }
     }
-    SSV_STAMP(5);
 }
 
 }  // namespace ssv

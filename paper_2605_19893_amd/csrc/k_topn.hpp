@@ -21,13 +21,6 @@
 
 namespace ssv {
 
-#ifdef SSV_CLOCKS   // development builds only: time stamps of the selection phases
-__device__ long long g_clk_topn[4096 * 8];
-#define SSV_TOPN_STAMP(i) do { if (threadIdx.x == 0 && wg < 4096) g_clk_topn[wg * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define SSV_TOPN_STAMP(i) do { } while (0)
-#endif
-
 struct TopnArgs {
     const float* colsum;     // [B, T, H_kv, nc_pitch]
     const int32_t *seq_lens, *n_cmp, *n_query, *parents;
@@ -279,10 +272,6 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     int* s_cmax = s_depth + kMaxT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-#ifdef SSV_CLOCKS
-    const int wg = blockIdx.x;
-#endif
-    SSV_TOPN_STAMP(0);
     const int g = blockIdx.x % a.H_kv;
     const int x = (blockIdx.x / a.H_kv) % a.T;
     const int b = blockIdx.x / (a.H_kv * a.T);
@@ -290,7 +279,6 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, a.max_seq_len, a.max_n_cmp, s_par, s_depth,
                                        s_cmax,
                                        s_anc);
-    SSV_TOPN_STAMP(1);
     if (x >= sm.Tq) {
         if (tid < a.n_sel) a.sel_idx[(((int64_t)b * a.T + x) * a.H_kv + g) * a.n_sel + tid] = -1;
         return;
@@ -372,7 +360,6 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
         }
     }
     s_best[tid] = best;
-    SSV_TOPN_STAMP(2);
     __syncthreads();
 
     // threshold: per wavefront, the n_eff-th largest of its per-thread bests (keys are distinct; threads without
@@ -385,7 +372,6 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
         if (best != 0 && rank == n_eff - 1) s_red[12 + wave] = best;
     }
     __syncthreads();
-    SSV_TOPN_STAMP(3);
     uint64_t thr = s_red[12];
 #pragma unroll
     for (int k = 1; k < 4; ++k) thr = s_red[12 + k] > thr ? s_red[12 + k] : thr;
@@ -397,7 +383,6 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
         }
     }
     __syncthreads();
-    SSV_TOPN_STAMP(4);
     const int n_cand = (int)*reinterpret_cast<unsigned*>(&s_red[1]);
     if (n_cand <= kMaxCand) {
         // rank candidates by counting; ranks below n_eff are the selection
@@ -435,7 +420,6 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
         }
     }
     __syncthreads();
-    SSV_TOPN_STAMP(5);
     // ascending order: pick e goes to position (number of smaller picks); picks are distinct
     if (tid < a.n_sel) {
         int pick = 0x7fffffff, rank = tid;   // threads beyond n_eff write the -1 padding at their own position
@@ -451,7 +435,6 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
         for (int m = m0; m < m1; ++m)
             a.sel_idx[(((int64_t)b * a.T + m) * a.H_kv + g) * a.n_sel + rank] = tid < n_eff ? pick : -1;
     }
-    SSV_TOPN_STAMP(6);
 }
 
 }  // namespace ssv

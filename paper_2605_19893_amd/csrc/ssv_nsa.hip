@@ -5,7 +5,6 @@
 
 #include <atomic>
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 
 #include "../../include/ssv_nsa.h"
@@ -24,25 +23,36 @@ struct Shape { int dtype, d_k, d_v; };
 constexpr int kMaxDevices = 64;   // per-device one-time set-up flags
 constexpr Shape kShapes[] = {{SSV_BF16, 192, 128}, {SSV_BF16, 128, 128}, {SSV_BF16, 64, 64}, {SSV_F32, 64, 64}};
 
-int env_int(const char* name, int dflt) {
-    const char* s = std::getenv(name);
-    if (!s || !*s) return dflt;
-    const int v = std::atoi(s);
-    return v > 0 ? v : dflt;
-}
-
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Planning constants (measured choices; none is read from the environment).
+constexpr int kResidentWgs = 256 * 2;        // workgroups one round holds: LDS and registers allow two per CU
+constexpr int kMinTilesPerSlice = 2;
+constexpr int kLongSliceTiles = 24;          // slice length once a launch needs several rounds (max_slice_tiles = 0)
+constexpr int kImportanceWgs = 512;          // one round of the importance pass (more, shorter workgroups measured slower)
+constexpr int kTopnInSlcMaxWgs = 256;        // SSV_TOPN_AUTO: select inside the selected-branch launch up to this many workgroups
+constexpr int kCombineRowsMaxSlots = 12;     // up to this many slices per row a thread group owns a row in the combine kernel
+constexpr size_t kMaxStreamLds = 80 * 1024;  // two workgroups per CU
 
 struct Layout {
     ssv_nsa_plan plan;
     int H_g, es;
-    bool one_launch;
+    bool one_launch, unfused;
     int imp_C, imp_n_qg, n_imp_chunks;   // importance pass: routed queries per workgroup, such workgroups per sequence, slices
-    int nc_pitch, max_blocks, bitmap_words;
+    int nc_pitch, max_blocks, bitmap_words, max_sched;
+    size_t lds_stream, lds_k, lds_vt;
     int64_t rows_total;
-    size_t off_stats, off_acc, off_colsum, total;
+    int64_t q_s[3], out_s[3];            // bytes
+    size_t off_stats, off_acc, off_colsum, off_branch, branch_bytes, total;
 };
+
+// LDS tile sizes of the streaming kernel for a shape (they equal StreamCfg<...>::LDS_K / LDS_VT)
+void stream_tile_lds(bool bf16, int d_k, int d_v, size_t* lds_k, size_t* lds_vt) {
+    const int es = bf16 ? 2 : 4;
+    *lds_k = (size_t)2 * kTile * d_k * es;
+    *lds_vt = bf16 ? (size_t)kTile * (d_v * 2 + 32) : (size_t)d_v * (kTile * 4 + 16);
+}
 
 int make_layout(const ssv_nsa_params* p, Layout* lo) {
     if (!p) return SSV_EINVAL;
@@ -54,6 +64,12 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     if (p->dtype != SSV_F32 && p->dtype != SSV_BF16) return SSV_EINVAL;
     if (p->mode != SSV_REFRESH && p->mode != SSV_REUSE && p->mode != SSV_REFRESH_SHARED) return SSV_EINVAL;
     if (p->group_size < 0 || !(p->scale >= 0.f) || std::isinf(p->scale)) return SSV_EINVAL;
+    if (p->exec != SSV_EXEC_FUSED && p->exec != SSV_EXEC_UNFUSED) return SSV_EINVAL;
+    if (p->topn_home != SSV_TOPN_AUTO && p->topn_home != SSV_TOPN_SEPARATE && p->topn_home != SSV_TOPN_IN_SLC) return SSV_EINVAL;
+    if (p->max_slice_tiles != 0 && (p->max_slice_tiles < 2 || p->max_slice_tiles > 64)) return SSV_EINVAL;
+    if (p->reserved != 0) return SSV_EINVAL;
+    const bool unfused = p->exec == SSV_EXEC_UNFUSED;
+    if (unfused && (p->mode == SSV_REFRESH_SHARED || p->group_size > 1 || p->scan_group_size > 1)) return SSV_EINVAL;
     const int H_g = p->H / p->H_kv;
     if (p->T > SSV_MAX_T) return SSV_EUNSUPPORTED;
     if (H_g != 1 && H_g != 2 && H_g != 4 && H_g != 8 && H_g != 16) return SSV_EUNSUPPORTED;
@@ -79,11 +95,28 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     if (max_blocks > 16384) return SSV_EUNSUPPORTED;
 
     std::memset(lo, 0, sizeof(*lo));
+    lo->unfused = unfused;
+    // q and out: all-zero strides mean contiguous [B, T, H, d]
+    {
+        const int64_t* given[2] = {p->q_stride, p->out_stride};
+        int64_t* bytes[2] = {lo->q_s, lo->out_s};
+        const int dd[2] = {p->d_k, p->d_v};
+        for (int a = 0; a < 2; ++a) {
+            const bool dense = !given[a][0] && !given[a][1] && !given[a][2];
+            const int64_t st[3] = {dense ? (int64_t)p->T * p->H * dd[a] : given[a][0], dense ? (int64_t)p->H * dd[a] : given[a][1],
+                                   dense ? (int64_t)dd[a] : given[a][2]};
+            for (int j = 0; j < 3; ++j) {
+                if (st[j] < 0 || (st[j] * es) % 16) return SSV_EINVAL;
+                bytes[a][j] = st[j] * es;
+            }
+            if (st[2] < dd[a] || st[1] < dd[a] || (p->B > 1 && st[0] < dd[a])) return SSV_EINVAL;
+        }
+    }
     ssv_nsa_plan& pl = lo->plan;
     // default: 64 rows per workgroup (one 16-row tile per wave keeps the software pipeline in registers);
     // up to 128 rows (two row tiles per wave) on request
     // (the shared-index variant keeps this automatic grouping: its group_size is the sharing group)
-    pl.C = (p->group_size && !shared) ? p->group_size : std::max(1, std::min(p->T, 64 / H_g));
+    pl.C = unfused ? 1 : ((p->group_size && !shared) ? p->group_size : std::max(1, std::min(p->T, 64 / H_g)));
     pl.share_group = shared ? (p->group_size ? p->group_size : pl.C) : 0;
     pl.n_qg = ceil_div(p->T, pl.C);
     pl.rows_per_wg = pl.C * H_g;
@@ -92,7 +125,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // never below min_tiles tiles per slice.  Small problems take one workgroup per CU instead (a workgroup that
     // has its CU to itself runs a tile in 2.3 us instead of 3.3): when that leaves slices of at most four tiles.
     const int units = p->B * p->H_kv * pl.n_qg;
-    const int capacity = env_int("SSV_CAPACITY", 256 * 2);
+    const int capacity = kResidentWgs;
     const int ntc = std::max(1, ceil_div(p->max_n_cmp, kTile));         // compressed tiles of the longest sequence
     // an average sequence has fewer compressed tiles than the longest one: budget slices for the average, so
     // that slices of long and short sequences come out at about the same length
@@ -105,55 +138,56 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // faster at 16-40 queries per sequence), balanced over the sequence's queries.  An explicit group_size applies
     // to both launches unless the scan has one of its own.
     pl.C_scan = pl.C;
-    if (p->scan_group_size) pl.C_scan = p->scan_group_size;
+    if (unfused) pl.C_scan = 1;
+    else if (p->scan_group_size) pl.C_scan = p->scan_group_size;
     else if (!p->group_size || shared) {
         const int n_a = ceil_div(p->T, std::max(1, std::min(p->T, 128 / H_g)));
         const int cand = ceil_div(p->T, n_a);
-        if (cand > pl.C && (int64_t)units * (ntc_avg + ntw) >= 8 * (int64_t)capacity && !env_int("SSV_NO_SCAN_GROUPS", 0)) pl.C_scan = cand;
+        if (cand > pl.C && (int64_t)units * (ntc_avg + ntw) >= 8 * (int64_t)capacity) pl.C_scan = cand;
     }
     pl.n_qg_scan = ceil_div(p->T, pl.C_scan);
     const int units_scan = p->B * p->H_kv * pl.n_qg_scan;
     pl.max_sched_entries = pl.C * p->n_sel;
     // selected tiles, at most; with one shared index set per group the schedule is a single set
     const int nts = shared ? ceil_div(pl.C, pl.share_group) * p->n_sel : pl.max_sched_entries;
-    pl.min_tiles_per_split = env_int("SSV_MIN_TILES", 2);
+    pl.min_tiles_per_split = kMinTilesPerSlice;
     const int mt = pl.min_tiles_per_split;
-    // Tiles per slice.  If one round of resident workgroups can take the launch with slices of at most 24
+    const int long_slice = p->max_slice_tiles ? p->max_slice_tiles : kLongSliceTiles;
+    // Tiles per slice.  If one round of resident workgroups can take the launch with slices of at most long_slice
     // tiles, `per` is grown until the slices of an average unit fit the capacity (no partial second round).
-    // Otherwise slices are cut to 24 tiles: several rounds of workgroups, and the longest slice, the long pole of
-    // a mixed-length batch, stays bounded (12-tile slices balanced better but cost 5-10 % at the 128K-context
-    // configurations: twice the partial states to write and merge, twice the per-workgroup start-up).
+    // Otherwise slices are cut to long_slice tiles: several rounds of workgroups, and the longest slice, the long
+    // pole of a mixed-length batch, stays bounded (12-tile slices balanced better but cost 5-10 % at the
+    // 128K-context configurations: twice the partial states to write and merge, twice the per-workgroup start-up).
     auto tiles_per_slice = [&](const int* tiles, int n_roles, int n_units) {
         int total = 0;
         for (int r = 0; r < n_roles; ++r) total += tiles[r];
         int spu = std::max(n_roles, (capacity / 2) / n_units);      // slices per unit one round can hold, one workgroup per CU
         if (std::max(mt, ceil_div(total, spu)) > 4) spu = std::max(n_roles, capacity / n_units);   // two per CU
         int per = std::max(mt, ceil_div(total, spu));
-        if (per > 24) return env_int("SSV_LONG_SLICE", 24);
+        if (per > long_slice) return long_slice;
         for (;; ++per) {
             int sum = 0;
             for (int r = 0; r < n_roles; ++r) sum += std::max(1, ceil_div(tiles[r], per));
             if (sum <= spu || per >= total) return per;
         }
     };
-    int per_a, per_b;
-    lo->one_launch = p->mode == SSV_REUSE && pl.C_scan == pl.C;   // all three branches in one launch
-    if (lo->one_launch) {
+    int per_c, per_w, per_s;
+    lo->one_launch = !unfused && p->mode == SSV_REUSE && pl.C_scan == pl.C;   // all three branches in one launch
+    if (unfused) {              // one launch per branch
+        per_c = tiles_per_slice(&ntc_avg, 1, units);
+        per_w = tiles_per_slice(&ntw, 1, units);
+        per_s = tiles_per_slice(&nts, 1, units);
+    } else if (lo->one_launch) {
         const int tiles[3] = {ntc_avg, ntw, nts};
-        per_a = per_b = tiles_per_slice(tiles, 3, units);
+        per_c = per_w = per_s = tiles_per_slice(tiles, 3, units);
     } else {
         const int tiles_a[2] = {ntc_avg, ntw};
-        per_a = tiles_per_slice(tiles_a, 2, units_scan);
-        per_b = tiles_per_slice(&nts, 1, units);
+        per_c = per_w = tiles_per_slice(tiles_a, 2, units_scan);
+        per_s = tiles_per_slice(&nts, 1, units);
     }
-    const int n_c = std::max(1, ceil_div(ntc, per_a)), n_w = std::max(1, ceil_div(ntw, per_a));
-    const int n_s = std::max(1, ceil_div(nts, per_b));
-    pl.n_cmp_chunks = env_int("SSV_CMP_CHUNKS", n_c);
-    pl.n_win_splits = env_int("SSV_WIN_SPLITS", n_w);
-    pl.n_slc_splits = env_int("SSV_SLC_SPLITS", n_s);
-    pl.n_cmp_chunks = std::min(pl.n_cmp_chunks, kMaxSlotsPerBranch);   // keeps the per-row slice loops of the combine kernel short
-    pl.n_win_splits = std::min(pl.n_win_splits, 32);
-    pl.n_slc_splits = std::min(pl.n_slc_splits, 32);
+    pl.n_cmp_chunks = std::min(std::max(1, ceil_div(ntc, per_c)), kMaxSlotsPerBranch);   // keeps the per-row slice loops of the combine kernel short
+    pl.n_win_splits = std::min(std::max(1, ceil_div(ntw, per_w)), 32);
+    pl.n_slc_splits = std::min(std::max(1, ceil_div(nts, per_s)), 32);
     pl.tiles_per_chunk = ceil_div(ntc, pl.n_cmp_chunks);
     pl.n_slots = pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits;
 
@@ -171,11 +205,29 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
         lo->imp_n_qg = ceil_div(p->T, lo->imp_C);
     }
     const int imp_units = p->B * p->H_kv * lo->imp_n_qg;
-    lo->n_imp_chunks = std::max(1, std::min(ceil_div(ntc, env_int("SSV_IMP_MIN_TILES", 1)), std::max(1, env_int("SSV_IMP_WGS", 512) / imp_units)));
+    lo->n_imp_chunks = std::max(1, std::min(ntc, std::max(1, kImportanceWgs / imp_units)));
     lo->es = es;
     lo->nc_pitch = (int)align_up((size_t)std::max(1, p->max_n_cmp), kTile);
     lo->max_blocks = max_blocks;
-    lo->bitmap_words = ceil_div(max_blocks, 32);
+    // rounded so that every LDS array behind them stays 16-byte aligned
+    lo->bitmap_words = (ceil_div(max_blocks, 32) + 1) & ~1;
+    lo->max_sched = (pl.max_sched_entries + 3) & ~3;
+    stream_tile_lds(p->dtype == SSV_BF16, p->d_k, p->d_v, &lo->lds_k, &lo->lds_vt);
+    lo->lds_stream = stream_lds_bytes(lo->lds_k, lo->lds_vt, lo->max_sched, lo->bitmap_words);
+    if (lo->lds_stream > kMaxStreamLds) return SSV_EUNSUPPORTED;     // merged schedules of very large groups do not fit
+    // Top-n selection of a refresh call: inside the selected-branch launch (every workgroup selects for its own
+    // group's queries, one query per wavefront, in the tile buffers that are idle until the schedule exists) when the
+    // importance arrays of four queries fit there.  Every slice of a group repeats the group's selections, which
+    // costs nothing while the launch leaves CUs idle (at most one workgroup per CU) and is slower than the
+    // separate launch once the chip is full.
+    const bool refresh = p->mode != SSV_REUSE;
+    const bool fits = fused_topn_lds_bytes(max_blocks, pl.C, p->n_sel) <= lo->lds_k + lo->lds_vt;
+    const int n_wg_b = units * pl.n_slc_splits;
+    pl.topn_in_slc = refresh && !unfused && fits &&
+                     (p->topn_home == SSV_TOPN_IN_SLC || (p->topn_home == SSV_TOPN_AUTO && n_wg_b <= kTopnInSlcMaxWgs));
+    pl.n_imp_chunks = refresh ? lo->n_imp_chunks : 0;
+    if (unfused) pl.n_launches = refresh ? 9 : 7;
+    else pl.n_launches = (lo->one_launch ? 1 : 2) + (refresh ? 1 + !pl.topn_in_slc : 0) + 1;
     lo->rows_total = (int64_t)p->B * p->T * p->H;
     size_t off = 0;
     lo->off_stats = off;
@@ -184,6 +236,9 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     off = align_up(off + (size_t)pl.n_slots * lo->rows_total * p->d_v * sizeof(float), 256);
     lo->off_colsum = off;
     off = align_up(off + (size_t)p->B * p->T * p->H_kv * lo->nc_pitch * sizeof(float), 256);
+    lo->off_branch = off;
+    lo->branch_bytes = align_up((size_t)lo->rows_total * p->d_v * es, 256);
+    if (unfused) off += 3 * lo->branch_bytes;    // the three branch outputs, [rows, d_v] in the storage type
     lo->total = off;
     pl.workspace_bytes = (int64_t)off;
     return SSV_OK;
@@ -242,6 +297,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
                Timer& tm) {
     using SC = StreamCfg<BF16, DK, DV>;
     using IC = ImportanceCfg<BF16, DK>;
+    static_assert(SC::LDS_K == 2 * kTile * DK * (BF16 ? 2 : 4), "stream_tile_lds must describe this shape");
     const ssv_nsa_plan& pl = lo.plan;
     const int es = lo.es;
     const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->d_k);
@@ -249,6 +305,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     float* part_stats = reinterpret_cast<float*>(ws + lo.off_stats);
     float* part_acc = reinterpret_cast<float*>(ws + lo.off_acc);
     float* colsum = reinterpret_cast<float*>(ws + lo.off_colsum);
+    if ((size_t)SC::LDS_K != lo.lds_k || (size_t)SC::LDS_VT != lo.lds_vt) return SSV_EUNSUPPORTED;   // (cannot happen)
 
     StreamArgs sa{};
     sa.q = (const char*)q; sa.k = (const char*)k; sa.v = (const char*)v; sa.kc = (const char*)kc; sa.vc = (const char*)vc;
@@ -259,14 +316,13 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     sa.max_seq_len = p->max_seq_len; sa.max_n_cmp = p->max_n_cmp;
     sa.n_cmp_chunks = pl.n_cmp_chunks; sa.n_win_splits = pl.n_win_splits; sa.n_slc_splits = pl.n_slc_splits;
     sa.min_tiles = 1;     // inside a launch the used slices share the tiles evenly, down to one tile each
-    // rounded so that every LDS array behind them stays 16-byte aligned
-    sa.max_sched = (pl.max_sched_entries + 3) & ~3; sa.bitmap_words = (lo.bitmap_words + 1) & ~1; sa.rows_total = lo.rows_total;
+    sa.max_sched = lo.max_sched; sa.bitmap_words = lo.bitmap_words; sa.rows_total = lo.rows_total;
     for (int j = 0; j < 3; ++j) {
         sa.k_s[j] = p->k_stride[j] * es; sa.v_s[j] = p->v_stride[j] * es;
         sa.kc_s[j] = p->kc_stride[j] * es; sa.vc_s[j] = p->vc_stride[j] * es;
+        sa.q_s[j] = lo.q_s[j];
     }
-    const size_t lds_stream = stream_lds_bytes(SC::LDS_K, SC::LDS_VT, sa.max_sched, sa.bitmap_words);
-    if (lds_stream > 80 * 1024) return SSV_EUNSUPPORTED;     // two workgroups per CU; merged schedules of very large groups do not fit
+    const size_t lds_stream = lo.lds_stream;
     {
         // kernels that may ask for more than 64 KB of dynamic LDS: raise their limit once per device (repeating the
         // calls after a lost race between two host threads is harmless)
@@ -277,76 +333,64 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
             const void* fns[] = {(const void*)k_stream<BF16, DK, DV, 1, kRolesAll>, (const void*)k_stream<BF16, DK, DV, 1, kRolesSlc>,
                                  (const void*)k_stream<BF16, DK, DV, 1, kRolesCmpWin>, (const void*)k_stream<BF16, DK, DV, 2, kRolesAll>,
                                  (const void*)k_stream<BF16, DK, DV, 2, kRolesSlc>, (const void*)k_stream<BF16, DK, DV, 2, kRolesCmpWin>,
+                                 (const void*)k_stream<BF16, DK, DV, 1, kRolesCmp>, (const void*)k_stream<BF16, DK, DV, 1, kRolesWin>,
                                  (const void*)k_importance<BF16, DK, 16>, (const void*)k_importance<BF16, DK, 4>,
                                  (const void*)k_importance<BF16, DK, 1>};
             for (const void* fn : fns)
-                if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024) != hipSuccess) return SSV_ELAUNCH;
+                if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStreamLds) != hipSuccess) return SSV_ELAUNCH;
             raised[dev].store(true, std::memory_order_release);
         }
     }
 
     const int reps = tm.on ? tm.repeats : 1;
-    auto launch_stream = [&](int K, int slot_lo, int slot_cnt, int C, int n_qg) -> int {
+    // one k_stream launch over the partial-state slots [slot_lo, slot_lo + slot_cnt) with query groups of C
+    auto launch_stream = [&](int K, int roles, int slot_lo, int slot_cnt, int C, int n_qg) -> int {
         sa.C = C; sa.n_qg = n_qg;
         sa.slot_lo = slot_lo; sa.slot_cnt = slot_cnt; sa.n_wg = p->B * p->H_kv * n_qg * slot_cnt;
         const int grid = ceil_div(sa.n_wg, 8) * 8;
-        const bool all = slot_cnt == pl.n_slots, only_slc = slot_lo > 0;
+        if (tm.begin(K)) return -1;
         for (int r = 0; r < reps; ++r) {
 #define SSV_LAUNCH_STREAM(NRT_, ROLES_) SSV_LAUNCH(K, (k_stream<BF16, DK, DV, NRT_, ROLES_>), grid, lds_stream, sa)
             if (C * lo.H_g > 64) {
-                if (all) SSV_LAUNCH_STREAM(2, kRolesAll);
-                else if (only_slc) SSV_LAUNCH_STREAM(2, kRolesSlc);
+                if (roles == kRolesAll) SSV_LAUNCH_STREAM(2, kRolesAll);
+                else if (roles == kRolesSlc) SSV_LAUNCH_STREAM(2, kRolesSlc);
                 else SSV_LAUNCH_STREAM(2, kRolesCmpWin);
             } else {
-                if (all) SSV_LAUNCH_STREAM(1, kRolesAll);
-                else if (only_slc) SSV_LAUNCH_STREAM(1, kRolesSlc);
+                if (roles == kRolesAll) SSV_LAUNCH_STREAM(1, kRolesAll);
+                else if (roles == kRolesSlc) SSV_LAUNCH_STREAM(1, kRolesSlc);
+                else if (roles == kRolesCmp) SSV_LAUNCH_STREAM(1, kRolesCmp);
+                else if (roles == kRolesWin) SSV_LAUNCH_STREAM(1, kRolesWin);
                 else SSV_LAUNCH_STREAM(1, kRolesCmpWin);
             }
 #undef SSV_LAUNCH_STREAM
         }
-        return hipGetLastError() == hipSuccess ? 0 : -1;
+        return (hipGetLastError() == hipSuccess && !tm.end(K)) ? 0 : -1;
     };
 
-    const int n_scan_slots = pl.n_cmp_chunks + pl.n_win_splits;
-    if (lo.one_launch) {
-        if (tm.begin(SSV_K_STREAM_A) || launch_stream(SSV_K_STREAM_A, 0, pl.n_slots, pl.C, pl.n_qg) || tm.end(SSV_K_STREAM_A)) return SSV_ELAUNCH;
-    } else {
-        if (tm.begin(SSV_K_STREAM_A) || launch_stream(SSV_K_STREAM_A, 0, n_scan_slots, pl.C_scan, pl.n_qg_scan) || tm.end(SSV_K_STREAM_A))
-            return SSV_ELAUNCH;
-    }
-    if (p->mode == SSV_REUSE) {
-        if (!lo.one_launch &&
-            (tm.begin(SSV_K_STREAM_B) || launch_stream(SSV_K_STREAM_B, n_scan_slots, pl.n_slc_splits, pl.C, pl.n_qg) || tm.end(SSV_K_STREAM_B)))
-            return SSV_ELAUNCH;
-    } else {
-
+    // routing of a refresh call: normalised head-summed probabilities, then (unless the selected-branch launch does
+    // it) block importance + top-n
+    auto launch_routing = [&]() -> int {
         ImportanceArgs ia{};
         ia.q = sa.q; ia.kc = sa.kc; ia.seq_lens = seq_lens; ia.n_cmp = n_cmp; ia.n_query = n_query; ia.parents = parents;
         ia.part_stats = part_stats; ia.colsum = colsum;
         ia.B = p->B; ia.T = p->T; ia.H = p->H; ia.H_kv = p->H_kv; ia.H_g = lo.H_g; ia.C = lo.imp_C; ia.n_qg = lo.imp_n_qg;
         ia.share = pl.share_group;
-        ia.l = p->l; ia.d = p->d; ia.max_seq_len = p->max_seq_len; ia.max_n_cmp = p->max_n_cmp; ia.scale_log2 = scale_log2; ia.n_cmp_chunks = pl.n_cmp_chunks; ia.n_imp_chunks = lo.n_imp_chunks;
+        ia.l = p->l; ia.d = p->d; ia.max_seq_len = p->max_seq_len; ia.max_n_cmp = p->max_n_cmp; ia.scale_log2 = scale_log2;
+        ia.n_cmp_chunks = pl.n_cmp_chunks; ia.n_imp_chunks = lo.n_imp_chunks;
         ia.n_wg = p->B * p->H_kv * lo.imp_n_qg * lo.n_imp_chunks; ia.nc_pitch = lo.nc_pitch; ia.rows_total = lo.rows_total;
-        for (int j = 0; j < 3; ++j) ia.kc_s[j] = sa.kc_s[j];
+        for (int j = 0; j < 3; ++j) { ia.kc_s[j] = sa.kc_s[j]; ia.q_s[j] = lo.q_s[j]; }
         const int grid_i = ceil_div(ia.n_wg, 8) * 8;
-        if (tm.begin(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
+        if (tm.begin(SSV_K_IMPORTANCE)) return -1;
         for (int r = 0; r < reps; ++r) {
             if (lo.H_g == 16) SSV_LAUNCH(SSV_K_IMPORTANCE, (k_importance<BF16, DK, 16>), grid_i, IC::LDS_RING, ia);
             else if (lo.H_g >= 4) SSV_LAUNCH(SSV_K_IMPORTANCE, (k_importance<BF16, DK, 4>), grid_i, IC::LDS_RING, ia);
             else SSV_LAUNCH(SSV_K_IMPORTANCE, (k_importance<BF16, DK, 1>), grid_i, IC::LDS_RING, ia);
         }
-        if (hipGetLastError() != hipSuccess || tm.end(SSV_K_IMPORTANCE)) return SSV_ELAUNCH;
+        if (hipGetLastError() != hipSuccess || tm.end(SSV_K_IMPORTANCE)) return -1;
 
-        // Top-n selection: inside the selected-branch launch (every workgroup selects for its own group's queries,
-        // one query per wavefront, in the tile buffers that are idle until the schedule exists) when the importance
-        // arrays of four queries fit there; else as a launch of its own.
         sa.colsum = colsum; sa.sel_out = sel_idx; sa.nc_pitch = lo.nc_pitch; sa.l_sel = p->l_sel; sa.n_init = p->n_init;
         sa.n_local = p->n_local; sa.max_blocks = lo.max_blocks; sa.share = pl.share_group;
-        // Every slice of a group repeats the group's selections, which costs nothing while the launch leaves CUs idle
-        // (at most one workgroup per CU) and is slower than the separate launch once the chip is full.
-        const int n_wg_b = p->B * p->H_kv * pl.n_qg * pl.n_slc_splits;
-        sa.fused_topn = fused_topn_lds_bytes(lo.max_blocks, pl.C, p->n_sel) <= (size_t)(SC::LDS_K + SC::LDS_VT) &&
-                        n_wg_b <= env_int("SSV_FUSED_TOPN_MAX_WGS", 256) && !env_int("SSV_SEPARATE_TOPN", 0);
+        sa.fused_topn = pl.topn_in_slc;
         if (!sa.fused_topn) {
             TopnArgs ta{};
             ta.colsum = colsum; ta.seq_lens = seq_lens; ta.n_cmp = n_cmp; ta.n_query = n_query; ta.parents = parents;
@@ -357,30 +401,68 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
             const size_t lds_topn = topn_lds_bytes(lo.max_blocks);
             if (lds_topn > 64 * 1024 &&
                 hipFuncSetAttribute((const void*)k_topn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_topn) != hipSuccess)
-                return SSV_ELAUNCH;
-            if (tm.begin(SSV_K_TOPN)) return SSV_ELAUNCH;
+                return -1;
+            if (tm.begin(SSV_K_TOPN)) return -1;
             for (int r = 0; r < reps; ++r)
                 SSV_LAUNCH(SSV_K_TOPN, k_topn, p->B * p->T * p->H_kv, lds_topn, ta);
-            if (hipGetLastError() != hipSuccess || tm.end(SSV_K_TOPN)) return SSV_ELAUNCH;
+            if (hipGetLastError() != hipSuccess || tm.end(SSV_K_TOPN)) return -1;
         }
-        if (tm.begin(SSV_K_STREAM_B) || launch_stream(SSV_K_STREAM_B, n_scan_slots, pl.n_slc_splits, pl.C, pl.n_qg) ||
-            tm.end(SSV_K_STREAM_B))
-            return SSV_ELAUNCH;
-    }
+        return 0;
+    };
 
     CombineArgs ca{};
     ca.part_stats = part_stats; ca.part_acc = part_acc; ca.gates = gates; ca.n_query = n_query; ca.out = out;
     ca.T = p->T; ca.H = p->H; ca.n_cmp_chunks = pl.n_cmp_chunks; ca.n_win_splits = pl.n_win_splits;
     ca.n_slc_splits = pl.n_slc_splits; ca.rows_total = lo.rows_total;
-    // few slices per row: thread groups own rows; many slices: one workgroup per row, slices in parallel
-    const bool by_rows = pl.n_slots <= env_int("SSV_COMBINE_ROWS_MAX_SLOTS", 12);
+    ca.br_lo = 0; ca.br_hi = 3; ca.use_gates = 1;
+    for (int j = 0; j < 3; ++j) ca.out_s[j] = lo.out_s[j];
     const int rows_per_wg = kThreads / (DV / 4);
-    const int grid_c = by_rows ? (int)((lo.rows_total + rows_per_wg - 1) / rows_per_wg) : (int)lo.rows_total;
+    const int grid_rows = (int)((lo.rows_total + rows_per_wg - 1) / rows_per_wg);
+    const int n_scan_slots = pl.n_cmp_chunks + pl.n_win_splits;
     if (tm.begin(SSV_T_EVENT_PAIR, true) || tm.end(SSV_T_EVENT_PAIR, true)) return SSV_ELAUNCH;   // empty pair: the overhead itself
+
+    if (lo.unfused) {
+        // The execution the fused path replaces: every query on its own (C = 1), one launch per branch; each branch's
+        // partial states are merged, normalised and written to scratch in the storage type; a gate kernel reads the
+        // three branch outputs back.  In a refresh call the indices go through sel_idx in HBM (separate top-n launch).
+        char* branch = ws + lo.off_branch;
+        auto branch_out = [&](int K, int br) -> int {
+            CombineArgs ba = ca;
+            ba.out = branch + (size_t)br * lo.branch_bytes;
+            ba.out_s[0] = (int64_t)p->T * p->H * DV * es; ba.out_s[1] = (int64_t)p->H * DV * es; ba.out_s[2] = (int64_t)DV * es;
+            ba.br_lo = br; ba.br_hi = br + 1; ba.use_gates = 0;
+            if (tm.begin(K)) return -1;
+            for (int r = 0; r < reps; ++r) SSV_LAUNCH(K, (k_combine_rows<BF16, DV>), grid_rows, 0, ba);
+            return (hipGetLastError() == hipSuccess && !tm.end(K)) ? 0 : -1;
+        };
+        if (launch_stream(SSV_K_STREAM_A, kRolesCmp, 0, pl.n_cmp_chunks, 1, p->T) || branch_out(SSV_K_OUT_CMP, 0)) return SSV_ELAUNCH;
+        if (p->mode != SSV_REUSE && launch_routing()) return SSV_ELAUNCH;
+        sa.fused_topn = 0;
+        if (launch_stream(SSV_K_STREAM_B, kRolesSlc, n_scan_slots, pl.n_slc_splits, 1, p->T) || branch_out(SSV_K_OUT_SLC, 1)) return SSV_ELAUNCH;
+        if (launch_stream(SSV_K_STREAM_W, kRolesWin, pl.n_cmp_chunks, pl.n_win_splits, 1, p->T) || branch_out(SSV_K_OUT_WIN, 2)) return SSV_ELAUNCH;
+        GateArgs ga{};
+        ga.o_cmp = branch; ga.o_slc = branch + lo.branch_bytes; ga.o_win = branch + 2 * lo.branch_bytes;
+        ga.gates = gates; ga.n_query = n_query; ga.out = out; ga.T = p->T; ga.H = p->H; ga.rows_total = lo.rows_total;
+        for (int j = 0; j < 3; ++j) ga.out_s[j] = lo.out_s[j];
+        if (tm.begin(SSV_K_COMBINE)) return SSV_ELAUNCH;
+        for (int r = 0; r < reps; ++r) SSV_LAUNCH(SSV_K_COMBINE, (k_gate<BF16, DV>), grid_rows, 0, ga);
+        if (hipGetLastError() != hipSuccess || tm.end(SSV_K_COMBINE)) return SSV_ELAUNCH;
+        return SSV_OK;
+    }
+
+    if (lo.one_launch) {
+        if (launch_stream(SSV_K_STREAM_A, kRolesAll, 0, pl.n_slots, pl.C, pl.n_qg)) return SSV_ELAUNCH;
+    } else {
+        if (launch_stream(SSV_K_STREAM_A, kRolesCmpWin, 0, n_scan_slots, pl.C_scan, pl.n_qg_scan)) return SSV_ELAUNCH;
+        if (p->mode != SSV_REUSE && launch_routing()) return SSV_ELAUNCH;
+        if (launch_stream(SSV_K_STREAM_B, kRolesSlc, n_scan_slots, pl.n_slc_splits, pl.C, pl.n_qg)) return SSV_ELAUNCH;
+    }
+    // few slices per row: thread groups own rows; many slices: one workgroup per row, slices in parallel
+    const bool by_rows = pl.n_slots <= kCombineRowsMaxSlots;
     if (tm.begin(SSV_K_COMBINE)) return SSV_ELAUNCH;
     for (int r = 0; r < reps; ++r) {
-        if (by_rows) SSV_LAUNCH(SSV_K_COMBINE, (k_combine_rows<BF16, DV>), grid_c, 0, ca);
-        else SSV_LAUNCH(SSV_K_COMBINE, (k_combine_slices<BF16, DV>), grid_c, 0, ca);
+        if (by_rows) SSV_LAUNCH(SSV_K_COMBINE, (k_combine_rows<BF16, DV>), grid_rows, 0, ca);
+        else SSV_LAUNCH(SSV_K_COMBINE, (k_combine_slices<BF16, DV>), (int)lo.rows_total, 0, ca);
     }
     if (hipGetLastError() != hipSuccess || tm.end(SSV_K_COMBINE)) return SSV_ELAUNCH;
     return SSV_OK;
@@ -390,11 +472,12 @@ int verify_impl(const void* q, const void* k, const void* v, const void* kc, con
                 const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query, const int32_t* parents,
                 const ssv_nsa_params* p, void* out, int32_t* sel_idx, void* workspace, size_t workspace_bytes,
                 void* stream, float* kernel_ms, int repeats, bool timed) {
-    if (!q || !k || !v || !kc || !vc || !gates || !seq_lens || !n_cmp || !p || !out || !sel_idx) return SSV_EINVAL;
-    if (timed && (!kernel_ms || repeats < 1 || repeats > 1000)) return SSV_EINVAL;
+    // the parameter checks come first and are the ones ssv_nsa_plan_query and ssv_nsa_workspace_bytes run
     Layout lo;
     const int rc = make_layout(p, &lo);
     if (rc != SSV_OK) return rc;
+    if (!q || !k || !v || !kc || !vc || !gates || !seq_lens || !n_cmp || !out || !sel_idx) return SSV_EINVAL;
+    if (timed && (!kernel_ms || repeats < 1 || repeats > 1000)) return SSV_EINVAL;
     const void* aligned16[] = {q, k, v, kc, vc, out};
     for (const void* ptr : aligned16)
         if (reinterpret_cast<uintptr_t>(ptr) % 16) return SSV_EINVAL;
@@ -486,7 +569,7 @@ int ssv_nsa_compress(const void* k, const void* v, void* k_cmp, void* v_cmp, con
     ca.before = committed_before; ca.after = committed_after; ca.n_cmp = n_cmp;
     ca.B = p->B; ca.H_kv = p->H_kv; ca.l = p->l; ca.d = p->d; ca.ratio = ratio;
     // 32 chunks per workgroup: with 16 or 24 column groups per row the chunk tasks fill whole passes of 256 threads
-    ca.rows_per_wg = std::min(std::max(1, env_int("SSV_CMP_ROWS", 33 - ratio)), p->max_new_rows); ca.cap = p->cmp_capacity; ca.kv_cap = p->kv_capacity;
+    ca.rows_per_wg = std::min(std::max(1, 33 - ratio), p->max_new_rows); ca.cap = p->cmp_capacity; ca.kv_cap = p->kv_capacity;
     ca.max_new = p->max_new_rows;
     ca.k_groups = p->d_k * es / 16; ca.v_groups = p->d_v * es / 16;
     ca.inv_l = 1.0f / (float)p->l;
@@ -540,23 +623,14 @@ const char* ssv_nsa_kernel_name(int idx) {
         case SSV_K_TOPN: return "k_topn";
         case SSV_K_STREAM_B: return "k_stream (selected blocks, merged schedule)";
         case SSV_K_COMBINE: return "k_combine";
+        case SSV_K_STREAM_W: return "k_stream (window branch alone; unfused execution)";
+        case SSV_K_OUT_CMP: return "k_combine_rows (compressed branch output to scratch; unfused execution)";
+        case SSV_K_OUT_SLC: return "k_combine_rows (selected branch output to scratch; unfused execution)";
+        case SSV_K_OUT_WIN: return "k_combine_rows (window branch output to scratch; unfused execution)";
         default: return "";
     }
 }
 
-int ssv_nsa_version(void) { return 1; }
-
-#ifdef SSV_CLOCKS
-// development builds only: copy the in-kernel time stamps of the last k_stream launch to the host
-int ssv_debug_read_clocks_topn(long long* host_out, int n) {
-    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ssv::g_clk_topn), sizeof(long long) * n) == hipSuccess ? 0 : -1;
-}
-int ssv_debug_read_clocks_imp(long long* host_out, int n) {
-    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ssv::g_clk_imp), sizeof(long long) * n) == hipSuccess ? 0 : -1;
-}
-int ssv_debug_read_clocks(long long* host_out, int n) {
-    return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(ssv::g_clk), sizeof(long long) * n) == hipSuccess ? 0 : -1;
-}
-#endif
+int ssv_nsa_version(void) { return 2; }
 
 }  // extern "C"

@@ -17,7 +17,8 @@ def _to_device(arr: np.ndarray, dtype: str, device) -> torch.Tensor:
 
 
 class DeviceCase:
-    def __init__(self, case, device="cuda:0", mode=B.SSV_REFRESH, group_size=0, scale=0.0):
+    def __init__(self, case, device="cuda:0", mode=B.SSV_REFRESH, group_size=0, scale=0.0, exec=B.SSV_EXEC_FUSED,
+                 topn_home=B.SSV_TOPN_AUTO, max_slice_tiles=0, strided_q_out=False):
         if not torch.cuda.is_available():
             raise RuntimeError("DeviceCase needs a GPU: the NSA verification path has no CPU fallback")
         B.load_library()
@@ -26,6 +27,15 @@ class DeviceCase:
         nsa = case.nsa
         dt = case.dtype
         self.q = _to_device(case.q, dt, self.device)
+        tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+        q_stride = out_stride = (0, 0, 0)
+        if strided_q_out:
+            # q and out as views into wider buffers (a fused QKV projection's output, a padded output): head-major
+            # [B, H, T, d + 8] storage addressed through (batch, query, head) strides
+            qbuf = torch.zeros((case.B, case.H, case.T, case.d_k + 8), dtype=tdt, device=self.device)
+            qbuf[..., :case.d_k] = self.q.permute(0, 2, 1, 3)
+            self.q = qbuf.permute(0, 2, 1, 3)[..., :case.d_k]
+            q_stride = self.q.stride()[:3]
         self.k = _to_device(case.k, dt, self.device)
         self.v = _to_device(case.v, dt, self.device)
         self.k_cmp = _to_device(case.k_cmp, dt, self.device)
@@ -36,8 +46,12 @@ class DeviceCase:
         self.n_query = torch.from_numpy(np.ascontiguousarray(case.n_query, np.int32)).to(self.device)
         self.parents = None if case.parents is None else \
             torch.from_numpy(np.ascontiguousarray(case.parents, np.int32)).to(self.device)
-        tdt = torch.bfloat16 if dt == "bf16" else torch.float32
         self.out = torch.zeros((case.B, case.T, case.H, case.d_v), dtype=tdt, device=self.device)
+        if strided_q_out:
+            obuf = torch.full((case.B, case.H, case.T, case.d_v + 8), 7.0, dtype=tdt, device=self.device)
+            self.out_buf = obuf
+            self.out = obuf.permute(0, 2, 1, 3)[..., :case.d_v]
+            out_stride = self.out.stride()[:3]
         self.sel_idx = torch.full((case.B, case.T, case.H_kv, nsa.n_sel), -1, dtype=torch.int32, device=self.device)
         self.params = B.make_params(
             B=case.B, T=case.T, H=case.H, H_kv=case.H_kv, d_k=case.d_k, d_v=case.d_v, l=nsa.l, d=nsa.d,
@@ -46,7 +60,8 @@ class DeviceCase:
             max_seq_len=int(case.seq_lens.max()), max_n_cmp=int(case.n_cmp.max()),
             avg_seq_len=int(case.seq_lens.mean()),
             k_stride=self.k.stride()[:3], v_stride=self.v.stride()[:3],
-            kc_stride=self.k_cmp.stride()[:3], vc_stride=self.v_cmp.stride()[:3])
+            kc_stride=self.k_cmp.stride()[:3], vc_stride=self.v_cmp.stride()[:3], q_stride=q_stride, out_stride=out_stride,
+            exec=exec, topn_home=topn_home, max_slice_tiles=max_slice_tiles)
         self.workspace_bytes = 0
         self.workspace = None
         self.set_group_size(group_size, mode)
@@ -59,7 +74,9 @@ class DeviceCase:
         mode = self.params.mode if mode is None else mode
         # the split plan (and with it the scratch size) depends on the mode: size the workspace for all of them
         need = 0
-        for m in (B.SSV_REFRESH, B.SSV_REUSE, B.SSV_REFRESH_SHARED):
+        modes = (B.SSV_REFRESH, B.SSV_REUSE) if self.params.exec == B.SSV_EXEC_UNFUSED else \
+            (B.SSV_REFRESH, B.SSV_REUSE, B.SSV_REFRESH_SHARED)
+        for m in modes:
             self.params.mode = m
             need = max(need, B.ssv_nsa_workspace_bytes(self.params))
         if need > self.workspace_bytes:
@@ -70,6 +87,11 @@ class DeviceCase:
     def set_mode(self, mode: int) -> None:
         self.params.mode = mode
         self.plan = B.ssv_nsa_plan_query(self.params)
+
+    def set_exec(self, exec: int, mode=None) -> None:
+        """Fused (grouped, merged schedule) or unfused (per query, one launch per branch) execution."""
+        self.params.exec = exec
+        self.set_group_size(0, mode)
 
     def set_queries(self, q: np.ndarray) -> None:
         """Replace the verifier queries (same shape), keeping the caches."""

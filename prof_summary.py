@@ -1,7 +1,7 @@
 """Condense rocprofv3 CSV output into the short text tables kept under profiles/.
 
-    python -m paper_2605_19893_amd.prof_summary trace  <dir>/p_kernel_trace.csv
-    python -m paper_2605_19893_amd.prof_summary pmc    <dir>/p_counter_collection.csv [...]
+    python prof_summary.py trace  <dir>/p_kernel_trace.csv
+    python prof_summary.py pmc    <dir>/p_counter_collection.csv [...]
 
 `trace` prints calls / average / min / max duration per (kernel, number of workgroups); `pmc` prints the
 average counter value per dispatch for the same grouping.  Reads files only; runs nothing on the GPU.

@@ -32,9 +32,17 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    # 20 four-byte fields followed by 12 int64 strides; 11 ints, padding and an int64 in the plan
-    assert ctypes.sizeof(B.SsvNsaParams) == 22 * 4 + 12 * 8
-    assert ctypes.sizeof(B.SsvNsaPlan) == 14 * 4 + 8
+    # 21 four-byte fields (+ 4 bytes of padding), 18 int64 strides, 4 four-byte fields; 16 ints and an int64 in the plan
+    assert ctypes.sizeof(B.SsvNsaParams) == 22 * 4 + 18 * 8 + 4 * 4
+    assert ctypes.sizeof(B.SsvNsaPlan) == 16 * 4 + 8
+    with open(os.path.join(ROOT, "include", "ssv_nsa.h")) as f:
+        header = f.read()
+    # every field of the two structs appears in the header in the binding's order
+    for struct, cls in (("ssv_nsa_params", B.SsvNsaParams), ("ssv_nsa_plan", B.SsvNsaPlan)):
+        body = header[header.index("typedef struct " + struct):header.index("} " + struct + ";")]
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        names = re.findall(r"\b([A-Za-z_][A-Za-z0-9_]*)\s*(?:\[\d+\])?\s*[,;]", body)
+        assert names == [n for n, _ in cls._fields_], (struct, names)
 
 
 def test_error_strings():
@@ -57,6 +65,12 @@ def test_supported_shapes():
     (dict(w=0), B.SSV_EINVAL), (dict(avg_seq_len=40000), B.SSV_EINVAL), (dict(group_size=9), B.SSV_EINVAL), (dict(scale=-1.0), B.SSV_EINVAL),
     (dict(k_stride=(1, 1, 100)), B.SSV_EINVAL), (dict(k_stride=(4 * 32832 * 192, 32832 * 192, 196)), B.SSV_EINVAL),
     (dict(mode=B.SSV_REFRESH_SHARED, group_size=9), B.SSV_EINVAL),
+    (dict(exec=2), B.SSV_EINVAL), (dict(topn_home=3), B.SSV_EINVAL), (dict(max_slice_tiles=1), B.SSV_EINVAL),
+    (dict(max_slice_tiles=65), B.SSV_EINVAL), (dict(exec=B.SSV_EXEC_UNFUSED, group_size=2), B.SSV_EINVAL),
+    (dict(exec=B.SSV_EXEC_UNFUSED, mode=B.SSV_REFRESH_SHARED), B.SSV_EINVAL),
+    (dict(q_stride=(8 * 64 * 192, 64 * 192, 100)), B.SSV_EINVAL), (dict(out_stride=(8 * 64 * 128, 64 * 128, 130)), B.SSV_EINVAL),
+    # the merged schedule of 32 queries x 32 blocks does not fit the LDS next to the tiles of d_k = 192
+    (dict(T=32, H=16, H_kv=4, n_sel=32, group_size=32), B.SSV_EUNSUPPORTED),
     (dict(T=129), B.SSV_EUNSUPPORTED), (dict(H=96, H_kv=4), B.SSV_EUNSUPPORTED), (dict(l_sel=128), B.SSV_EUNSUPPORTED),
     (dict(d_k=96), B.SSV_EUNSUPPORTED), (dict(n_sel=40), B.SSV_EUNSUPPORTED),
     (dict(max_seq_len=2 ** 21), B.SSV_EUNSUPPORTED),
@@ -135,6 +149,53 @@ def test_plan_fills_the_chip_and_respects_limits():
     # 12 queries: two balanced scan groups of 6
     pl = B.ssv_nsa_plan_query(std_params(B=32, T=12, max_seq_len=131072, max_n_cmp=8191))
     assert (pl.C, pl.n_qg, pl.C_scan, pl.n_qg_scan) == (4, 3, 6, 2)
+
+
+def test_plan_reflects_the_execution_choices():
+    auto = B.ssv_nsa_plan_query(std_params())
+    assert auto.topn_in_slc == 1 and auto.n_launches == 4 and auto.n_imp_chunks >= 1      # cfg1: selection inside launch B
+    sep = B.ssv_nsa_plan_query(std_params(topn_home=B.SSV_TOPN_SEPARATE))
+    assert sep.topn_in_slc == 0 and sep.n_launches == 5
+    big = std_params(B=16, T=4, max_seq_len=65536, max_n_cmp=4095)
+    assert B.ssv_nsa_plan_query(big).topn_in_slc == 0
+    big.topn_home = B.SSV_TOPN_IN_SLC
+    assert B.ssv_nsa_plan_query(big).topn_in_slc == 1
+    reuse = B.ssv_nsa_plan_query(std_params(mode=B.SSV_REUSE))
+    assert reuse.topn_in_slc == 0 and reuse.n_imp_chunks == 0 and reuse.n_launches == 2
+    # several rounds of workgroups: the slice bound applies
+    long_default = B.ssv_nsa_plan_query(std_params(B=32, T=16, max_seq_len=131072, max_n_cmp=8191))
+    long_12 = B.ssv_nsa_plan_query(std_params(B=32, T=16, max_seq_len=131072, max_n_cmp=8191, max_slice_tiles=12))
+    assert long_default.tiles_per_chunk <= 24 and long_12.tiles_per_chunk <= 12 and long_12.n_cmp_chunks > long_default.n_cmp_chunks
+    # unfused execution: every query on its own, one launch per branch plus their merges and the gate kernel
+    un = B.ssv_nsa_plan_query(std_params(exec=B.SSV_EXEC_UNFUSED))
+    assert (un.C, un.n_qg, un.C_scan, un.n_qg_scan, un.topn_in_slc, un.n_launches) == (1, 8, 1, 8, 0, 9)
+    assert B.ssv_nsa_plan_query(std_params(exec=B.SSV_EXEC_UNFUSED, mode=B.SSV_REUSE)).n_launches == 7
+    rows = 8 * 64
+    assert un.workspace_bytes >= 3 * rows * 128 * 2 + un.n_slots * rows * 130 * 4
+
+
+def test_plan_workspace_and_verify_agree():
+    """One set of checks serves the three entry points: whatever the plan query accepts, the workspace query sizes
+    and verify accepts (up to its pointer checks), and the reverse."""
+    fake = 4096
+    grid = [dict(), dict(T=32, H=16, H_kv=4, n_sel=32, group_size=32), dict(T=32, H=16, H_kv=4, n_sel=32, group_size=16),
+            dict(T=64, H=8, H_kv=4, n_sel=32, group_size=64), dict(T=64, H=8, H_kv=4, n_sel=16, group_size=64),
+            dict(d_k=64, d_v=64, T=64, H=8, H_kv=4, n_sel=32, group_size=64), dict(exec=B.SSV_EXEC_UNFUSED)]
+    seen = set()
+    for over in grid:
+        p = std_params(**over)
+        try:
+            B.ssv_nsa_plan_query(p)
+            plan_rc = B.SSV_OK
+        except B.SsvError as e:
+            plan_rc = e.code
+        need = B.ssv_nsa_workspace_bytes(p)
+        assert (need > 0) == (plan_rc == B.SSV_OK)
+        with pytest.raises(B.SsvError) as e:      # a null query pointer: the first check after the parameters
+            B.ssv_nsa_verify(None, fake, fake, fake, fake, fake, fake, fake, None, None, p, fake, fake, fake, 1 << 40, 0)
+        assert e.value.code == (B.SSV_EINVAL if plan_rc == B.SSV_OK else plan_rc), over
+        seen.add(plan_rc)
+    assert seen == {B.SSV_OK, B.SSV_EUNSUPPORTED}
 
 
 def test_shared_index_plan_keeps_the_automatic_grouping():

@@ -19,9 +19,9 @@ def dev_mod():
     return device_case
 
 
-def run_refresh(dev_mod, oracle, case, group_size=0):
+def run_refresh(dev_mod, oracle, case, group_size=0, **dev_kw):
     ref = oracle.nsa_verify(case)
-    dev = dev_mod.DeviceCase(case, group_size=group_size)
+    dev = dev_mod.DeviceCase(case, group_size=group_size, **dev_kw)
     print(f"[run] {case.name} refresh C={dev.plan.C} plan={dev.plan.as_dict()}", flush=True)
     dev.run()
     out, sel = dev.results()
@@ -45,12 +45,12 @@ def run_reuse(dev_mod, oracle, case, sel, group_size=0, dev=None):
     return out
 
 
-def run_shared(dev_mod, oracle, case, C):
+def run_shared(dev_mod, oracle, case, C, **dev_kw):
     """Approximate shared-index variant with groups of C queries, then reuse of the indices it wrote."""
     from paper_2605_19893_amd import SSV_REFRESH_SHARED
     ref = oracle.nsa_verify_shared(case, C)
     rep = oracle.group_representatives(case, C)
-    dev = dev_mod.DeviceCase(case, mode=SSV_REFRESH_SHARED, group_size=C)
+    dev = dev_mod.DeviceCase(case, mode=SSV_REFRESH_SHARED, group_size=C, **dev_kw)
     assert dev.plan.share_group == C
     print(f"[run] {case.name} shared-index C={C} plan={dev.plan.as_dict()}", flush=True)
     dev.run()
@@ -266,35 +266,34 @@ def test_scan_launch_with_its_own_grouping(dev_mod, oracle, shape):
 
 
 @pytest.mark.parametrize("where", ["separate_launch", "inside_selected_launch"])
-def test_both_homes_of_the_top_n_selection(dev_mod, oracle, where, monkeypatch):
+def test_both_homes_of_the_top_n_selection(dev_mod, oracle, where):
     """The top-n selection runs inside the selected-branch launch (one wavefront per query) when that launch
-    leaves CUs idle, else as a launch of its own; both are forced here on the same cases (the library reads the
-    switches at every call): chain with ragged query counts, tree, shared-index variant, massive ties, a geometry
-    other than the standard one, fp32."""
-    if where == "separate_launch":
-        monkeypatch.setenv("SSV_SEPARATE_TOPN", "1")
-    else:
-        monkeypatch.setenv("SSV_FUSED_TOPN_MAX_WGS", "1000000")
+    leaves CUs idle, else as a launch of its own; both are forced here on the same cases through the topn_home
+    parameter: chain with ragged query counts, tree, shared-index variant, massive ties, a geometry other than
+    the standard one, fp32."""
+    from paper_2605_19893_amd import binding as B
+    home = B.SSV_TOPN_SEPARATE if where == "separate_launch" else B.SSV_TOPN_IN_SLC
     case = si.make_case("topn_home_chain", "bf16", 2, 11, 64, 4, 192, 128, si.STD_NSA, [5000, 2300], 181, rho=0.6,
                         n_query=[11, 7], poison_pad=True)
     for C in (0, 8, 3):
-        dev, ref, out, sel = run_refresh(dev_mod, oracle, case, group_size=C)
+        dev, ref, out, sel = run_refresh(dev_mod, oracle, case, group_size=C, topn_home=home)
+        assert dev.plan.topn_in_slc == (where == "inside_selected_launch")
     run_reuse(dev_mod, oracle, case, sel, dev=dev)
     par = si.tree_parents((3, 2, 2), "dfs")
     case = si.make_case("topn_home_tree", "bf16", 2, len(par), 32, 2, 192, 128, si.STD_NSA, [4100, 1500], 183, rho=0.6,
                         parents=par)
-    run_refresh(dev_mod, oracle, case)
-    run_shared(dev_mod, oracle, case, 3)
+    run_refresh(dev_mod, oracle, case, topn_home=home)
+    run_shared(dev_mod, oracle, case, 3, topn_home=home)
     # every key equal: all importances tie, the smallest indices win (the list of candidates overflows)
     case = si.make_case("topn_home_ties", "f32", 1, 3, 4, 2, 64, 64, si.STD_NSA, [40000], 185, rho=0.0)
     case.k[:] = 0.25
     case.k_cmp[:] = 0.25
-    dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case, topn_home=home)
     assert np.array_equal(sel, ref.sel_idx)
     # l = 64, d = 16, l' = 64: seven compressed columns per block (the general form of the importance sum)
     nsa = si.NsaParams(l=64, d=16, l_sel=64, n_sel=8, w=128)
     case = si.make_case("topn_home_geometry", "f32", 2, 5, 8, 2, 64, 64, nsa, [3000, 1111], 187, rho=0.4)
-    dev, ref, out, sel = run_refresh(dev_mod, oracle, case)
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case, topn_home=home)
     assert np.array_equal(sel, ref.sel_idx)
 
 
@@ -424,3 +423,52 @@ def test_calls_can_be_captured_in_a_hip_graph(dev_mod, oracle):
         graph2.replay()
         out, _ = dev.results()
         assert np.array_equal(out, out_reuse), replay
+
+
+# ----------------------------------------------------------------------------- unfused execution, strided q / out
+@pytest.mark.parametrize("shape", ["std_chain", "tree_small_heads", "fp32"])
+def test_unfused_per_query_execution_matches_the_oracle(dev_mod, oracle, shape):
+    """SSV_EXEC_UNFUSED (every query on its own, one launch per branch, branch outputs through scratch in the
+    storage type, separate gate kernel) computes the same function: refresh and reuse against the oracle, and the
+    indices equal to the fused execution's bit for bit (the routing kernels are the same)."""
+    from paper_2605_19893_amd import binding as B
+    if shape == "std_chain":
+        case = si.make_case("unfused_chain", "bf16", 2, 9, 64, 4, 192, 128, si.STD_NSA, [5000, 2300], 301, rho=0.6,
+                            n_query=[9, 5], poison_pad=True)
+    elif shape == "tree_small_heads":
+        par = si.tree_parents((3, 2, 2), "bfs")
+        case = si.make_case("unfused_tree", "bf16", 2, len(par), 32, 8, 64, 64, si.STD_NSA, [4100, 700], 303, rho=0.5,
+                            parents=par)
+    else:
+        case = si.make_case("unfused_f32", "f32", 1, 5, 8, 2, 64, 64, si.STD_NSA, [3000], 305, rho=0.4)
+    dev_f, ref, out_f, sel_f = run_refresh(dev_mod, oracle, case)
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case, exec=B.SSV_EXEC_UNFUSED)
+    assert dev.plan.C == 1 and dev.plan.n_launches == 9
+    assert np.array_equal(sel, sel_f)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+    assert dev.plan.n_launches == 7
+    # per-kernel timing entry point covers the additional launches
+    ms = []
+    dev.run(kernel_ms=ms)
+    assert len(ms) == B.SSV_NUM_TIMINGS and all(ms[k] > 0 for k in (B.SSV_K_STREAM_A, B.SSV_K_STREAM_B, B.SSV_K_STREAM_W,
+                                                                   B.SSV_K_OUT_CMP, B.SSV_K_OUT_SLC, B.SSV_K_OUT_WIN, B.SSV_K_COMBINE))
+
+
+@pytest.mark.parametrize("exec_name", ["fused", "unfused"])
+def test_strided_queries_and_output(dev_mod, oracle, exec_name):
+    """q and out addressed through (batch, query, head) strides: head-major buffers with padded rows; the padding
+    of the output buffer is left untouched."""
+    import torch
+    from paper_2605_19893_amd import binding as B
+    ex = B.SSV_EXEC_UNFUSED if exec_name == "unfused" else B.SSV_EXEC_FUSED
+    par = si.tree_parents((2, 3), "dfs")
+    case = si.make_case("strided", "bf16", 2, len(par), 64, 4, 192, 128, si.STD_NSA, [3000, 4500], 311, rho=0.5, parents=par,
+                        n_query=[len(par), 5])
+    dev, ref, out, sel = run_refresh(dev_mod, oracle, case, exec=ex, strided_q_out=True)
+    assert dev.params.q_stride[2] == case.T * (case.d_k + 8) and dev.params.out_stride[1] == case.d_v + 8
+    assert torch.all(dev.out_buf[..., case.d_v:] == 7.0)
+    run_reuse(dev_mod, oracle, case, sel, dev=dev)
+    dev.set_group_size(0 if ex else 3, B.SSV_REFRESH)
+    dev.run()
+    out2, sel2 = dev.results()
+    check(case, compare(case, oracle, ref, out2, sel2))

@@ -45,13 +45,14 @@ def draw_case(seed):
 
 
 @pytest.mark.parametrize("seed", list(range(24)))
-def test_random_problem(seed, oracle, monkeypatch):
+def test_random_problem(seed, oracle):
     from paper_2605_19893_amd import SSV_REFRESH, SSV_REUSE, SSV_REFRESH_SHARED
+    from paper_2605_19893_amd import binding as B
     from paper_2605_19893_amd.device_case import DeviceCase
     case, group, scan_group, share, fused = draw_case(seed)
-    monkeypatch.setenv("SSV_FUSED_TOPN_MAX_WGS", "1000000" if fused else "0")
     ref = oracle.nsa_verify(case)
-    dev = DeviceCase(case, group_size=group)
+    dev = DeviceCase(case, group_size=group, topn_home=B.SSV_TOPN_IN_SLC if fused else B.SSV_TOPN_SEPARATE,
+                     max_slice_tiles=(0, 2, 5)[seed % 3])
     dev.set_group_size(group, SSV_REFRESH, scan_group_size=scan_group)
     print(f"[run] {case.name} B={case.B} T={case.T} H={case.H}/{case.H_kv} L={case.seq_lens.tolist()} nq={case.n_query.tolist()} "
           f"tree={case.parents is not None} fused_topn={fused} plan={dev.plan.as_dict()}", flush=True)

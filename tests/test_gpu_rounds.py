@@ -10,6 +10,7 @@ import pytest
 
 import ssv_inputs as si
 from oracle import compress as oc
+from oracle import planner as op
 from parity import check, compare
 
 pytestmark = pytest.mark.gpu
@@ -34,7 +35,13 @@ def test_verification_rounds_with_deferred_commit(oracle):
     dev.v_cmp.zero_()
     del roomy
     stream = torch.cuda.current_stream().cuda_stream
-    guard = B.ssv_guard_init(B.ssv_guard_default_config(), [6.0, 5.0, 4.0])
+    # a guard with a short warm-up and patience, so that the four rounds take it through two moves: the profiled
+    # expectations of the first two strategies are far above anything a chain of 8 can accept
+    gcfg = B.ssv_guard_default_config()
+    gcfg.warmup_steps, gcfg.patience = 1, 1
+    expected = [20.0, 19.0, 0.1]
+    guard = B.ssv_guard_init(gcfg, expected)
+    observations, strategies = [], []
     committed_before = np.zeros(2, np.int32)
     rng = np.random.default_rng(7)
     for r in range(rounds):
@@ -77,8 +84,10 @@ def test_verification_rounds_with_deferred_commit(oracle):
         check(mirror, compare(mirror, oracle, oracle.nsa_verify(mirror, sel_idx=sel), out2, sel, reuse_sel=sel))
         # 3. acceptance of a prefix of the chain; the guard sees the counts
         accept = rng.integers(0, T + 1, size=2).astype(np.int32)
-        strategy = B.ssv_guard_observe(guard, float(accept.mean()), 1.0)
-        assert strategy == 0        # four rounds are inside the warm-up
+        observations.append((float(accept.mean()), 1.0 + 0.25 * r))
+        strategies.append(B.ssv_guard_observe(guard, *observations[-1]))
         committed_before = L.copy()
         case = si.advance_case(case, step=r + 10, accept=accept)
-    assert guard.total_steps == rounds
+    assert guard.total_steps == rounds and guard.transitions == 2
+    want = op.guard_trace(op.GuardConfig(warmup_steps=1, patience=1), expected, None, observations)
+    assert strategies == want == [0, 1, 1, 2]
