@@ -374,3 +374,40 @@ def advance_case(case: VerifyCase, step: int = 1, accept: Optional[np.ndarray] =
     _fill_queries(nxt, seed, 0.7)
     nxt.extra["accept"] = accept
     return nxt
+
+
+def planted_overlap_indices(case: VerifyCase, s: int, seed: int) -> np.ndarray:
+    """Index sets for reuse-mode calls with a controlled overlap (the knob of the paper's kernel benchmark, Section
+    7.3): along every chain, consecutive verifier queries share exactly `s` selected blocks, the mandatory initial
+    and local blocks included (so s >= 3 at the standard parameters).  Sets are valid selections: ascending, no
+    block beyond the query's own, forced blocks present.  [B, T, H_kv, n_sel] int32, -1 padded.  Chains only."""
+    assert case.parents is None, "planted overlaps are defined along linear chains"
+    nsa = case.nsa
+    sel = np.full((case.B, case.T, case.H_kv, nsa.n_sel), -1, np.int32)
+    for b in range(case.B):
+        L, Tq = int(case.seq_lens[b]), int(case.n_query[b])
+        for g in range(case.H_kv):
+            rng = _rng(seed, 77, b, g)
+            prev = None
+            for i in range(Tq):
+                J = (L + i) // nsa.l_sel
+                forced = {j for j in range(nsa.n_init) if j <= J} | {j for j in range(J - nsa.n_local + 1, J + 1) if j >= 0}
+                n_eff = min(nsa.n_sel, J + 1)
+                n_free = n_eff - len(forced)
+                pool = [j for j in range(J + 1) if j not in forced]
+                if prev is None:
+                    chosen = set(rng.choice(pool, size=n_free, replace=False).tolist()) if n_free else set()
+                else:
+                    keep_from = sorted(prev - forced)
+                    n_keep = s - len(forced & prev)
+                    fresh_pool = [j for j in pool if j not in prev]
+                    assert 0 <= n_keep <= min(len(keep_from), n_free) and n_free - n_keep <= len(fresh_pool), \
+                        f"overlap {s} cannot be planted at L={L}, query {i}"
+                    kept = set(rng.choice(keep_from, size=n_keep, replace=False).tolist()) if n_keep else set()
+                    fresh = set(rng.choice(fresh_pool, size=n_free - n_keep, replace=False).tolist()) if n_free > n_keep else set()
+                    chosen = kept | fresh
+                cur = forced | chosen
+                row = sorted(cur)
+                sel[b, i, g, :len(row)] = row
+                prev = cur
+    return sel
