@@ -45,6 +45,7 @@ extern "C" {
 #define SSV_EUNSUPPORTED -2   /* valid NSA problem, but a shape this build has no kernel for */
 #define SSV_EWORKSPACE   -3   /* workspace missing, misaligned or smaller than ssv_nsa_workspace_bytes */
 #define SSV_ELAUNCH      -4   /* the HIP runtime reported an error when enqueueing */
+#define SSV_ESTATIC      -5   /* ssv_nsa_verify_static: the problem needs more scratch than SSV_STATIC_SCRATCH_BYTES */
 
 #define SSV_F32  0
 #define SSV_BF16 1
@@ -186,6 +187,25 @@ int ssv_nsa_verify_timed(const void* q, const void* k, const void* v, const void
                          const float* gates, const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query,
                          const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx,
                          void* workspace, size_t workspace_bytes, void* stream, int repeats, float* kernel_ms);
+
+/*
+ * ssv_nsa_verify without a workspace argument, for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the scratch is a fixed array of
+ * SSV_STATIC_SCRATCH_BYTES inside the library's device image (one copy per GPU, held until the process ends),
+ * and the call allocates and frees nothing.  Same arguments, semantics and results as ssv_nsa_verify.
+ * Returns SSV_ESTATIC, before anything is enqueued, when ssv_nsa_workspace_bytes(p) exceeds SSV_STATIC_SCRATCH_BYTES
+ * (use ssv_nsa_verify with a workspace of the caller's for such a problem).
+ * The first call on a GPU looks up that GPU's copy of the array (and, like ssv_nsa_verify, raises the kernels'
+ * dynamic-LDS limit): make it outside graph capture.
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (different streams or
+ * host threads) race, like calls of ssv_nsa_verify that share a workspace.  The array keeps the previous call's
+ * contents; no kernel relies on them.
+ */
+#define SSV_STATIC_SCRATCH_BYTES (32u << 20)
+int ssv_nsa_verify_static(const void* q, const void* k, const void* v, const void* k_cmp, const void* v_cmp,
+                          const float* gates, const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query,
+                          const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx,
+                          void* stream);
 
 /* Parameters of ssv_nsa_compress.  Strides in elements (sequence, KV head, row), as in ssv_nsa_params. */
 typedef struct ssv_cmp_params {

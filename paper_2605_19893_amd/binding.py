@@ -13,7 +13,8 @@ from typing import Optional
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libssv_nsa.so")
 
-SSV_OK, SSV_EINVAL, SSV_EUNSUPPORTED, SSV_EWORKSPACE, SSV_ELAUNCH = 0, -1, -2, -3, -4
+SSV_OK, SSV_EINVAL, SSV_EUNSUPPORTED, SSV_EWORKSPACE, SSV_ELAUNCH, SSV_ESTATIC = 0, -1, -2, -3, -4, -5
+SSV_STATIC_SCRATCH_BYTES = 32 << 20
 SSV_F32, SSV_BF16 = 0, 1
 SSV_REFRESH, SSV_REUSE, SSV_REFRESH_SHARED = 0, 1, 2
 SSV_MAX_T = 128
@@ -24,7 +25,7 @@ SSV_T_EVENT_PAIR, SSV_NUM_TIMINGS = 9, 10
 SSV_EXEC_FUSED, SSV_EXEC_UNFUSED = 0, 1
 SSV_TOPN_AUTO, SSV_TOPN_SEPARATE, SSV_TOPN_IN_SLC = 0, 1, 2
 
-EXPORTS = ("ssv_nsa_verify", "ssv_nsa_verify_timed", "ssv_nsa_plan_query", "ssv_nsa_workspace_bytes",
+EXPORTS = ("ssv_nsa_verify", "ssv_nsa_verify_static", "ssv_nsa_verify_timed", "ssv_nsa_plan_query", "ssv_nsa_workspace_bytes",
            "ssv_nsa_supported", "ssv_nsa_strerror", "ssv_nsa_kernel_name", "ssv_nsa_version", "ssv_nsa_compress",
            "ssv_guard_default_config", "ssv_guard_init", "ssv_guard_observe", "ssv_tree_flatten")
 SSV_GUARD_MAX_CANDIDATES = 16
@@ -92,6 +93,8 @@ def load_library() -> ctypes.CDLL:
         common = [vp] * 5 + [vp, i32p, i32p, i32p, i32p, ctypes.POINTER(SsvNsaParams), vp, i32p, vp, ctypes.c_size_t, vp]
         lib.ssv_nsa_verify.restype = ctypes.c_int
         lib.ssv_nsa_verify.argtypes = common
+        lib.ssv_nsa_verify_static.restype = ctypes.c_int
+        lib.ssv_nsa_verify_static.argtypes = common[:13] + [vp]
         lib.ssv_nsa_verify_timed.restype = ctypes.c_int
         lib.ssv_nsa_verify_timed.argtypes = common + [ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
         lib.ssv_nsa_plan_query.restype = ctypes.c_int
@@ -188,6 +191,16 @@ def ssv_nsa_verify(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_
         kernel_ms.extend(float(x) for x in ms)
     if rc != SSV_OK:
         raise SsvError(rc, "ssv_nsa_verify")
+
+
+def ssv_nsa_verify_static(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_parents, p: SsvNsaParams, out, sel_idx,
+                          stream: int) -> None:
+    """ssv_nsa_verify on the library's own fixed scratch array: no workspace argument, nothing allocated."""
+    rc = load_library().ssv_nsa_verify_static(_ptr(q), _ptr(k), _ptr(v), _ptr(k_cmp), _ptr(v_cmp), _ptr(gates), _ptr(seq_lens),
+                                              _ptr(n_cmp), _ptr(n_query), _ptr(tree_parents), ctypes.byref(p), _ptr(out),
+                                              _ptr(sel_idx), ctypes.c_void_p(int(stream)))
+    if rc != SSV_OK:
+        raise SsvError(rc, "ssv_nsa_verify_static")
 
 
 def make_cmp_params(*, B, H_kv, d_k, d_v, l, d, dtype, max_new_rows, kv_capacity, cmp_capacity, k_stride, v_stride,

@@ -15,6 +15,10 @@
 #include "k_topn.hpp"
 #include "planner.hpp"
 
+// Scratch of ssv_nsa_verify_static: one copy per GPU inside the library's device image.  In host code this name is
+// only a handle for hipGetSymbolAddress; the device address it resolves to is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[SSV_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace ssv;
@@ -535,6 +539,26 @@ int ssv_nsa_verify(const void* q, const void* k, const void* v, const void* k_cm
                        workspace_bytes, stream, nullptr, 1, false);
 }
 
+int ssv_nsa_verify_static(const void* q, const void* k, const void* v, const void* k_cmp, const void* v_cmp,
+                          const float* gates, const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query,
+                          const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx, void* stream) {
+    Layout lo;
+    const int rc = make_layout(p, &lo);
+    if (rc != SSV_OK) return rc;
+    if (lo.total > (size_t)SSV_STATIC_SCRATCH_BYTES) return SSV_ESTATIC;
+    // address of the current device's copy of the array, looked up once per device
+    static std::atomic<void*> scratch_ptr[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SSV_ELAUNCH;
+    void* ptr = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SSV_ELAUNCH;
+        scratch_ptr[dev].store(ptr, std::memory_order_release);     // (two host threads racing here store the same address)
+    }
+    return verify_impl(q, k, v, k_cmp, v_cmp, gates, seq_lens, n_cmp, n_query, tree_parents, p, out, sel_idx, ptr,
+                       (size_t)SSV_STATIC_SCRATCH_BYTES, stream, nullptr, 1, false);
+}
+
 int ssv_nsa_verify_timed(const void* q, const void* k, const void* v, const void* k_cmp, const void* v_cmp,
                          const float* gates, const int32_t* seq_lens, const int32_t* n_cmp, const int32_t* n_query,
                          const int32_t* tree_parents, const ssv_nsa_params* p, void* out, int32_t* sel_idx,
@@ -612,6 +636,7 @@ const char* ssv_nsa_strerror(int code) {
         case SSV_EUNSUPPORTED: return "shape not supported by this build";
         case SSV_EWORKSPACE: return "workspace missing, misaligned or too small";
         case SSV_ELAUNCH: return "HIP launch failed";
+        case SSV_ESTATIC: return "problem needs more scratch than the static array of ssv_nsa_verify_static holds";
         default: return "unknown error";
     }
 }

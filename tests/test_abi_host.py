@@ -47,7 +47,7 @@ def test_struct_layout_matches_header():
 
 def test_error_strings():
     assert B.strerror(B.SSV_OK) == "ok"
-    for code in (B.SSV_EINVAL, B.SSV_EUNSUPPORTED, B.SSV_EWORKSPACE, B.SSV_ELAUNCH):
+    for code in (B.SSV_EINVAL, B.SSV_EUNSUPPORTED, B.SSV_EWORKSPACE, B.SSV_ELAUNCH, B.SSV_ESTATIC):
         assert B.strerror(code) and B.strerror(code) != "unknown error"
     assert B.kernel_name(0).startswith("k_stream") and B.kernel_name(99) == ""
 
@@ -149,6 +149,19 @@ def test_plan_fills_the_chip_and_respects_limits():
     # 12 queries: two balanced scan groups of 6
     pl = B.ssv_nsa_plan_query(std_params(B=32, T=12, max_seq_len=131072, max_n_cmp=8191))
     assert (pl.C, pl.n_qg, pl.C_scan, pl.n_qg_scan) == (4, 3, 6, 2)
+
+
+def test_static_scratch_entry_point_checks_before_touching_the_device():
+    fake = 4096
+    big = std_params(B=16, T=4, max_seq_len=65536, max_n_cmp=4095)
+    assert B.ssv_nsa_workspace_bytes(big) > B.SSV_STATIC_SCRATCH_BYTES
+    with pytest.raises(B.SsvError) as e:
+        B.ssv_nsa_verify_static(fake, fake, fake, fake, fake, fake, fake, fake, None, None, big, fake, fake, 0)
+    assert e.value.code == B.SSV_ESTATIC and "static" in B.strerror(B.SSV_ESTATIC)
+    with pytest.raises(B.SsvError) as e:      # parameter errors come first, as in the other entry points
+        B.ssv_nsa_verify_static(fake, fake, fake, fake, fake, fake, fake, fake, None, None, std_params(H=63), fake, fake, 0)
+    assert e.value.code == B.SSV_EINVAL
+    assert 0 < B.ssv_nsa_workspace_bytes(std_params()) <= B.SSV_STATIC_SCRATCH_BYTES      # the 32K single-sequence shape fits
 
 
 def test_plan_reflects_the_execution_choices():
