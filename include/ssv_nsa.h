@@ -120,8 +120,10 @@ typedef struct ssv_nsa_params {
                              scan_group_size must be 0 or 1 there) */
     int32_t topn_home;    /* SSV_TOPN_AUTO, SSV_TOPN_SEPARATE or SSV_TOPN_IN_SLC; never changes the result */
     int32_t max_slice_tiles; /* upper bound on the 64-row tiles one workgroup streams when a launch needs several
-                             rounds of workgroups (2..64; 0 = automatic: 24); never changes the result */
-    int32_t reserved;     /* must be 0 */
+                             rounds of workgroups (2..64; 0 = automatic: 32); never changes the result */
+    int32_t imp_rows;     /* rows (routed queries x heads of a group) per workgroup in the importance pass of a refresh
+                             call: 64, 128 or 256; 0 = automatic (more than 64 where a KV head has that many rows and
+                             the pass runs for several tiles per workgroup); never changes the result */
 } ssv_nsa_params;
 
 /* How one call is cut into workgroups (host-side planning; filled by ssv_nsa_plan). */
@@ -143,6 +145,7 @@ typedef struct ssv_nsa_plan {
     int32_t n_qg_scan;        /* such groups per (sequence, KV head) */
     int32_t topn_in_slc;      /* refresh: 1 if the top-n selection runs inside the selected-branch launch, else 0 */
     int32_t n_imp_chunks;     /* refresh: workgroups splitting the importance pass over k_cmp of one query group */
+    int32_t imp_rows;         /* refresh: rows per workgroup in the importance pass (64, 128 or 256) */
     int32_t n_launches;       /* kernel launches of one call */
     int64_t workspace_bytes;
 } ssv_nsa_plan;

@@ -35,65 +35,78 @@ __device__ __forceinline__ int64_t out_row_offset(const CombineArgs& a, int64_t 
     return b * a.out_s[0] + i * a.out_s[1] + h * a.out_s[2];
 }
 
-constexpr int kMaxSlotsPerBranch = 64;
+constexpr int kMaxSlotsPerBranch = 64;      // compressed scan; the other two branches: 32 each
+constexpr int kMaxSlotsTotal = kMaxSlotsPerBranch + 32 + 32;
 
-template <bool BF16, int DV>
+constexpr int kCombineRowsMaxSlots = 16;   // slices per row up to which a thread group owns a row (k_combine_rows)
+
+// EAGER: every load is issued at once (one memory round trip: small, latency-bound calls); otherwise the statistics
+// come first and only the accumulators of slices that contributed are fetched (large calls are bound by the bytes
+// of the partial states, and a short sequence of a mixed batch leaves most of its slices empty).
+template <bool BF16, int DV, bool EAGER>
 __global__ void __launch_bounds__(kThreads) k_combine_rows(const CombineArgs a) {
     constexpr int TPR = DV / 4;                 // threads across one row, 4 columns each
     constexpr int RPW = kThreads / TPR;         // rows per workgroup
+    constexpr int MS = kCombineRowsMaxSlots;
     const int tid = threadIdx.x;
     const int64_t row = (int64_t)blockIdx.x * RPW + tid / TPR;
     if (row >= a.rows_total) return;
     const int c = tid % TPR;
     const int i = (int)((row / a.H) % a.T);
     const int b = (int)(row / ((int64_t)a.H * a.T));
+    // slot ranges: cmp [0, n_cmp), win [n_cmp, n_cmp + n_win), slc after; gate order: cmp, slc, win
+    const int lo3[3] = {0, a.n_cmp_chunks + a.n_win_splits, a.n_cmp_chunks};
+    const int cnt3[3] = {a.n_cmp_chunks, a.n_slc_splits, a.n_win_splits};
+    // the slots this launch reads: all of them, or one branch's (the host keeps either count within MS)
+    const bool one_branch = a.br_hi - a.br_lo == 1;
+    const int base = one_branch ? (a.br_lo == 0 ? lo3[0] : (a.br_lo == 1 ? lo3[1] : lo3[2])) : 0;
+    const int n_read = one_branch ? (a.br_lo == 0 ? cnt3[0] : (a.br_lo == 1 ? cnt3[1] : cnt3[2]))
+                                  : a.n_cmp_chunks + a.n_win_splits + a.n_slc_splits;
+
+    // Everything this thread needs is fetched in one round of independent loads (EAGER: slices that contributed
+    // nothing never wrote their accumulator; whatever is read there is discarded by its zero weight), so the kernel
+    // costs one memory round trip, or two, instead of one per batch of slices.
+    float2 st[MS];
+    f32x4 v[MS];
+#pragma unroll
+    for (int s = 0; s < MS; ++s) {
+        st[s] = make_float2(0.f, 0.f);
+        v[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (s < n_read) {              // uniform
+            const int64_t pr = (int64_t)(base + s) * a.rows_total + row;
+            st[s] = *reinterpret_cast<const float2*>(a.part_stats + pr * 2);
+            if constexpr (EAGER) v[s] = *reinterpret_cast<const f32x4*>(a.part_acc + pr * DV + c * 4);
+        }
+    }
+    if constexpr (!EAGER) {
+#pragma unroll
+        for (int s = 0; s < MS; ++s)
+            if (s < n_read && st[s].y > 0.f)
+                v[s] = *reinterpret_cast<const f32x4*>(a.part_acc + ((int64_t)(base + s) * a.rows_total + row) * DV + c * 4);
+    }
+    const float g3[3] = {a.gates[row * 3 + 0], a.gates[row * 3 + 1], a.gates[row * 3 + 2]};
     const int Tq = a.n_query ? min(max(a.n_query[b], 0), a.T) : a.T;
 
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     if (i < Tq) {
-        // slot ranges: cmp [0, n_cmp), win [n_cmp, n_cmp + n_win), slc after; gate order: cmp, slc, win
-        const int lo3[3] = {0, a.n_cmp_chunks + a.n_win_splits, a.n_cmp_chunks};
-        const int cnt3[3] = {a.n_cmp_chunks, a.n_slc_splits, a.n_win_splits};
 #pragma unroll
         for (int br = 0; br < 3; ++br) {
             if (br < a.br_lo || br >= a.br_hi) continue;
-            const int lo = lo3[br], cnt = cnt3[br];
-            const float* st_base = a.part_stats + ((int64_t)lo * a.rows_total + row) * 2;
-            // branch maximum and total, one pass with a running maximum (slices that saw no key have Z = 0)
-            float M = -INFINITY, Zt = 0.f;
-            for (int s0 = 0; s0 < cnt; s0 += 4) {
-                float2 st[4];
+            const int lo = lo3[br] - base, hi = lo + cnt3[br];      // in units of the slots read
+            // branch maximum and total (slices that saw no key have Z = 0)
+            float M = -INFINITY;
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    st[u] = *reinterpret_cast<const float2*>(st_base + (int64_t)min(s0 + u, cnt - 1) * a.rows_total * 2);
+            for (int s = 0; s < MS; ++s)
+                if (s >= lo && s < hi && s < n_read && st[s].y > 0.f) M = fmaxf(M, st[s].x);
+            float Zt = 0.f;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (s0 + u < cnt && st[u].y > 0.f) {
-                        const float Mn = fmaxf(M, st[u].x);
-                        Zt = Zt * fast_exp2(M - Mn) + st[u].y * fast_exp2(st[u].x - Mn);
-                        M = Mn;
-                    }
-                }
-            }
+            for (int s = 0; s < MS; ++s)
+                if (s >= lo && s < hi && s < n_read && st[s].y > 0.f) Zt += st[s].y * fast_exp2(st[s].x - M);
             if (!(Zt > 0.f)) continue;
-            const float scale = (a.use_gates ? a.gates[row * 3 + br] : 1.f) / Zt;
-            for (int s0 = 0; s0 < cnt; s0 += 4) {
-                float w[4];
-                f32x4 v[4];
+            const float scale = (a.use_gates ? g3[br] : 1.f) / Zt;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int s = min(s0 + u, cnt - 1);
-                    const float2 st = *reinterpret_cast<const float2*>(st_base + (int64_t)s * a.rows_total * 2);
-                    w[u] = (s0 + u < cnt && st.y > 0.f) ? scale * fast_exp2(st.x - M) : 0.f;
-                    // slices that contributed nothing never wrote their accumulator: read slice 0's memory instead
-                    // (always mapped) and discard it, so that the load stays unconditional
-                    const int64_t pr = (int64_t)(w[u] != 0.f ? lo + s : 0) * a.rows_total + row;
-                    v[u] = *reinterpret_cast<const f32x4*>(a.part_acc + pr * DV + c * 4);
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (w[u] != 0.f) acc += w[u] * v[u];
-            }
+            for (int s = 0; s < MS; ++s)
+                if (s >= lo && s < hi && s < n_read && st[s].y > 0.f) acc += (scale * fast_exp2(st[s].x - M)) * v[s];
         }
     }
     if constexpr (BF16) {
@@ -121,7 +134,7 @@ template <bool BF16, int DV>
 __global__ void __launch_bounds__(kThreads) k_combine_slices(const CombineArgs a) {
     constexpr int TPR = DV / 4;                 // threads across one row, 4 columns each
     constexpr int SL = kThreads / TPR;          // slices accumulated in parallel
-    __shared__ float s_w[3 * kMaxSlotsPerBranch];
+    __shared__ float s_w[kMaxSlotsTotal];
     __shared__ f32x4 s_red[SL][TPR];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t row = blockIdx.x;
@@ -131,6 +144,16 @@ __global__ void __launch_bounds__(kThreads) k_combine_slices(const CombineArgs a
     const int n_slots = a.n_cmp_chunks + a.n_win_splits + a.n_slc_splits;
     const int c = tid % TPR, sl = tid / TPR;
 
+    // this thread's accumulator loads (slices sl, sl + SL, ...), all issued before the weights exist: they are
+    // independent of them, and whatever a slice that contributed nothing left in memory meets a zero weight
+    constexpr int ML = (kMaxSlotsTotal + SL - 1) / SL;      // loads per thread, at most
+    f32x4 v[ML];
+#pragma unroll
+    for (int u = 0; u < ML; ++u) {
+        const int s = min(sl + u * SL, n_slots - 1);
+        if (u * SL < n_slots)          // uniform
+            v[u] = *reinterpret_cast<const f32x4*>(a.part_acc + ((int64_t)s * a.rows_total + row) * DV + c * 4);
+    }
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     if (i < Tq) {     // uniform per workgroup
         if (wave < 3) {
@@ -149,21 +172,13 @@ __global__ void __launch_bounds__(kThreads) k_combine_slices(const CombineArgs a
             if (lane < cnt) s_w[lo + lane] = Zt > 0.f ? gate * e / Zt : 0.f;
         }
         __syncthreads();
-        for (int s0 = sl; s0 < n_slots; s0 += 4 * SL) {
-            float w[4];
-            f32x4 v[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int s = s0 + u * SL;
-                w[u] = s < n_slots ? s_w[s] : 0.f;
-                // slices that contributed nothing never wrote their accumulator: read slice 0's memory instead
-                // (always mapped) and discard it, so that the load stays unconditional
-                const int64_t pr = (int64_t)(w[u] != 0.f ? s : 0) * a.rows_total + row;
-                v[u] = *reinterpret_cast<const f32x4*>(a.part_acc + pr * DV + c * 4);
+        for (int u = 0; u < ML; ++u) {
+            const int s = sl + u * SL;
+            if (u * SL < n_slots) {    // uniform
+                const float w = s < n_slots ? s_w[s] : 0.f;
+                if (w != 0.f) acc += w * v[u];
             }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (w[u] != 0.f) acc += w[u] * v[u];
         }
     }
     s_red[sl][c] = acc;

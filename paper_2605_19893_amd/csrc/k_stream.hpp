@@ -130,6 +130,25 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
     const bool r_win = (ROLES & 2) && role == ROLE_WIN;
     const bool r_slc = (ROLES & 4) && role == ROLE_SLC;
 
+    // ---- query fragments (B operand of S^T = K Q^T), kept in registers for the whole slice.  Their addresses need
+    //      nothing from the sequence's metadata, so the loads go first and overlap the latency of everything below
+    //      (rows past the sequence's query count exist in the buffer; their fragments are zeroed once the count is known)
+    //      (two row tiles per wave: the registers do not allow it; those launches are long, the loads follow the metadata)
+    u32x4 qf[NRT][KCH];
+    if constexpr (NRT == 1) {
+        const int rr = wave * 16 + n;
+        const int qi = min(qg * a.C + rr / a.H_g, a.T - 1);
+        const char* qp = a.q + b * a.q_s[0] + qi * a.q_s[1] + (g * a.H_g + rr % a.H_g) * a.q_s[2] + G * 16;
+#pragma unroll
+        for (int kc = 0; kc < KCH; ++kc) qf[0][kc] = *reinterpret_cast<const u32x4*>(qp + kc * 64);
+    }
+    // (reuse mode, selected branch) this thread's first entry of the group's index sets, fetched early for the same reason
+    int pre_id = -1;
+    if constexpr (ROLES & 4) {
+        if (r_slc && !a.fused_topn && tid < a.C * a.n_sel && qg * a.C + tid / a.n_sel < a.T)
+            pre_id = a.sel_idx[(((int64_t)b * a.T + qg * a.C + tid / a.n_sel) * a.H_kv + g) * a.n_sel + tid % a.n_sel];
+    }
+
     const SeqMeta sm = build_tree_meta(tid, b, a.T, a.seq_lens, a.n_query, a.n_cmp, a.parents, a.l, a.d, a.max_seq_len, a.max_n_cmp, s_par, s_depth,
                                        s_cmax,
                                        s_anc);
@@ -141,7 +160,7 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
     bool rvalid[NRT];
     AncSet anc[NRT];
     int pos[NRT], cmax[NRT], iq[NRT];
-    int64_t grow[NRT], qoff[NRT];
+    int64_t grow[NRT];
 #pragma unroll
     for (int t = 0; t < NRT; ++t) {
         const int rr = (wave + 4 * t) * 16 + n;
@@ -153,7 +172,6 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
         pos[t] = L + s_depth[qs];
         cmax[t] = rvalid[t] ? s_cmax[qs] : 0;
         grow[t] = ((int64_t)b * a.T + qs) * a.H + g * a.H_g + rr % a.H_g;
-        qoff[t] = b * a.q_s[0] + qs * a.q_s[1] + (g * a.H_g + rr % a.H_g) * a.q_s[2];
     }
 
     // ---- fused top-n selection (Section 5.1: routing, then attention over the selected blocks)
@@ -207,7 +225,7 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
             const int n_ent = nq_grp * a.n_sel;
             for (int i = tid; i < n_ent; i += kThreads) {
                 const int j = i / a.n_sel, e = i % a.n_sel;
-                const int id = s_sel ? s_sel[i] : a.sel_idx[(((int64_t)b * a.T + qg * a.C + j) * a.H_kv + g) * a.n_sel + e];
+                const int id = s_sel ? s_sel[i] : (i < kThreads ? pre_id : a.sel_idx[(((int64_t)b * a.T + qg * a.C + j) * a.H_kv + g) * a.n_sel + e]);
                 if (id >= 0 && id < nblk) atomicOr(&s_bitmap[id >> 5], 1u << (id & 31));
             }
             __syncthreads();
@@ -229,7 +247,7 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
             __syncthreads();
             for (int i = tid; i < n_ent; i += kThreads) {
                 const int j = i / a.n_sel, e = i % a.n_sel;
-                const int id = s_sel ? s_sel[i] : a.sel_idx[(((int64_t)b * a.T + qg * a.C + j) * a.H_kv + g) * a.n_sel + e];
+                const int id = s_sel ? s_sel[i] : (i < kThreads ? pre_id : a.sel_idx[(((int64_t)b * a.T + qg * a.C + j) * a.H_kv + g) * a.n_sel + e]);
                 if (id >= 0 && id < nblk) {
                     const uint32_t wd = s_bitmap[id >> 5];
                     const int rank = s_prefix[id >> 5] + __popc(wd & ((1u << (id & 31)) - 1u));
@@ -243,16 +261,22 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
         }
     }
 
-    // ---- query fragments (B operand of S^T = K Q^T), kept in registers for the whole slice
-    u32x4 qf[NRT][KCH];
+    // ---- fragments of rows that do not exist are zero (nothing of theirs is ever written; zero keeps their
+    //      scores finite)
 #pragma unroll
-    for (int t = 0; t < NRT; ++t)
+    for (int t = 0; t < NRT; ++t) {
+        if constexpr (NRT > 1) {
+            const int64_t qoff = b * a.q_s[0] + (qg * a.C + iq[t]) * a.q_s[1] + (g * a.H_g + ((wave + 4 * t) * 16 + n) % a.H_g) * a.q_s[2];
 #pragma unroll
-        for (int kc = 0; kc < KCH; ++kc) {
-            qf[t][kc] = u32x4{0, 0, 0, 0};
-            if (rvalid[t] && t0 < t1)
-                qf[t][kc] = *reinterpret_cast<const u32x4*>(a.q + qoff[t] + kc * 64 + G * 16);
+            for (int kc = 0; kc < KCH; ++kc) {
+                qf[t][kc] = u32x4{0, 0, 0, 0};
+                if (rvalid[t]) qf[t][kc] = *reinterpret_cast<const u32x4*>(a.q + qoff + kc * 64 + G * 16);
+            }
+        } else if (!rvalid[t]) {
+#pragma unroll
+            for (int kc = 0; kc < KCH; ++kc) qf[t][kc] = u32x4{0, 0, 0, 0};
         }
+    }
 
     f32x4 acc[NRT][MT];
     float mrun[NRT], zrun[NRT];

@@ -33,17 +33,17 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Planning constants (measured choices; none is read from the environment).
 constexpr int kResidentWgs = 256 * 2;        // workgroups one round holds: LDS and registers allow two per CU
 constexpr int kMinTilesPerSlice = 2;
-constexpr int kLongSliceTiles = 24;          // slice length once a launch needs several rounds (max_slice_tiles = 0)
+constexpr int kMinTilesMultiRound = 4;       // launches of several rounds: slices of a short sequence hold at least this many tiles
+constexpr int kLongSliceTiles = 32;          // slice length once a launch needs several rounds (max_slice_tiles = 0)
 constexpr int kImportanceWgs = 512;          // one round of the importance pass (more, shorter workgroups measured slower)
 constexpr int kTopnInSlcMaxWgs = 256;        // SSV_TOPN_AUTO: select inside the selected-branch launch up to this many workgroups
-constexpr int kCombineRowsMaxSlots = 12;     // up to this many slices per row a thread group owns a row in the combine kernel
 constexpr size_t kMaxStreamLds = 80 * 1024;  // two workgroups per CU
 
 struct Layout {
     ssv_nsa_plan plan;
     int H_g, es;
     bool one_launch, unfused;
-    int imp_C, imp_n_qg, n_imp_chunks;   // importance pass: routed queries per workgroup, such workgroups per sequence, slices
+    int imp_C, imp_n_qg, n_imp_chunks, imp_rw;   // importance pass: routed queries per workgroup, such workgroups per sequence, slices, blocks of 64 rows per workgroup
     int nc_pitch, max_blocks, bitmap_words, max_sched;
     size_t lds_stream, lds_k, lds_vt;
     int64_t rows_total;
@@ -71,7 +71,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     if (p->exec != SSV_EXEC_FUSED && p->exec != SSV_EXEC_UNFUSED) return SSV_EINVAL;
     if (p->topn_home != SSV_TOPN_AUTO && p->topn_home != SSV_TOPN_SEPARATE && p->topn_home != SSV_TOPN_IN_SLC) return SSV_EINVAL;
     if (p->max_slice_tiles != 0 && (p->max_slice_tiles < 2 || p->max_slice_tiles > 64)) return SSV_EINVAL;
-    if (p->reserved != 0) return SSV_EINVAL;
+    if (p->imp_rows != 0 && p->imp_rows != 64 && p->imp_rows != 128 && p->imp_rows != 256) return SSV_EINVAL;
     const bool unfused = p->exec == SSV_EXEC_UNFUSED;
     if (unfused && (p->mode == SSV_REFRESH_SHARED || p->group_size > 1 || p->scan_group_size > 1)) return SSV_EINVAL;
     const int H_g = p->H / p->H_kv;
@@ -189,24 +189,39 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
         per_c = per_w = tiles_per_slice(tiles_a, 2, units_scan);
         per_s = tiles_per_slice(&nts, 1, units);
     }
-    pl.n_cmp_chunks = std::min(std::max(1, ceil_div(ntc, per_c)), kMaxSlotsPerBranch);   // keeps the per-row slice loops of the combine kernel short
-    pl.n_win_splits = std::min(std::max(1, ceil_div(ntw, per_w)), 32);
-    pl.n_slc_splits = std::min(std::max(1, ceil_div(nts, per_s)), 32);
+    // (caps: the combine kernel's per-row slice loops; unfused: every branch is merged by thread groups that own rows)
+    const int cap_c = unfused ? kCombineRowsMaxSlots : kMaxSlotsPerBranch, cap_ws = unfused ? kCombineRowsMaxSlots : 32;
+    pl.n_cmp_chunks = std::min(std::max(1, ceil_div(ntc, per_c)), cap_c);
+    pl.n_win_splits = std::min(std::max(1, ceil_div(ntw, per_w)), cap_ws);
+    pl.n_slc_splits = std::min(std::max(1, ceil_div(nts, per_s)), cap_ws);
     pl.tiles_per_chunk = ceil_div(ntc, pl.n_cmp_chunks);
     pl.n_slots = pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits;
 
     lo->H_g = H_g;
     // importance pass: every query is routed, or one representative per group of C (shared-index variant), then
-    // packed 64 rows to a workgroup; 2 workgroups per CU are resident (72 KB of LDS each for the K strips in
-    // flight): one round of at most 512 (more, shorter workgroups measured slower: every workgroup pays about 10 us
-    // of start-up before its first tile)
-    if (shared) {
-        const int routed = ceil_div(p->T, pl.share_group);
-        lo->imp_C = std::max(1, std::min(routed, 64 / H_g));
+    // packed 64, 128 or 256 rows to a workgroup; 2 workgroups per CU are resident (72 KB of LDS each for the K strips
+    // in flight): one round of at most 512 (more, shorter workgroups measured slower: every workgroup pays about
+    // 10 us of start-up before its first tile).  With 64 rows per workgroup every workgroup streams its whole slice
+    // of k_cmp from L2 for those 64 rows, which is what bounds the pass once a KV head has several hundred rows;
+    // wider workgroups share every strip between 2 or 4 row blocks.  Small problems keep 64 rows: more workgroups,
+    // each with one or two tiles.
+    const int routed = shared ? ceil_div(p->T, pl.share_group) : p->T;
+    const int rows_routed = routed * H_g;
+    // (an explicit group_size, like the unfused execution, also sets the queries per workgroup of this pass, so that
+    // per-query execution is per-query throughout)
+    const bool own_groups = !shared && (p->group_size || unfused);
+    int rw = 1;
+    if (p->imp_rows) rw = p->imp_rows / 64;
+    else if (!own_groups && (int64_t)p->B * p->H_kv * ceil_div(rows_routed, 64) * ntc_avg >= 4 * (int64_t)kImportanceWgs)
+        rw = rows_routed >= 256 ? 4 : (rows_routed >= 128 ? 2 : 1);
+    while (rw > 1 && rows_routed <= 64 * (rw / 2)) rw /= 2;         // no more row blocks than the rows fill
+    lo->imp_rw = rw;
+    {
+        int c_cap = std::max(1, 64 * rw / H_g);                         // queries one workgroup can hold
+        if (own_groups && !p->imp_rows) c_cap = std::min(c_cap, pl.C);
+        const int n_g = ceil_div(routed, c_cap);
+        lo->imp_C = ceil_div(routed, n_g);                              // balanced over the groups
         lo->imp_n_qg = ceil_div(routed, lo->imp_C);
-    } else {
-        lo->imp_C = std::min(pl.C, std::max(1, 64 / H_g));
-        lo->imp_n_qg = ceil_div(p->T, lo->imp_C);
     }
     const int imp_units = p->B * p->H_kv * lo->imp_n_qg;
     lo->n_imp_chunks = std::max(1, std::min(ntc, std::max(1, kImportanceWgs / imp_units)));
@@ -230,6 +245,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     pl.topn_in_slc = refresh && !unfused && fits &&
                      (p->topn_home == SSV_TOPN_IN_SLC || (p->topn_home == SSV_TOPN_AUTO && n_wg_b <= kTopnInSlcMaxWgs));
     pl.n_imp_chunks = refresh ? lo->n_imp_chunks : 0;
+    pl.imp_rows = refresh ? 64 * lo->imp_rw : 0;
     if (unfused) pl.n_launches = refresh ? 9 : 7;
     else pl.n_launches = (lo->one_launch ? 1 : 2) + (refresh ? 1 + !pl.topn_in_slc : 0) + 1;
     lo->rows_total = (int64_t)p->B * p->T * p->H;
@@ -247,6 +263,23 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     pl.workspace_bytes = (int64_t)off;
     return SSV_OK;
 }
+
+// The importance kernel of a shape: bf16 on the 32x32x16 matrix instruction, fp32 on 16x16x4; by heads-per-group class
+// (16, 4, 1) and blocks of 64 rows per workgroup (1, 2, 4).
+template <bool BF16, int DK>
+struct ImportanceKernels {
+    static constexpr size_t LDS = BF16 ? (size_t)Importance32Cfg<DK>::LDS_RING : (size_t)ImportanceCfg<false, DK>::LDS_RING;
+    template <int HGM, int RW>
+    static const void* one() {
+        if constexpr (BF16) return (const void*)k_importance32<DK, HGM, RW>;
+        else return (const void*)k_importance<false, DK, HGM, RW>;
+    }
+    static const void* fn(int hgm, int rw) {
+#define SSV_IMP_ROW(HGM_) (rw == 4 ? one<HGM_, 4>() : (rw == 2 ? one<HGM_, 2>() : one<HGM_, 1>()))
+        return hgm == 16 ? SSV_IMP_ROW(16) : (hgm == 4 ? SSV_IMP_ROW(4) : SSV_IMP_ROW(1));
+#undef SSV_IMP_ROW
+    }
+};
 
 struct Timer {
     bool on = false;
@@ -300,7 +333,6 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
                const ssv_nsa_params* p, void* out, int32_t* sel_idx, char* ws, const Layout& lo, hipStream_t stream,
                Timer& tm) {
     using SC = StreamCfg<BF16, DK, DV>;
-    using IC = ImportanceCfg<BF16, DK>;
     static_assert(SC::LDS_K == 2 * kTile * DK * (BF16 ? 2 : 4), "stream_tile_lds must describe this shape");
     const ssv_nsa_plan& pl = lo.plan;
     const int es = lo.es;
@@ -319,7 +351,8 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     sa.l = p->l; sa.d = p->d; sa.n_sel = p->n_sel; sa.w = p->w; sa.scale_log2 = scale_log2;
     sa.max_seq_len = p->max_seq_len; sa.max_n_cmp = p->max_n_cmp;
     sa.n_cmp_chunks = pl.n_cmp_chunks; sa.n_win_splits = pl.n_win_splits; sa.n_slc_splits = pl.n_slc_splits;
-    sa.min_tiles = 1;     // inside a launch the used slices share the tiles evenly, down to one tile each
+    sa.min_tiles = 1;     // inside a launch the used slices share the tiles evenly, down to one tile each (launch_stream
+                          // raises this for launches of several rounds)
     sa.max_sched = lo.max_sched; sa.bitmap_words = lo.bitmap_words; sa.rows_total = lo.rows_total;
     for (int j = 0; j < 3; ++j) {
         sa.k_s[j] = p->k_stride[j] * es; sa.v_s[j] = p->v_stride[j] * es;
@@ -338,8 +371,9 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
                                  (const void*)k_stream<BF16, DK, DV, 1, kRolesCmpWin>, (const void*)k_stream<BF16, DK, DV, 2, kRolesAll>,
                                  (const void*)k_stream<BF16, DK, DV, 2, kRolesSlc>, (const void*)k_stream<BF16, DK, DV, 2, kRolesCmpWin>,
                                  (const void*)k_stream<BF16, DK, DV, 1, kRolesCmp>, (const void*)k_stream<BF16, DK, DV, 1, kRolesWin>,
-                                 (const void*)k_importance<BF16, DK, 16>, (const void*)k_importance<BF16, DK, 4>,
-                                 (const void*)k_importance<BF16, DK, 1>};
+                                 ImportanceKernels<BF16, DK>::fn(16, 1), ImportanceKernels<BF16, DK>::fn(4, 1), ImportanceKernels<BF16, DK>::fn(1, 1),
+                                 ImportanceKernels<BF16, DK>::fn(16, 2), ImportanceKernels<BF16, DK>::fn(4, 2), ImportanceKernels<BF16, DK>::fn(1, 2),
+                                 ImportanceKernels<BF16, DK>::fn(16, 4), ImportanceKernels<BF16, DK>::fn(4, 4), ImportanceKernels<BF16, DK>::fn(1, 4)};
             for (const void* fn : fns)
                 if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStreamLds) != hipSuccess) return SSV_ELAUNCH;
             raised[dev].store(true, std::memory_order_release);
@@ -351,6 +385,9 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     auto launch_stream = [&](int K, int roles, int slot_lo, int slot_cnt, int C, int n_qg) -> int {
         sa.C = C; sa.n_qg = n_qg;
         sa.slot_lo = slot_lo; sa.slot_cnt = slot_cnt; sa.n_wg = p->B * p->H_kv * n_qg * slot_cnt;
+        // A launch of several rounds of workgroups gains nothing from cutting a short sequence into slices of one
+        // or two tiles: every slice pays the start-up of a workgroup and leaves a partial state to merge.
+        sa.min_tiles = sa.n_wg > kResidentWgs ? kMinTilesMultiRound : 1;
         const int grid = ceil_div(sa.n_wg, 8) * 8;
         if (tm.begin(K)) return -1;
         for (int r = 0; r < reps; ++r) {
@@ -385,11 +422,9 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         for (int j = 0; j < 3; ++j) { ia.kc_s[j] = sa.kc_s[j]; ia.q_s[j] = lo.q_s[j]; }
         const int grid_i = ceil_div(ia.n_wg, 8) * 8;
         if (tm.begin(SSV_K_IMPORTANCE)) return -1;
-        for (int r = 0; r < reps; ++r) {
-            if (lo.H_g == 16) SSV_LAUNCH(SSV_K_IMPORTANCE, (k_importance<BF16, DK, 16>), grid_i, IC::LDS_RING, ia);
-            else if (lo.H_g >= 4) SSV_LAUNCH(SSV_K_IMPORTANCE, (k_importance<BF16, DK, 4>), grid_i, IC::LDS_RING, ia);
-            else SSV_LAUNCH(SSV_K_IMPORTANCE, (k_importance<BF16, DK, 1>), grid_i, IC::LDS_RING, ia);
-        }
+        using IK = ImportanceKernels<BF16, DK>;
+        const auto imp_kernel = reinterpret_cast<void (*)(ImportanceArgs)>(const_cast<void*>(IK::fn(lo.H_g == 16 ? 16 : (lo.H_g >= 4 ? 4 : 1), lo.imp_rw)));
+        for (int r = 0; r < reps; ++r) SSV_LAUNCH(SSV_K_IMPORTANCE, imp_kernel, grid_i, IK::LDS, ia);
         if (hipGetLastError() != hipSuccess || tm.end(SSV_K_IMPORTANCE)) return -1;
 
         sa.colsum = colsum; sa.sel_out = sel_idx; sa.nc_pitch = lo.nc_pitch; sa.l_sel = p->l_sel; sa.n_init = p->n_init;
@@ -436,7 +471,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
             ba.out_s[0] = (int64_t)p->T * p->H * DV * es; ba.out_s[1] = (int64_t)p->H * DV * es; ba.out_s[2] = (int64_t)DV * es;
             ba.br_lo = br; ba.br_hi = br + 1; ba.use_gates = 0;
             if (tm.begin(K)) return -1;
-            for (int r = 0; r < reps; ++r) SSV_LAUNCH(K, (k_combine_rows<BF16, DV>), grid_rows, 0, ba);
+            for (int r = 0; r < reps; ++r) SSV_LAUNCH(K, (k_combine_rows<BF16, DV, true>), grid_rows, 0, ba);
             return (hipGetLastError() == hipSuccess && !tm.end(K)) ? 0 : -1;
         };
         if (launch_stream(SSV_K_STREAM_A, kRolesCmp, 0, pl.n_cmp_chunks, 1, p->T) || branch_out(SSV_K_OUT_CMP, 0)) return SSV_ELAUNCH;
@@ -463,9 +498,12 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     }
     // few slices per row: thread groups own rows; many slices: one workgroup per row, slices in parallel
     const bool by_rows = pl.n_slots <= kCombineRowsMaxSlots;
+    // partial states beyond the last-level cache: fetch statistics first, then only the accumulators that count
+    const bool eager = (int64_t)pl.n_slots * lo.rows_total * (DV + 2) * 4 <= (int64_t)64 << 20;
     if (tm.begin(SSV_K_COMBINE)) return SSV_ELAUNCH;
     for (int r = 0; r < reps; ++r) {
-        if (by_rows) SSV_LAUNCH(SSV_K_COMBINE, (k_combine_rows<BF16, DV>), grid_rows, 0, ca);
+        if (by_rows && eager) SSV_LAUNCH(SSV_K_COMBINE, (k_combine_rows<BF16, DV, true>), grid_rows, 0, ca);
+        else if (by_rows) SSV_LAUNCH(SSV_K_COMBINE, (k_combine_rows<BF16, DV, false>), grid_rows, 0, ca);
         else SSV_LAUNCH(SSV_K_COMBINE, (k_combine_slices<BF16, DV>), (int)lo.rows_total, 0, ca);
     }
     if (hipGetLastError() != hipSuccess || tm.end(SSV_K_COMBINE)) return SSV_ELAUNCH;

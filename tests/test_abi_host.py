@@ -32,9 +32,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    # 21 four-byte fields (+ 4 bytes of padding), 18 int64 strides, 4 four-byte fields; 16 ints and an int64 in the plan
+    # 21 four-byte fields (+ 4 bytes of padding), 18 int64 strides, 4 four-byte fields; 17 ints (+ padding) and an int64 in the plan
     assert ctypes.sizeof(B.SsvNsaParams) == 22 * 4 + 18 * 8 + 4 * 4
-    assert ctypes.sizeof(B.SsvNsaPlan) == 16 * 4 + 8
+    assert ctypes.sizeof(B.SsvNsaPlan) == 18 * 4 + 8
     with open(os.path.join(ROOT, "include", "ssv_nsa.h")) as f:
         header = f.read()
     # every field of the two structs appears in the header in the binding's order
@@ -66,7 +66,7 @@ def test_supported_shapes():
     (dict(k_stride=(1, 1, 100)), B.SSV_EINVAL), (dict(k_stride=(4 * 32832 * 192, 32832 * 192, 196)), B.SSV_EINVAL),
     (dict(mode=B.SSV_REFRESH_SHARED, group_size=9), B.SSV_EINVAL),
     (dict(exec=2), B.SSV_EINVAL), (dict(topn_home=3), B.SSV_EINVAL), (dict(max_slice_tiles=1), B.SSV_EINVAL),
-    (dict(max_slice_tiles=65), B.SSV_EINVAL), (dict(exec=B.SSV_EXEC_UNFUSED, group_size=2), B.SSV_EINVAL),
+    (dict(max_slice_tiles=65), B.SSV_EINVAL), (dict(imp_rows=100), B.SSV_EINVAL), (dict(exec=B.SSV_EXEC_UNFUSED, group_size=2), B.SSV_EINVAL),
     (dict(exec=B.SSV_EXEC_UNFUSED, mode=B.SSV_REFRESH_SHARED), B.SSV_EINVAL),
     (dict(q_stride=(8 * 64 * 192, 64 * 192, 100)), B.SSV_EINVAL), (dict(out_stride=(8 * 64 * 128, 64 * 128, 130)), B.SSV_EINVAL),
     # the merged schedule of 32 queries x 32 blocks does not fit the LDS next to the tiles of d_k = 192
@@ -126,9 +126,9 @@ def test_plan_fills_the_chip_and_respects_limits():
         assert (pl.C_scan, pl.n_qg_scan) == {"cfg1": (4, 2), "cfg2": (4, 1), "cfg3": (8, 5), "cfg4": (8, 2)}[name]
         units = p.B * p.H_kv * pl.n_qg_scan
         wgs = units * (pl.n_cmp_chunks + pl.n_win_splits)
-        # either one resident round (at most 2 workgroups per CU) or several rounds of slices of at most 24 tiles
+        # either one resident round (at most 2 workgroups per CU) or several rounds of slices of at most 32 tiles
         assert wgs >= min(256, units * ((p.max_n_cmp + 63) // 64) // 2), (name, wgs)
-        assert wgs <= 512 or pl.tiles_per_chunk <= 24, (name, wgs)
+        assert wgs <= 512 or pl.tiles_per_chunk <= 32, (name, wgs)
         assert pl.workspace_bytes == B.ssv_nsa_workspace_bytes(p) and pl.workspace_bytes % 256 == 0
     p = std_params(group_size=2)
     pl = B.ssv_nsa_plan_query(p)
@@ -178,7 +178,15 @@ def test_plan_reflects_the_execution_choices():
     # several rounds of workgroups: the slice bound applies
     long_default = B.ssv_nsa_plan_query(std_params(B=32, T=16, max_seq_len=131072, max_n_cmp=8191))
     long_12 = B.ssv_nsa_plan_query(std_params(B=32, T=16, max_seq_len=131072, max_n_cmp=8191, max_slice_tiles=12))
-    assert long_default.tiles_per_chunk <= 24 and long_12.tiles_per_chunk <= 12 and long_12.n_cmp_chunks > long_default.n_cmp_chunks
+    assert long_default.tiles_per_chunk <= 32 and long_12.tiles_per_chunk <= 12 and long_12.n_cmp_chunks > long_default.n_cmp_chunks
+    # importance pass: 64 rows per workgroup for small problems, wider where a KV head has the rows and the pass is long
+    assert auto.imp_rows == 64 and reuse.imp_rows == 0
+    assert B.ssv_nsa_plan_query(std_params(B=4, T=40, max_seq_len=131072, max_n_cmp=8191)).imp_rows == 256
+    assert B.ssv_nsa_plan_query(std_params(B=32, T=16, max_seq_len=131072, max_n_cmp=8191)).imp_rows == 256
+    assert B.ssv_nsa_plan_query(std_params(B=32, T=8, max_seq_len=131072, max_n_cmp=8191)).imp_rows == 128
+    assert B.ssv_nsa_plan_query(std_params(B=16, T=4, max_seq_len=65536, max_n_cmp=4095)).imp_rows == 64
+    assert B.ssv_nsa_plan_query(std_params(imp_rows=256)).imp_rows == 128      # 8 queries x 16 heads fill two blocks
+    assert B.ssv_nsa_plan_query(std_params(B=4, T=40, max_seq_len=131072, max_n_cmp=8191, imp_rows=64)).imp_rows == 64
     # unfused execution: every query on its own, one launch per branch plus their merges and the gate kernel
     un = B.ssv_nsa_plan_query(std_params(exec=B.SSV_EXEC_UNFUSED))
     assert (un.C, un.n_qg, un.C_scan, un.n_qg_scan, un.topn_in_slc, un.n_launches) == (1, 8, 1, 8, 0, 9)

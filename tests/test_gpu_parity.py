@@ -472,3 +472,30 @@ def test_strided_queries_and_output(dev_mod, oracle, exec_name):
     dev.run()
     out2, sel2 = dev.results()
     check(case, compare(case, oracle, ref, out2, sel2))
+
+
+@pytest.mark.parametrize("imp_rows", [128, 256])
+def test_wide_importance_pass(dev_mod, oracle, imp_rows):
+    """The importance pass with 128 or 256 rows per workgroup (row blocks of one workgroup share every strip of
+    k_cmp through the ring in LDS) selects exactly what the 64-row pass selects: chains with ragged query counts and
+    several tiles per slice, a tree, every heads-per-group class, the shared-index variant, fp32."""
+    from paper_2605_19893_amd import binding as B
+    cases = [
+        si.make_case("wide_imp_chain", "bf16", 2, 19, 64, 4, 192, 128, si.STD_NSA, [9000, 2300], 501, rho=0.6, n_query=[19, 11],
+                     poison_pad=True),
+        si.make_case("wide_imp_tree", "bf16", 2, len(si.tree_parents((4, 3, 2), "bfs")), 32, 2, 192, 128, si.STD_NSA, [4100, 12000], 503,
+                     rho=0.6, parents=si.tree_parents((4, 3, 2), "bfs")),
+        si.make_case("wide_imp_hg4", "bf16", 1, 64, 32, 8, 64, 64, si.STD_NSA, [7000], 505, rho=0.3),
+        si.make_case("wide_imp_hg8", "bf16", 2, 30, 16, 2, 128, 128, si.STD_NSA, [3000, 5000], 507, rho=0.3, n_query=[30, 17]),
+        si.make_case("wide_imp_hg2", "bf16", 1, 100, 4, 2, 64, 64, si.STD_NSA, [2500], 509, rho=0.3),
+        si.make_case("wide_imp_hg1", "f32", 1, 128, 2, 2, 64, 64, si.STD_NSA, [1800], 511, rho=0.3),
+    ]
+    for case in cases:
+        dev, ref, out, sel = run_refresh(dev_mod, oracle, case, imp_rows=64)
+        assert dev.plan.imp_rows == 64
+        dev_w, ref, out_w, sel_w = run_refresh(dev_mod, oracle, case, imp_rows=imp_rows)
+        assert dev_w.plan.imp_rows in (128, 256) and dev_w.plan.imp_rows <= imp_rows
+        assert np.array_equal(sel_w, sel), case.name            # the same sums in the same order
+        assert np.array_equal(out_w, out), case.name
+    run_shared(dev_mod, oracle, cases[0], 2, imp_rows=imp_rows)
+    run_shared(dev_mod, oracle, cases[1], 3, imp_rows=imp_rows)
