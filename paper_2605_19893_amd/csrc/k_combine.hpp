@@ -144,16 +144,6 @@ __global__ void __launch_bounds__(kThreads) k_combine_slices(const CombineArgs a
     const int n_slots = a.n_cmp_chunks + a.n_win_splits + a.n_slc_splits;
     const int c = tid % TPR, sl = tid / TPR;
 
-    // this thread's accumulator loads (slices sl, sl + SL, ...), all issued before the weights exist: they are
-    // independent of them, and whatever a slice that contributed nothing left in memory meets a zero weight
-    constexpr int ML = (kMaxSlotsTotal + SL - 1) / SL;      // loads per thread, at most
-    f32x4 v[ML];
-#pragma unroll
-    for (int u = 0; u < ML; ++u) {
-        const int s = min(sl + u * SL, n_slots - 1);
-        if (u * SL < n_slots)          // uniform
-            v[u] = *reinterpret_cast<const f32x4*>(a.part_acc + ((int64_t)s * a.rows_total + row) * DV + c * 4);
-    }
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
     if (i < Tq) {     // uniform per workgroup
         if (wave < 3) {
@@ -172,13 +162,21 @@ __global__ void __launch_bounds__(kThreads) k_combine_slices(const CombineArgs a
             if (lane < cnt) s_w[lo + lane] = Zt > 0.f ? gate * e / Zt : 0.f;
         }
         __syncthreads();
+        for (int s0 = sl; s0 < n_slots; s0 += 4 * SL) {
+            float w[4];
+            f32x4 v[4];
 #pragma unroll
-        for (int u = 0; u < ML; ++u) {
-            const int s = sl + u * SL;
-            if (u * SL < n_slots) {    // uniform
-                const float w = s < n_slots ? s_w[s] : 0.f;
-                if (w != 0.f) acc += w * v[u];
+            for (int u = 0; u < 4; ++u) {
+                const int s = s0 + u * SL;
+                w[u] = s < n_slots ? s_w[s] : 0.f;
+                // slices that contributed nothing never wrote their accumulator: read slice 0's memory instead
+                // (always mapped) and discard it, so that the load stays unconditional
+                const int64_t pr = (int64_t)(w[u] != 0.f ? s : 0) * a.rows_total + row;
+                v[u] = *reinterpret_cast<const f32x4*>(a.part_acc + pr * DV + c * 4);
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (w[u] != 0.f) acc += w[u] * v[u];
         }
     }
     s_red[sl][c] = acc;

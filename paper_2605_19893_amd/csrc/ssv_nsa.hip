@@ -212,8 +212,11 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     const bool own_groups = !shared && (p->group_size || unfused);
     int rw = 1;
     if (p->imp_rows) rw = p->imp_rows / 64;
-    else if (!own_groups && (int64_t)p->B * p->H_kv * ceil_div(rows_routed, 64) * ntc_avg >= 4 * (int64_t)kImportanceWgs)
-        rw = rows_routed >= 256 ? 4 : (rows_routed >= 128 ? 2 : 1);
+    else if (!own_groups) {
+        // wide only where the wide workgroups still get four tiles or more each
+        for (int cand = rows_routed >= 256 ? 4 : (rows_routed >= 128 ? 2 : 1); cand > 1 && rw == 1; cand /= 2)
+            if ((int64_t)p->B * p->H_kv * ceil_div(rows_routed, 64 * cand) * ntc_avg >= 4 * (int64_t)kImportanceWgs) rw = cand;
+    }
     while (rw > 1 && rows_routed <= 64 * (rw / 2)) rw /= 2;         // no more row blocks than the rows fill
     lo->imp_rw = rw;
     {
@@ -497,7 +500,8 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         if (launch_stream(SSV_K_STREAM_B, kRolesSlc, n_scan_slots, pl.n_slc_splits, pl.C, pl.n_qg)) return SSV_ELAUNCH;
     }
     // few slices per row: thread groups own rows; many slices: one workgroup per row, slices in parallel
-    const bool by_rows = pl.n_slots <= kCombineRowsMaxSlots;
+    // (13..16 slices: thread groups only where there are rows enough to fill the chip with them)
+    const bool by_rows = pl.n_slots <= 12 || (pl.n_slots <= kCombineRowsMaxSlots && lo.rows_total >= 4096);
     // partial states beyond the last-level cache: fetch statistics first, then only the accumulators that count
     const bool eager = (int64_t)pl.n_slots * lo.rows_total * (DV + 2) * 4 <= (int64_t)64 << 20;
     if (tm.begin(SSV_K_COMBINE)) return SSV_ELAUNCH;
