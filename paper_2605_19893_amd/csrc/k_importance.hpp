@@ -581,6 +581,16 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance32(const ImportanceAr
     }
     __syncthreads();
 
+    // of the sixteen rows (8 j + 4 hb + r) this lane holds of each of its row tiles: the softmax offset (in registers:
+    // a 16-byte LDS read that all lanes of a half aim at one address is served as a bank conflict)
+    float rowMp[RTW][16];
+#pragma unroll
+    for (int t = 0; t < RTW; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float4 mp = *reinterpret_cast<const float4*>(s_mp + (rt0 + t) * 32 + 8 * j + 4 * hb);
+            rowMp[t][4 * j + 0] = mp.x; rowMp[t][4 * j + 1] = mp.y; rowMp[t][4 * j + 2] = mp.z; rowMp[t][4 * j + 3] = mp.w;
+        }
     // the colsum row and the visibility limit behind each of this lane's stores of a block (H_g >= 4: kept in
     // registers; below that a block has up to sixteen queries per lane and they are looked up at the store)
     constexpr int NQR = HGM >= 4 ? QPT : 1;
@@ -633,16 +643,8 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance32(const ImportanceAr
         const int c = tile * kTile + 32 * kt + n;
         float hs[4];                 // sums of this lane's four consecutive rows 8 j + 4 hb + 0..3
         float p[16];
-        // the softmax offsets of this lane's sixteen rows (8 j + 4 hb + r) come from LDS at every block: registers
-        // are what limits the rows a wavefront can hold
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float4 mp = *reinterpret_cast<const float4*>(s_mp + (rt0 + t) * 32 + 8 * j + 4 * hb);
-            p[4 * j + 0] = fast_exp2(__builtin_fmaf(s[4 * j + 0], a.scale_log2, -mp.x));
-            p[4 * j + 1] = fast_exp2(__builtin_fmaf(s[4 * j + 1], a.scale_log2, -mp.y));
-            p[4 * j + 2] = fast_exp2(__builtin_fmaf(s[4 * j + 2], a.scale_log2, -mp.z));
-            p[4 * j + 3] = fast_exp2(__builtin_fmaf(s[4 * j + 3], a.scale_log2, -mp.w));
-        }
+        for (int i = 0; i < 16; ++i) p[i] = fast_exp2(__builtin_fmaf(s[i], a.scale_log2, -rowMp[t][i]));
 #pragma unroll
         for (int j = 0; j < 4; ++j) hs[j] = (p[4 * j] + p[4 * j + 1]) + (p[4 * j + 2] + p[4 * j + 3]);
         if constexpr (HGM == 16) {

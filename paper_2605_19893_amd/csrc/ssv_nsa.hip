@@ -37,6 +37,7 @@ constexpr int kMinTilesMultiRound = 4;       // launches of several rounds: slic
 constexpr int kLongSliceTiles = 32;          // slice length once a launch needs several rounds (max_slice_tiles = 0)
 constexpr int kImportanceWgs = 512;          // one round of the importance pass (more, shorter workgroups measured slower)
 constexpr int kTopnInSlcMaxWgs = 256;        // SSV_TOPN_AUTO: select inside the selected-branch launch up to this many workgroups
+                                             // (twice as many when a wavefront has one query to select for)
 constexpr size_t kMaxStreamLds = 80 * 1024;  // two workgroups per CU
 
 struct Layout {
@@ -246,7 +247,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     const bool fits = fused_topn_lds_bytes(max_blocks, pl.C, p->n_sel) <= lo->lds_k + lo->lds_vt;
     const int n_wg_b = units * pl.n_slc_splits;
     pl.topn_in_slc = refresh && !unfused && fits &&
-                     (p->topn_home == SSV_TOPN_IN_SLC || (p->topn_home == SSV_TOPN_AUTO && n_wg_b <= kTopnInSlcMaxWgs));
+                     (p->topn_home == SSV_TOPN_IN_SLC || (p->topn_home == SSV_TOPN_AUTO && n_wg_b <= (pl.C <= 4 ? 2 : 1) * kTopnInSlcMaxWgs));
     pl.n_imp_chunks = refresh ? lo->n_imp_chunks : 0;
     pl.imp_rows = refresh ? 64 * lo->imp_rw : 0;
     if (unfused) pl.n_launches = refresh ? 9 : 7;

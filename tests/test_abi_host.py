@@ -169,7 +169,8 @@ def test_plan_reflects_the_execution_choices():
     assert auto.topn_in_slc == 1 and auto.n_launches == 4 and auto.n_imp_chunks >= 1      # cfg1: selection inside launch B
     sep = B.ssv_nsa_plan_query(std_params(topn_home=B.SSV_TOPN_SEPARATE))
     assert sep.topn_in_slc == 0 and sep.n_launches == 5
-    big = std_params(B=16, T=4, max_seq_len=65536, max_n_cmp=4095)
+    assert B.ssv_nsa_plan_query(std_params(B=16, T=4, max_seq_len=65536, max_n_cmp=4095)).topn_in_slc == 1   # 512 workgroups: still inside
+    big = std_params(B=32, T=16, max_seq_len=131072, max_n_cmp=8191)
     assert B.ssv_nsa_plan_query(big).topn_in_slc == 0
     big.topn_home = B.SSV_TOPN_IN_SLC
     assert B.ssv_nsa_plan_query(big).topn_in_slc == 1
