@@ -203,14 +203,16 @@ def read_traffic(tag):
     return out
 
 
-def kernel_roofs(B, work, dtype, refresh_ms):
+def kernel_roofs(B, work, dtype, refresh_ms, plan):
     """Per kernel of the refresh path: the method's bytes and flops of that launch, the time each would take at the
-    chip's peaks (HBM 8 TB/s; dense MFMA 2.5 PFLOP/s bf16), which of the two binds, and the measured fraction."""
+    chip's peaks (HBM 8 TB/s; dense MFMA 2.5 PFLOP/s bf16), which of the two binds, and the measured fraction.
+    With the matrix-core scan (plan.scan_matrix) the window branch runs in the selected-branch launch."""
     by, fl = work["bytes"], work["flops"]
+    win_in_b = bool(plan.scan_matrix)
     per_kernel = {
-        B.SSV_K_STREAM_A: (by["compressed"] + by["window_union"], fl["compressed"] + fl["window"]),
+        B.SSV_K_STREAM_A: (by["compressed"] + (0 if win_in_b else by["window_union"]), fl["compressed"] + (0 if win_in_b else fl["window"])),
         B.SSV_K_IMPORTANCE: (work["kcmp_bytes"], fl["importance"]),
-        B.SSV_K_STREAM_B: (by["selected_union"], fl["selected"]),
+        B.SSV_K_STREAM_B: (by["selected_union"] + (by["window_union"] if win_in_b else 0), fl["selected"] + (fl["window"] if win_in_b else 0)),
     }
     peak_fl = MFMA_PEAK_TFLOPS[dtype] * 1e12
     rows = {}
@@ -219,7 +221,12 @@ def kernel_roofs(B, work, dtype, refresh_ms):
         if ms <= 0:
             continue
         t_hbm, t_mfma = nbytes / (HBM_PEAK_GBS * 1e9), nflops / peak_fl
-        rows[k] = {"kernel": B.kernel_name(k), "us": ms * 1e3, "method_bytes": int(nbytes), "method_flops": int(nflops),
+        name = B.kernel_name(k)
+        if plan.scan_matrix and k == B.SSV_K_STREAM_A:
+            name = "k_scan32 (compressed scan on the 32x32x16 matrix instruction)"
+        if plan.scan_matrix and k == B.SSV_K_STREAM_B:
+            name = "k_stream (window + selected blocks, merged schedule)"
+        rows[k] = {"kernel": name, "us": ms * 1e3, "method_bytes": int(nbytes), "method_flops": int(nflops),
                    "hbm_frac": t_hbm / (ms * 1e-3), "mfma_frac": t_mfma / (ms * 1e-3),
                    "bound": "hbm" if t_hbm >= t_mfma else "mfma"}
     return rows
@@ -255,7 +262,8 @@ def measure_workload(torch, oracle, case, name, tag, steps, warmup, parity=True,
                          "worst_swap_margin": rep.worst_swap_margin,
                          "ambiguous_units": rep.n_ambiguous, "units": rep.n_units, "max_abs_err": rep.max_abs_err}
         assert rep.n_mismatch_strict == 0 and rep.n_swap_violations == 0, rep.line()
-    work = method_work(case, ref.sel_idx, dev0.plan.C, dev0.plan.C_scan)
+    # (with the matrix-core scan the window branch runs in the selected-branch launch, in that launch's groups)
+    work = method_work(case, ref.sel_idx, dev0.plan.C, dev0.plan.C if dev0.plan.scan_matrix else dev0.plan.C_scan)
     work["kcmp_bytes"] = work["bytes"]["compressed"] * case.d_k // (case.d_k + case.d_v)
     ab = work["bytes"]
     res["algorithmic_bytes"] = ab
@@ -300,7 +308,9 @@ def measure_workload(torch, oracle, case, name, tag, steps, warmup, parity=True,
         out_modes[mname] = m
     res["modes"] = out_modes
     # both roofs per kernel of the refresh path, and the roofline object of the longest one
-    roofs = kernel_roofs(B, work, case.dtype, raw["refresh"])
+    for d in devs:
+        d.set_mode(B.SSV_REFRESH)
+    roofs = kernel_roofs(B, work, case.dtype, raw["refresh"], devs[0].plan)
     res["kernel_roofs_refresh"] = list(roofs.values())
     dom = max(roofs, key=lambda k: roofs[k]["us"])
     r = roofs[dom]

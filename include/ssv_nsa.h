@@ -68,15 +68,23 @@ extern "C" {
 #define SSV_TOPN_SEPARATE 1   /* always a launch of its own */
 #define SSV_TOPN_IN_SLC   2   /* inside the selected-branch launch whenever its scratch fits the tile buffers */
 
+/* ssv_nsa_params.scan_kernel: which kernel scans the compressed cache */
+#define SSV_SCAN_AUTO   0     /* the matrix-core scan where a KV head has 192 rows or more and the scan runs for several
+                                 tiles per workgroup, else the streaming kernel */
+#define SSV_SCAN_STREAM 1     /* the streaming kernel (64 or 128 rows per workgroup, two workgroups per CU) */
+#define SSV_SCAN_MATRIX 2     /* the matrix-core scan (bf16 only: 256 rows per workgroup, one workgroup per CU; the window
+                                 branch then runs in the selected-branch launch) */
+
 /* kernels of one call, in launch order (indices into kernel_ms of ssv_nsa_verify_timed) */
 #define SSV_K_STREAM_A  0     /* refresh: compressed scan + window;  reuse: compressed + window (+ selected, unless
-                                 SSV_K_STREAM_B is launched) */
+                                 SSV_K_STREAM_B is launched); with plan.scan_matrix: the compressed scan alone */
 #define SSV_K_IMPORTANCE 1    /* refresh only: normalised compressed probabilities summed over the group's heads */
 #define SSV_K_TOPN      2     /* refresh only: block importance + top-n selection; not launched (time 0) when the
                                  selection runs inside SSV_K_STREAM_B, which it does when that launch has at most
                                  one workgroup per CU */
 #define SSV_K_STREAM_B  3     /* selected-block attention over the merged schedule: refresh, and reuse when the scans
-                                 of SSV_K_STREAM_A use larger query groups than the selected branch (plan.C_scan > C) */
+                                 of SSV_K_STREAM_A use larger query groups than the selected branch (plan.C_scan > C);
+                                 with plan.scan_matrix: selected blocks + window */
 #define SSV_K_COMBINE   4     /* merge of split partial states + gated combination */
 #define SSV_K_STREAM_W  5     /* SSV_EXEC_UNFUSED only: the window branch as a launch of its own (SSV_K_STREAM_A then is
                                  the compressed branch alone) */
@@ -124,6 +132,8 @@ typedef struct ssv_nsa_params {
     int32_t imp_rows;     /* rows (routed queries x heads of a group) per workgroup in the importance pass of a refresh
                              call: 64, 128 or 256; 0 = automatic (more than 64 where a KV head has that many rows and
                              the pass runs for several tiles per workgroup); never changes the result */
+    int32_t scan_kernel;  /* SSV_SCAN_AUTO, SSV_SCAN_STREAM or SSV_SCAN_MATRIX (SSV_EXEC_FUSED, SSV_BF16 only; with it
+                             scan_group_size may reach 256 / H_g); never changes the result beyond rounding */
 } ssv_nsa_params;
 
 /* How one call is cut into workgroups (host-side planning; filled by ssv_nsa_plan). */
@@ -147,6 +157,8 @@ typedef struct ssv_nsa_plan {
     int32_t n_imp_chunks;     /* refresh: workgroups splitting the importance pass over k_cmp of one query group */
     int32_t imp_rows;         /* refresh: rows per workgroup in the importance pass (64, 128 or 256) */
     int32_t n_launches;       /* kernel launches of one call */
+    int32_t scan_matrix;      /* 1 if the compressed scan runs in the matrix-core kernel (then C_scan counts its groups of
+                                 up to 256 rows and the window branch runs in the selected-branch launch), else 0 */
     int64_t workspace_bytes;
 } ssv_nsa_plan;
 

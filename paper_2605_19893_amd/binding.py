@@ -24,6 +24,7 @@ SSV_NUM_KERNELS = 9
 SSV_T_EVENT_PAIR, SSV_NUM_TIMINGS = 9, 10
 SSV_EXEC_FUSED, SSV_EXEC_UNFUSED = 0, 1
 SSV_TOPN_AUTO, SSV_TOPN_SEPARATE, SSV_TOPN_IN_SLC = 0, 1, 2
+SSV_SCAN_AUTO, SSV_SCAN_STREAM, SSV_SCAN_MATRIX = 0, 1, 2
 
 EXPORTS = ("ssv_nsa_verify", "ssv_nsa_verify_static", "ssv_nsa_verify_timed", "ssv_nsa_plan_query", "ssv_nsa_workspace_bytes",
            "ssv_nsa_supported", "ssv_nsa_strerror", "ssv_nsa_kernel_name", "ssv_nsa_version", "ssv_nsa_compress",
@@ -39,7 +40,7 @@ class SsvNsaParams(ctypes.Structure):
                [("scale", ctypes.c_float), ("max_seq_len", ctypes.c_int32), ("max_n_cmp", ctypes.c_int32),
                 ("avg_seq_len", ctypes.c_int32), ("scan_group_size", ctypes.c_int32)] + \
                [(n, ctypes.c_int64 * 3) for n in ("k_stride", "v_stride", "kc_stride", "vc_stride", "q_stride", "out_stride")] + \
-               [(n, ctypes.c_int32) for n in ("exec", "topn_home", "max_slice_tiles", "imp_rows")]
+               [(n, ctypes.c_int32) for n in ("exec", "topn_home", "max_slice_tiles", "imp_rows", "scan_kernel")]
 
 
 class SsvCmpParams(ctypes.Structure):
@@ -67,7 +68,7 @@ class SsvNsaPlan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("C", "n_qg", "rows_per_wg", "n_cmp_chunks", "tiles_per_chunk", "n_win_splits", "n_slc_splits",
                  "min_tiles_per_split", "n_slots", "max_sched_entries", "share_group", "C_scan", "n_qg_scan", "topn_in_slc",
-                 "n_imp_chunks", "imp_rows", "n_launches")] + [("workspace_bytes", ctypes.c_int64)]
+                 "n_imp_chunks", "imp_rows", "n_launches", "scan_matrix")] + [("workspace_bytes", ctypes.c_int64)]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -135,11 +136,12 @@ def kernel_name(idx: int) -> str:
 def make_params(*, B, T, H, H_kv, d_k, d_v, l, d, l_sel, n_sel, w, n_init=1, n_local=2, dtype=SSV_BF16,
                 mode=SSV_REFRESH, group_size=0, scale=0.0, max_seq_len, max_n_cmp, avg_seq_len=0, scan_group_size=0, k_stride, v_stride, kc_stride,
                 vc_stride, q_stride=(0, 0, 0), out_stride=(0, 0, 0), exec=SSV_EXEC_FUSED, topn_home=SSV_TOPN_AUTO,
-                max_slice_tiles=0, imp_rows=0) -> SsvNsaParams:
+                max_slice_tiles=0, imp_rows=0, scan_kernel=SSV_SCAN_AUTO) -> SsvNsaParams:
     p = SsvNsaParams(B=B, T=T, H=H, H_kv=H_kv, d_k=d_k, d_v=d_v, l=l, d=d, l_sel=l_sel, n_sel=n_sel, w=w,
                      n_init=n_init, n_local=n_local, dtype=dtype, mode=mode, group_size=group_size, scale=scale,
                      max_seq_len=max_seq_len, max_n_cmp=max_n_cmp, avg_seq_len=avg_seq_len, scan_group_size=scan_group_size,
-                     exec=exec, topn_home=topn_home, max_slice_tiles=max_slice_tiles, imp_rows=imp_rows)
+                     exec=exec, topn_home=topn_home, max_slice_tiles=max_slice_tiles, imp_rows=imp_rows,
+                     scan_kernel=scan_kernel)
     for name, st in (("k_stride", k_stride), ("v_stride", v_stride), ("kc_stride", kc_stride), ("vc_stride", vc_stride),
                      ("q_stride", q_stride), ("out_stride", out_stride)):
         setattr(p, name, (ctypes.c_int64 * 3)(*[int(x) for x in st]))

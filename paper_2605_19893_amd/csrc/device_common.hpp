@@ -67,13 +67,18 @@ __device__ __forceinline__ void wait_vmcnt_upto(int n) {
 // Exchange with the lane 16 (32) positions away, without going through LDS: the gfx950 swap instructions return
 // the operand with its odd 16-lane (upper 32-lane) rows replaced by the even (lower) ones, and the reverse, so
 // combining the two results leaves op(x[l], x[l ^ 16]) (op(x[l], x[l ^ 32])) in every lane.
+// Maximum of two floats with the NaN-propagating instruction (v_maximum3_f32 on gfx950): unlike the IEEE maximum it
+// needs no canonicalisation of its inputs (one extra instruction per matrix-instruction result under the default
+// floating-point mode), and two nested calls fuse into one three-operand instruction.  Equal to fmaxf for non-NaN inputs.
+__device__ __forceinline__ float max_nan(float a, float b) { return __builtin_elementwise_maximum(a, b); }
+
 __device__ __forceinline__ float xor16_max(float x) {
     const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    return max_nan(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 __device__ __forceinline__ float xor32_max(float x) {
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    return max_nan(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 __device__ __forceinline__ float xor16_add(float x) {
     const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -86,6 +91,13 @@ __device__ __forceinline__ float xor32_add(float x) {
 
 __device__ __forceinline__ u32x4 lds_read16(const char* p) { return *reinterpret_cast<const u32x4*>(p); }
 __device__ __forceinline__ u32x2 lds_read8(const char* p) { return *reinterpret_cast<const u32x2*>(p); }
+// LDS addresses as 32-bit integers (for address arithmetic that pointers do not allow, such as XOR)
+__device__ __forceinline__ uint32_t lds_addr(const char* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+__device__ __forceinline__ u32x4 lds_read16_at(uint32_t addr) {
+    return *reinterpret_cast<__attribute__((address_space(3))) const u32x4*>((uintptr_t)addr);
+}
 
 // Tile loaders come in two halves so that the global loads of the next tile can be in flight while the
 // current tile is being computed: *_issue reads into registers, *_commit writes the registers to LDS.
@@ -147,15 +159,29 @@ struct RowTileRegs {
 // kind, which makes the compiler wait for ALL outstanding LDS reads before every use while one is in flight.  The LDS image has no row
 // padding; instead the 16-byte granule index inside every group of eight granules is XORed with the low three bits
 // of the row, which spreads the sixteen rows an MFMA operand read touches over the banks as padding would.
-//   granule (row r, column c)  ->  LDS granule r * CPR + ((c & ~7) | ((c & 7) ^ (r & 7)))
+//   granule (row r, column c)  ->  LDS granule r * CPR + swizzled(r, c), by policy SWZ:
+//   0: (c & ~7) | ((c & 7) ^ (r & 7)): for operand reads in which 16 lanes take the same granule of 16 consecutive rows
+//      while the other lane groups take the neighbouring granules (the 16x16x32 fragments);
+//   1: (c & ~7) | ((c & 7) ^ ((r >> 1) & 7)): for reads in which 32 lanes take the same granule of 32 consecutive rows
+//      (the 32x32x16 fragments: with policy 0 rows r and r + 8 of a 384- or 128-byte row pitch fall on the same banks
+//      and every read is served in two passes; measured on the device);
+//   2: the 64-byte chunk index c / 4 XORed with r & 3 (rows of four chunks) or (r >> 1) & 1 (rows of two): for the
+//      transposing 8-byte reads of a 32x32x16 A operand, in which each half of the wavefront takes 64 bytes of four
+//      consecutive rows (measured: as fast as a linear read; with an unswizzled 256-byte pitch three times slower).
 // Rows beyond valid_rows repeat the last valid row (the caller masks their scores; nothing is zero-filled).
-template <int ROW_BYTES>
+// NT: threads of the workgroup that share the tile's loads.
+template <int ROW_BYTES, int SWZ = 0, int NT = kThreads>
 struct DirectRowTile {
     static constexpr int CPR = ROW_BYTES / 16;            // granules per row
-    static_assert(CPR % 8 == 0, "rows must be whole groups of eight granules");
+    static_assert(SWZ == 2 ? (CPR == 8 || CPR == 16) : CPR % 8 == 0, "row length not covered by the swizzle");
+    __host__ __device__ __forceinline__ static constexpr int swizzled(int r, int c) {
+        if constexpr (SWZ == 0) return (c & ~7) | ((c & 7) ^ (r & 7));
+        else if constexpr (SWZ == 1) return (c & ~7) | ((c & 7) ^ ((r >> 1) & 7));
+        else return (((c >> 2) ^ (CPR == 16 ? (r & 3) : ((r >> 1) & 1))) << 2) | (c & 3);
+    }
     static constexpr int TOTAL = kTile * CPR;
-    static_assert(TOTAL % kThreads == 0, "tile must divide evenly over the workgroup");
-    static constexpr int ITERS = TOTAL / kThreads;        // load instructions per wavefront
+    static_assert(TOTAL % NT == 0, "tile must divide evenly over the workgroup");
+    static constexpr int ITERS = TOTAL / NT;        // load instructions per wavefront
     static constexpr int BYTES = kTile * ROW_BYTES;
     uint32_t off[ITERS];     // global byte offset, inside a full tile, of the granule this lane fetches in instruction it
 
@@ -164,7 +190,7 @@ struct DirectRowTile {
         const int p = ((tid >> 6) * ITERS + it) * 64 + (tid & 63);
         r = p / CPR;
         const int csw = p % CPR;
-        c = (csw & ~7) | ((csw & 7) ^ (r & 7));
+        c = swizzled(r, csw);     // (the swizzle is its own inverse)
     }
     __device__ __forceinline__ void init(uint32_t g_row_bytes, int tid) {
 #pragma unroll
@@ -175,9 +201,15 @@ struct DirectRowTile {
         }
     }
     // rsrc: buffer resource over the rows of one (sequence, KV head); tile_off: byte offset of the tile's first row
+    // RECOMPUTE: the (row, column) pairs behind the clamped offsets of a partial tile are derived again at every
+    // partial tile instead of being kept in registers across the caller's loops (for kernels short of registers).
+    template <bool RECOMPUTE = false>
     __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rsrc, uint32_t tile_off, char* lds_tile, uint32_t g_row_bytes,
                                           int valid_rows, int tid) {
         char* dst = lds_tile + (tid >> 6) * ITERS * 1024;     // wave-uniform
+        if constexpr (RECOMPUTE) {
+            if (valid_rows < kTile) asm volatile("" : "+v"(tid));    // opaque from here on: nothing below can be hoisted
+        }
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             uint32_t o = off[it];
@@ -199,6 +231,7 @@ struct DirectRowTile {
     // reads row `row` and granule G of 64-byte chunk kc finds it at base(kc & 1) + kc * 64, with
     //   base(0) = row * ROW_BYTES + ((G ^ (row & 3)) * 16) + ((row >> 2) & 1) * 64,   base(1) = base(0) - 2 * ((row >> 2) & 1) * 64
     __device__ __forceinline__ static int read_base(int row, int G, int odd) {
+        static_assert(SWZ == 0, "written for the row & 7 swizzle");
         const int hb = (row >> 2) & 1;
         return row * ROW_BYTES + ((G ^ (row & 3)) * 16) + (odd ? -hb * 64 : hb * 64);
     }
@@ -212,6 +245,12 @@ struct DirectRowTile {
 __device__ __forceinline__ u32x2 lds_read_tr16(const char* p) {
     typedef short s16x4 __attribute__((ext_vector_type(4)));
     const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+    return __builtin_bit_cast(u32x2, v);
+}
+
+__device__ __forceinline__ u32x2 lds_read_tr16_at(uint32_t addr) {
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)addr);
     return __builtin_bit_cast(u32x2, v);
 }
 

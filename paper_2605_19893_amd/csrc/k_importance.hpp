@@ -447,7 +447,7 @@ struct Importance32Cfg {
 template <int DK, int HGM, int RW>
 __global__ void __launch_bounds__(kThreads, 2) k_importance32(const ImportanceArgs a) {
     using Cfg = Importance32Cfg<DK>;
-    using Loader = DirectRowTile<Cfg::KROW>;
+    using Loader = DirectRowTile<Cfg::KROW, 1>;
     constexpr int STEPS = Cfg::STEPS, DEPTH = Cfg::DEPTH, TILE = Cfg::TILE, LD = Loader::ITERS;
     constexpr int WGR = kImpRows * RW;                 // rows per workgroup
     constexpr int RTW = RW == 4 ? 2 : 1, KTW = RW == 1 ? 1 : 2;
@@ -618,10 +618,10 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance32(const ImportanceAr
     }
 
     // this lane's byte offsets into a tile for the four contraction steps of a 128-byte group (the swizzle XORs the
-    // granule index with the low bits of the row, which for row 32 kt + n are those of n)
+    // granule index with bits 1..3 of the row, which for row 32 kt + n are those of n)
     int koff[4];
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) koff[q4] = n * Cfg::KROW + (((2 * q4 + hb) ^ (n & 7)) << 4);
+    for (int q4 = 0; q4 < 4; ++q4) koff[q4] = n * Cfg::KROW + (((2 * q4 + hb) ^ ((n >> 1) & 7)) << 4);
 
     // The 32 x 32 blocks of one key tile, one per row tile of this wavefront: 16 scores per lane and block; every K
     // fragment read from LDS serves all RTW row tiles.  Then, per block: exponentials, head sums and stores.

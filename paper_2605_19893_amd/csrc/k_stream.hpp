@@ -83,8 +83,9 @@ __device__ __forceinline__ void even_slice(int n, int parts, int min_items, int 
 
 // ROLES: which branches this instantiation can run (bit 0 CMP, bit 1 WIN, bit 2 SLC).  The refresh path
 // launches <CMP|WIN> and then <SLC>, the reuse path launches all three at once, the unfused execution launches
-// each branch on its own; code of absent roles is compiled out.
-constexpr int kRolesCmp = 1, kRolesWin = 2, kRolesCmpWin = 3, kRolesSlc = 4, kRolesAll = 7;
+// each branch on its own, and <WIN|SLC> follows the matrix-core scan of the compressed cache (k_scan32.hpp); code of
+// absent roles is compiled out.
+constexpr int kRolesCmp = 1, kRolesWin = 2, kRolesCmpWin = 3, kRolesSlc = 4, kRolesWinSlc = 6, kRolesAll = 7;
 
 // Two workgroups per CU (the LDS of the full-size shapes allows no more), stated to the compiler as exactly two
 // waves per SIMD: left free to aim for three, it trades away the read-ahead of the K fragments for registers that
@@ -176,8 +177,8 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
 
     // ---- fused top-n selection (Section 5.1: routing, then attention over the selected blocks)
     int32_t* s_sel = nullptr;     // [C][n_sel] index sets of the group's queries, in the (still idle) tile buffers
-    if constexpr (ROLES == kRolesSlc) {
-        if (a.fused_topn) {
+    if constexpr (ROLES == kRolesSlc || ROLES == kRolesWinSlc) {
+        if (a.fused_topn && r_slc) {      // (uniform per workgroup)
             s_sel = reinterpret_cast<int32_t*>(smem + 4 * wave_topn_lds_bytes(a.max_blocks));
             const WaveTopnScratch ws = wave_topn_scratch(smem + wave * wave_topn_lds_bytes(a.max_blocks), a.max_blocks);
             for (int j = wave; j < a.C; j += 4) {
@@ -464,10 +465,10 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
 #pragma unroll
                 for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[t][kt][r]);
+                    for (int r = 0; r < 4; ++r) mx = max_nan(mx, s[t][kt][r]);
                 mx = xor16_max(mx);
                 mx = xor32_max(mx);
-                const float m_new = fmaxf(mrun[t], mx);
+                const float m_new = max_nan(mrun[t], mx);
                 const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
                 const float alpha = fast_exp2((mrun[t] - m_use) * a.scale_log2);
                 const float neg_ms = -m_use * a.scale_log2;

@@ -11,6 +11,7 @@
 #include "k_combine.hpp"
 #include "k_compress.hpp"
 #include "k_importance.hpp"
+#include "k_scan32.hpp"
 #include "k_stream.hpp"
 #include "k_topn.hpp"
 #include "planner.hpp"
@@ -39,11 +40,16 @@ constexpr int kImportanceWgs = 512;          // one round of the importance pass
 constexpr int kTopnInSlcMaxWgs = 256;        // SSV_TOPN_AUTO: select inside the selected-branch launch up to this many workgroups
                                              // (twice as many when a wavefront has one query to select for)
 constexpr size_t kMaxStreamLds = 80 * 1024;  // two workgroups per CU
+constexpr int kScan32Wgs = 256;              // the matrix-core scan: one workgroup per CU
+constexpr int kScan32MinRows = 192;          // SSV_SCAN_AUTO: rows per (sequence, KV head) from which it is used ...
+constexpr int kScan32MinTileSteps = 1024;    // ... when the launch has at least this many tile steps (four per CU)
+constexpr int kScan32MinTilesMultiRound = 8; // its launches of several rounds: slices of a short sequence hold at least this many tiles
+constexpr size_t kMaxLds = 160 * 1024;
 
 struct Layout {
     ssv_nsa_plan plan;
     int H_g, es;
-    bool one_launch, unfused;
+    bool one_launch, unfused, scan32;
     int imp_C, imp_n_qg, n_imp_chunks, imp_rw;   // importance pass: routed queries per workgroup, such workgroups per sequence, slices, blocks of 64 rows per workgroup
     int nc_pitch, max_blocks, bitmap_words, max_sched;
     size_t lds_stream, lds_k, lds_vt;
@@ -73,7 +79,9 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     if (p->topn_home != SSV_TOPN_AUTO && p->topn_home != SSV_TOPN_SEPARATE && p->topn_home != SSV_TOPN_IN_SLC) return SSV_EINVAL;
     if (p->max_slice_tiles != 0 && (p->max_slice_tiles < 2 || p->max_slice_tiles > 64)) return SSV_EINVAL;
     if (p->imp_rows != 0 && p->imp_rows != 64 && p->imp_rows != 128 && p->imp_rows != 256) return SSV_EINVAL;
+    if (p->scan_kernel != SSV_SCAN_AUTO && p->scan_kernel != SSV_SCAN_STREAM && p->scan_kernel != SSV_SCAN_MATRIX) return SSV_EINVAL;
     const bool unfused = p->exec == SSV_EXEC_UNFUSED;
+    if (p->scan_kernel == SSV_SCAN_MATRIX && (unfused || p->dtype != SSV_BF16)) return SSV_EINVAL;
     if (unfused && (p->mode == SSV_REFRESH_SHARED || p->group_size > 1 || p->scan_group_size > 1)) return SSV_EINVAL;
     const int H_g = p->H / p->H_kv;
     if (p->T > SSV_MAX_T) return SSV_EUNSUPPORTED;
@@ -95,7 +103,10 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     const bool shared = p->mode == SSV_REFRESH_SHARED;
     const int c_max = shared ? p->T : std::min(p->T, std::min(64, 128 / H_g));   // ownership masks hold 64 queries
     if (p->group_size > c_max) return SSV_EINVAL;
-    if (p->scan_group_size < 0 || p->scan_group_size > std::min(p->T, std::min(64, 128 / H_g))) return SSV_EINVAL;
+    const bool force32 = p->scan_kernel == SSV_SCAN_MATRIX;
+    if (p->scan_group_size < 0 || p->scan_group_size > std::min(p->T, force32 ? 256 / H_g : std::min(64, 128 / H_g))) return SSV_EINVAL;
+    // (the matrix-core scan fetches V rows through 32-bit buffer offsets as well)
+    if (force32 && (int64_t)p->max_n_cmp * p->vc_stride[2] * es >= (1ll << 31)) return SSV_EUNSUPPORTED;
     const int max_blocks = (p->max_seq_len + p->T) / p->l_sel + 1;
     if (max_blocks > 16384) return SSV_EUNSUPPORTED;
 
@@ -142,8 +153,22 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // groups of up to 128 rows (two row tiles per wave share every K and V fragment read from LDS: measured 18-20 %
     // faster at 16-40 queries per sequence), balanced over the sequence's queries.  An explicit group_size applies
     // to both launches unless the scan has one of its own.
+    // The matrix-core scan (bf16): groups of up to 256 rows, one workgroup per CU.  Automatic where a KV head has
+    // enough rows to fill most of such a workgroup and the launch runs for several tiles per CU: there the scan is
+    // bound by the matrix cores, and the streaming kernel's 128-row workgroups re-read every tile from L2.
+    {
+        const int n_g32 = ceil_div(p->T * H_g, 256);
+        const bool can32 = !unfused && p->dtype == SSV_BF16 && (int64_t)p->max_n_cmp * p->vc_stride[2] * es < (1ll << 31);
+        lo->scan32 = force32 || (p->scan_kernel == SSV_SCAN_AUTO && can32 && !p->scan_group_size && (!p->group_size || shared) &&
+                                 p->T * H_g >= kScan32MinRows &&
+                                 (int64_t)p->B * p->H_kv * n_g32 * ntc_avg >= kScan32MinTileSteps);
+    }
     pl.C_scan = pl.C;
     if (unfused) pl.C_scan = 1;
+    else if (lo->scan32) {
+        const int c_cap = std::max(1, std::min(p->T, 256 / H_g));
+        pl.C_scan = p->scan_group_size ? p->scan_group_size : ceil_div(p->T, ceil_div(p->T, c_cap));   // balanced over the groups
+    }
     else if (p->scan_group_size) pl.C_scan = p->scan_group_size;
     else if (!p->group_size || shared) {
         const int n_a = ceil_div(p->T, std::max(1, std::min(p->T, 128 / H_g)));
@@ -177,11 +202,18 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
         }
     };
     int per_c, per_w, per_s;
-    lo->one_launch = !unfused && p->mode == SSV_REUSE && pl.C_scan == pl.C;   // all three branches in one launch
+    lo->one_launch = !unfused && !lo->scan32 && p->mode == SSV_REUSE && pl.C_scan == pl.C;   // all three branches in one launch
     if (unfused) {              // one launch per branch
         per_c = tiles_per_slice(&ntc_avg, 1, units);
         per_w = tiles_per_slice(&ntw, 1, units);
         per_s = tiles_per_slice(&nts, 1, units);
+    } else if (lo->scan32) {
+        // the scan: slices so that the average unit fills one round of one workgroup per CU, cut to long_slice tiles
+        // when that takes several rounds; window and selected blocks share the second launch
+        const int spu = std::max(1, kScan32Wgs / units_scan);
+        per_c = std::min(std::max(1, ceil_div(ntc_avg, spu)), long_slice);
+        const int tiles_b[2] = {ntw, nts};
+        per_w = per_s = tiles_per_slice(tiles_b, 2, units);
     } else if (lo->one_launch) {
         const int tiles[3] = {ntc_avg, ntw, nts};
         per_c = per_w = per_s = tiles_per_slice(tiles, 3, units);
@@ -245,13 +277,14 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // separate launch once the chip is full.
     const bool refresh = p->mode != SSV_REUSE;
     const bool fits = fused_topn_lds_bytes(max_blocks, pl.C, p->n_sel) <= lo->lds_k + lo->lds_vt;
-    const int n_wg_b = units * pl.n_slc_splits;
+    const int n_wg_b = units * (pl.n_slc_splits + (lo->scan32 ? pl.n_win_splits : 0));
     pl.topn_in_slc = refresh && !unfused && fits &&
                      (p->topn_home == SSV_TOPN_IN_SLC || (p->topn_home == SSV_TOPN_AUTO && n_wg_b <= (pl.C <= 4 ? 2 : 1) * kTopnInSlcMaxWgs));
     pl.n_imp_chunks = refresh ? lo->n_imp_chunks : 0;
     pl.imp_rows = refresh ? 64 * lo->imp_rw : 0;
     if (unfused) pl.n_launches = refresh ? 9 : 7;
     else pl.n_launches = (lo->one_launch ? 1 : 2) + (refresh ? 1 + !pl.topn_in_slc : 0) + 1;
+    pl.scan_matrix = lo->scan32;
     lo->rows_total = (int64_t)p->B * p->T * p->H;
     size_t off = 0;
     lo->off_stats = off;
@@ -323,13 +356,14 @@ struct Timer {
 };
 
 // Launch of timed kernel K_: with its own start/stop events when every kernel is launched once, plainly otherwise.
-#define SSV_LAUNCH(K_, KERNEL_, GRID_, LDS_, ARGS_)                                                                      \
+#define SSV_LAUNCH_T(K_, KERNEL_, GRID_, THREADS_, LDS_, ARGS_)                                                          \
     do {                                                                                                                 \
         if (tm.per_dispatch())                                                                                           \
-            hipExtLaunchKernelGGL(KERNEL_, dim3(GRID_), dim3(kThreads), (uint32_t)(LDS_), stream, tm.ev[K_][0], tm.ev[K_][1], 0, ARGS_); \
+            hipExtLaunchKernelGGL(KERNEL_, dim3(GRID_), dim3(THREADS_), (uint32_t)(LDS_), stream, tm.ev[K_][0], tm.ev[K_][1], 0, ARGS_); \
         else                                                                                                             \
-            hipLaunchKernelGGL(KERNEL_, dim3(GRID_), dim3(kThreads), LDS_, stream, ARGS_);                               \
+            hipLaunchKernelGGL(KERNEL_, dim3(GRID_), dim3(THREADS_), LDS_, stream, ARGS_);                               \
     } while (0)
+#define SSV_LAUNCH(K_, KERNEL_, GRID_, LDS_, ARGS_) SSV_LAUNCH_T(K_, KERNEL_, GRID_, kThreads, LDS_, ARGS_)
 
 template <bool BF16, int DK, int DV>
 int launch_all(const void* q, const void* k, const void* v, const void* kc, const void* vc, const float* gates,
@@ -375,11 +409,17 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
                                  (const void*)k_stream<BF16, DK, DV, 1, kRolesCmpWin>, (const void*)k_stream<BF16, DK, DV, 2, kRolesAll>,
                                  (const void*)k_stream<BF16, DK, DV, 2, kRolesSlc>, (const void*)k_stream<BF16, DK, DV, 2, kRolesCmpWin>,
                                  (const void*)k_stream<BF16, DK, DV, 1, kRolesCmp>, (const void*)k_stream<BF16, DK, DV, 1, kRolesWin>,
+                                 (const void*)k_stream<BF16, DK, DV, 1, kRolesWinSlc>, (const void*)k_stream<BF16, DK, DV, 2, kRolesWinSlc>,
                                  ImportanceKernels<BF16, DK>::fn(16, 1), ImportanceKernels<BF16, DK>::fn(4, 1), ImportanceKernels<BF16, DK>::fn(1, 1),
                                  ImportanceKernels<BF16, DK>::fn(16, 2), ImportanceKernels<BF16, DK>::fn(4, 2), ImportanceKernels<BF16, DK>::fn(1, 2),
                                  ImportanceKernels<BF16, DK>::fn(16, 4), ImportanceKernels<BF16, DK>::fn(4, 4), ImportanceKernels<BF16, DK>::fn(1, 4)};
             for (const void* fn : fns)
                 if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStreamLds) != hipSuccess) return SSV_ELAUNCH;
+            if constexpr (BF16) {
+                if (hipFuncSetAttribute((const void*)k_scan32<DK, DV>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)Scan32Cfg<DK, DV>::LDS) != hipSuccess)
+                    return SSV_ELAUNCH;
+            }
             raised[dev].store(true, std::memory_order_release);
         }
     }
@@ -399,10 +439,12 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
             if (C * lo.H_g > 64) {
                 if (roles == kRolesAll) SSV_LAUNCH_STREAM(2, kRolesAll);
                 else if (roles == kRolesSlc) SSV_LAUNCH_STREAM(2, kRolesSlc);
+                else if (roles == kRolesWinSlc) SSV_LAUNCH_STREAM(2, kRolesWinSlc);
                 else SSV_LAUNCH_STREAM(2, kRolesCmpWin);
             } else {
                 if (roles == kRolesAll) SSV_LAUNCH_STREAM(1, kRolesAll);
                 else if (roles == kRolesSlc) SSV_LAUNCH_STREAM(1, kRolesSlc);
+                else if (roles == kRolesWinSlc) SSV_LAUNCH_STREAM(1, kRolesWinSlc);
                 else if (roles == kRolesCmp) SSV_LAUNCH_STREAM(1, kRolesCmp);
                 else if (roles == kRolesWin) SSV_LAUNCH_STREAM(1, kRolesWin);
                 else SSV_LAUNCH_STREAM(1, kRolesCmpWin);
@@ -410,6 +452,29 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
 #undef SSV_LAUNCH_STREAM
         }
         return (hipGetLastError() == hipSuccess && !tm.end(K)) ? 0 : -1;
+    };
+
+    // the compressed scan in the matrix-core kernel: partial-state slots [0, n_cmp_chunks), groups of C_scan queries
+    auto launch_scan32 = [&]() -> int {
+        if constexpr (BF16) {
+            Scan32Args ca{};
+            ca.q = sa.q; ca.kc = sa.kc; ca.vc = sa.vc; ca.seq_lens = seq_lens; ca.n_cmp = n_cmp; ca.n_query = n_query; ca.parents = parents;
+            ca.part_stats = part_stats; ca.part_acc = part_acc;
+            ca.B = p->B; ca.T = p->T; ca.H = p->H; ca.H_kv = p->H_kv; ca.H_g = lo.H_g; ca.C = pl.C_scan; ca.n_qg = pl.n_qg_scan;
+            ca.l = p->l; ca.d = p->d; ca.max_seq_len = p->max_seq_len; ca.max_n_cmp = p->max_n_cmp; ca.scale_log2 = scale_log2;
+            ca.n_chunks = pl.n_cmp_chunks;
+            ca.n_wg = p->B * p->H_kv * pl.n_qg_scan * pl.n_cmp_chunks;
+            ca.min_tiles = ca.n_wg > kScan32Wgs ? kScan32MinTilesMultiRound : 1;
+            ca.rows_total = lo.rows_total;
+            for (int j = 0; j < 3; ++j) { ca.kc_s[j] = sa.kc_s[j]; ca.vc_s[j] = sa.vc_s[j]; ca.q_s[j] = lo.q_s[j]; }
+            if (pl.C_scan * lo.H_g > Scan32Cfg<DK, DV>::ROWS) return -1;      // (cannot happen: make_layout bounds C_scan)
+            const int grid = ceil_div(ca.n_wg, 8) * 8;
+            if (tm.begin(SSV_K_STREAM_A)) return -1;
+            for (int r = 0; r < reps; ++r) SSV_LAUNCH_T(SSV_K_STREAM_A, (k_scan32<DK, DV>), grid, kScan32Threads, (Scan32Cfg<DK, DV>::LDS), ca);
+            return (hipGetLastError() == hipSuccess && !tm.end(SSV_K_STREAM_A)) ? 0 : -1;
+        } else {
+            return -1;
+        }
     };
 
     // routing of a refresh call: normalised head-summed probabilities, then (unless the selected-branch launch does
@@ -493,7 +558,11 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         return SSV_OK;
     }
 
-    if (lo.one_launch) {
+    if (lo.scan32) {
+        if (launch_scan32()) return SSV_ELAUNCH;
+        if (p->mode != SSV_REUSE && launch_routing()) return SSV_ELAUNCH;
+        if (launch_stream(SSV_K_STREAM_B, kRolesWinSlc, pl.n_cmp_chunks, pl.n_win_splits + pl.n_slc_splits, pl.C, pl.n_qg)) return SSV_ELAUNCH;
+    } else if (lo.one_launch) {
         if (launch_stream(SSV_K_STREAM_A, kRolesAll, 0, pl.n_slots, pl.C, pl.n_qg)) return SSV_ELAUNCH;
     } else {
         if (launch_stream(SSV_K_STREAM_A, kRolesCmpWin, 0, n_scan_slots, pl.C_scan, pl.n_qg_scan)) return SSV_ELAUNCH;

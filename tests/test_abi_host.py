@@ -32,8 +32,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layout_matches_header():
-    # 21 four-byte fields (+ 4 bytes of padding), 18 int64 strides, 4 four-byte fields; 17 ints (+ padding) and an int64 in the plan
-    assert ctypes.sizeof(B.SsvNsaParams) == 22 * 4 + 18 * 8 + 4 * 4
+    # 21 four-byte fields (+ 4 bytes of padding), 18 int64 strides, 5 four-byte fields (+ padding); 18 ints and an int64 in the plan
+    assert ctypes.sizeof(B.SsvNsaParams) == 22 * 4 + 18 * 8 + 6 * 4
     assert ctypes.sizeof(B.SsvNsaPlan) == 18 * 4 + 8
     with open(os.path.join(ROOT, "include", "ssv_nsa.h")) as f:
         header = f.read()
@@ -121,14 +121,22 @@ def test_plan_fills_the_chip_and_respects_limits():
         assert pl.n_slots == pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits
         assert pl.n_cmp_chunks * pl.tiles_per_chunk * 64 >= p.max_n_cmp
         assert pl.max_sched_entries == pl.C * p.n_sel
-        # scan launch: larger, balanced groups only where the scans keep the chip busy for several rounds
-        assert pl.C_scan * pl.n_qg_scan >= p.T and pl.C <= pl.C_scan <= 128 // H_g
-        assert (pl.C_scan, pl.n_qg_scan) == {"cfg1": (4, 2), "cfg2": (4, 1), "cfg3": (8, 5), "cfg4": (8, 2)}[name]
+        # scan launch: larger, balanced groups only where the scans keep the chip busy for several rounds; the
+        # matrix-core scan (groups of up to 256 rows, one workgroup per CU) where a KV head has the rows for it
+        assert pl.scan_matrix == {"cfg1": 0, "cfg2": 0, "cfg3": 1, "cfg4": 1}[name]
+        assert pl.C_scan * pl.n_qg_scan >= p.T and pl.C <= pl.C_scan <= (256 if pl.scan_matrix else 128) // H_g
+        assert (pl.C_scan, pl.n_qg_scan) == {"cfg1": (4, 2), "cfg2": (4, 1), "cfg3": (14, 3), "cfg4": (16, 1)}[name]
         units = p.B * p.H_kv * pl.n_qg_scan
-        wgs = units * (pl.n_cmp_chunks + pl.n_win_splits)
-        # either one resident round (at most 2 workgroups per CU) or several rounds of slices of at most 32 tiles
-        assert wgs >= min(256, units * ((p.max_n_cmp + 63) // 64) // 2), (name, wgs)
-        assert wgs <= 512 or pl.tiles_per_chunk <= 32, (name, wgs)
+        if pl.scan_matrix:
+            wgs = units * pl.n_cmp_chunks
+            # one round of one workgroup per CU, or several rounds of slices of at most 32 tiles
+            assert 128 < wgs <= 256 or (wgs > 256 and pl.tiles_per_chunk <= 32), (name, wgs)
+            assert pl.n_launches == (5 if name == "cfg4" else 4)
+        else:
+            wgs = units * (pl.n_cmp_chunks + pl.n_win_splits)
+            # either one resident round (at most 2 workgroups per CU) or several rounds of slices of at most 32 tiles
+            assert wgs >= min(256, units * ((p.max_n_cmp + 63) // 64) // 2), (name, wgs)
+            assert wgs <= 512 or pl.tiles_per_chunk <= 32, (name, wgs)
         assert pl.workspace_bytes == B.ssv_nsa_workspace_bytes(p) and pl.workspace_bytes % 256 == 0
     p = std_params(group_size=2)
     pl = B.ssv_nsa_plan_query(p)
@@ -146,9 +154,21 @@ def test_plan_fills_the_chip_and_respects_limits():
         with pytest.raises(B.SsvError) as e:
             B.ssv_nsa_plan_query(std_params(scan_group_size=bad))
         assert e.value.code == B.SSV_EINVAL
-    # 12 queries: two balanced scan groups of 6
+    # 12 queries: one group of 192 rows in the matrix-core scan; two balanced groups of 6 in the streaming kernel
     pl = B.ssv_nsa_plan_query(std_params(B=32, T=12, max_seq_len=131072, max_n_cmp=8191))
-    assert (pl.C, pl.n_qg, pl.C_scan, pl.n_qg_scan) == (4, 3, 6, 2)
+    assert (pl.C, pl.n_qg, pl.C_scan, pl.n_qg_scan, pl.scan_matrix) == (4, 3, 12, 1, 1)
+    pl = B.ssv_nsa_plan_query(std_params(B=32, T=12, max_seq_len=131072, max_n_cmp=8191, scan_kernel=B.SSV_SCAN_STREAM))
+    assert (pl.C, pl.n_qg, pl.C_scan, pl.n_qg_scan, pl.scan_matrix) == (4, 3, 6, 2, 0)
+    # the matrix-core scan on request: any bf16 problem of the fused execution; its groups hold up to 256 rows
+    pl = B.ssv_nsa_plan_query(std_params(scan_kernel=B.SSV_SCAN_MATRIX))
+    assert (pl.scan_matrix, pl.C_scan, pl.n_qg_scan, pl.n_launches) == (1, 8, 1, 4)
+    pl = B.ssv_nsa_plan_query(std_params(scan_kernel=B.SSV_SCAN_MATRIX, scan_group_size=3, mode=B.SSV_REUSE))
+    assert (pl.scan_matrix, pl.C_scan, pl.n_qg_scan, pl.n_launches) == (1, 3, 3, 3)
+    for bad in (dict(scan_kernel=3), dict(scan_kernel=B.SSV_SCAN_MATRIX, exec=B.SSV_EXEC_UNFUSED),
+                dict(scan_kernel=B.SSV_SCAN_MATRIX, dtype=B.SSV_F32, d_k=64, d_v=64), dict(scan_kernel=B.SSV_SCAN_MATRIX, scan_group_size=17)):
+        with pytest.raises(B.SsvError) as e:
+            B.ssv_nsa_plan_query(std_params(**bad))
+        assert e.value.code == B.SSV_EINVAL, bad
 
 
 def test_static_scratch_entry_point_checks_before_touching_the_device():

@@ -499,3 +499,39 @@ def test_wide_importance_pass(dev_mod, oracle, imp_rows):
         assert np.array_equal(out_w, out), case.name
     run_shared(dev_mod, oracle, cases[0], 2, imp_rows=imp_rows)
     run_shared(dev_mod, oracle, cases[1], 3, imp_rows=imp_rows)
+
+
+def test_matrix_core_scan(dev_mod, oracle):
+    """The compressed scan in the matrix-core kernel (256 rows per workgroup, the window branch moved into the
+    selected-branch launch) against the oracle: chains with ragged query counts and several tiles per slice, a row count
+    that fills one workgroup partly and one that needs three, a tree (per-row visibility limits in the last tiles),
+    every heads-per-group class, a sequence with fewer compressed rows than one tile and one with none, the
+    shared-index variant, reuse mode, and an explicit scan grouping."""
+    from paper_2605_19893_amd import binding as B
+    tree = si.tree_parents((4, 3, 2), "bfs")
+    cases = [
+        si.make_case("mscan_chain", "bf16", 2, 19, 64, 4, 192, 128, si.STD_NSA, [9000, 2300], 601, rho=0.6, n_query=[19, 11],
+                     poison_pad=True),
+        si.make_case("mscan_tree", "bf16", 2, len(tree), 32, 2, 192, 128, si.STD_NSA, [4100, 12000], 603, rho=0.6, parents=tree),
+        si.make_case("mscan_hg4", "bf16", 1, 64, 32, 8, 64, 64, si.STD_NSA, [7000], 605, rho=0.3),
+        si.make_case("mscan_hg8", "bf16", 2, 30, 16, 2, 128, 128, si.STD_NSA, [3000, 5000], 607, rho=0.3, n_query=[30, 17]),
+        si.make_case("mscan_hg2", "bf16", 1, 100, 4, 2, 64, 64, si.STD_NSA, [2500], 609, rho=0.3),
+        si.make_case("mscan_short", "bf16", 3, 6, 32, 2, 192, 128, si.STD_NSA, [700, 20, 1100], 611, rho=0.3, n_query=[6, 6, 2]),
+    ]
+    for case in cases:
+        dev, ref, out, sel = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_MATRIX)
+        assert dev.plan.scan_matrix == 1 and dev.plan.C_scan * (case.H // case.H_kv) <= 256
+        run_reuse(dev_mod, oracle, case, sel, dev=dev)
+        assert dev.plan.scan_matrix == 1
+        dev_s, _, out_s, sel_s = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_STREAM)
+        assert dev_s.plan.scan_matrix == 0
+        assert np.array_equal(sel_s, sel), case.name            # the routing sees the same statistics up to rounding
+    run_shared(dev_mod, oracle, cases[0], 2, scan_kernel=B.SSV_SCAN_MATRIX)
+    run_shared(dev_mod, oracle, cases[1], 3, scan_kernel=B.SSV_SCAN_MATRIX)
+    # explicit scan grouping: 5 queries (80 rows) per workgroup of the scan, 2 per workgroup of the other branches
+    dev = dev_mod.DeviceCase(cases[0], scan_kernel=B.SSV_SCAN_MATRIX)
+    dev.set_group_size(2, B.SSV_REFRESH, scan_group_size=5)
+    assert dev.plan.scan_matrix == 1 and dev.plan.C_scan == 5 and dev.plan.C == 2
+    dev.run()
+    out, sel = dev.results()
+    check(cases[0], compare(cases[0], oracle, oracle.nsa_verify(cases[0]), out, sel))
