@@ -444,13 +444,20 @@ struct Importance32Cfg {
     static constexpr int LDS_RING = DEPTH * TILE;
 };
 
-template <int DK, int HGM, int RW>
-__global__ void __launch_bounds__(kThreads, 2) k_importance32(const ImportanceArgs a) {
+// NW: wavefronts per workgroup.  Eight (RW = 4 only) give every wavefront one row tile and both key tiles, four
+// wavefronts per SIMD with two workgroups per CU: measured on the device, one wavefront issues a 32x32x16 matrix
+// instruction every 64 clocks at best and its vector instructions at about half the rate a SIMD reaches with several
+// wavefronts, so a tile step takes a wavefront the sum of its own matrix and vector work whatever else the SIMD holds;
+// halving the work per wavefront halves the step, as long as the registers (128 per lane) allow four per SIMD.
+template <int DK, int HGM, int RW, int NW = 4>
+__global__ void __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) __attribute__((amdgpu_waves_per_eu(NW == 8 ? 4 : 2, NW == 8 ? 4 : 8)))
+k_importance32(const ImportanceArgs a) {
     using Cfg = Importance32Cfg<DK>;
-    using Loader = DirectRowTile<Cfg::KROW, 1>;
+    using Loader = DirectRowTile<Cfg::KROW, 1, 64 * NW>;
+    static_assert(NW == 4 || (NW == 8 && RW == 4), "eight wavefronts: 256 rows only");
     constexpr int STEPS = Cfg::STEPS, DEPTH = Cfg::DEPTH, TILE = Cfg::TILE, LD = Loader::ITERS;
     constexpr int WGR = kImpRows * RW;                 // rows per workgroup
-    constexpr int RTW = RW == 4 ? 2 : 1, KTW = RW == 1 ? 1 : 2;
+    constexpr int RTW = (RW == 4 && NW == 4) ? 2 : 1, KTW = RW == 1 ? 1 : 2;
     constexpr int QPT = HGM == 16 ? 1 : (HGM == 4 ? 4 : 16);   // stores per 32 x 32 block and lane (H_g = 8: two of the four are used)
     static_assert(RW == 1 || RW == 2 || RW == 4, "row blocks per workgroup");
     static_assert(4 * WGR * 8 <= TILE, "the partial statistics fit one ring slot");
@@ -544,6 +551,7 @@ __global__ void __launch_bounds__(kThreads, 2) k_importance32(const ImportanceAr
         const int q_of_row = j < nq_grp ? s_qi[j] : s_qi[0];
         const int64_t srow = ((int64_t)b * a.T + q_of_row) * a.H + g * a.H_g + rr % a.H_g;
         float M = -INFINITY, Z = 0.f;
+        if (wave >= 4) continue;      // (the first four wavefronts do this part, in the same order whatever NW is)
         for (int s0 = wave; s0 < a.n_cmp_chunks; s0 += 16) {
             float2 st[4];
 #pragma unroll

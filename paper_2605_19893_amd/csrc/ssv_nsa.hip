@@ -306,9 +306,12 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
 template <bool BF16, int DK>
 struct ImportanceKernels {
     static constexpr size_t LDS = BF16 ? (size_t)Importance32Cfg<DK>::LDS_RING : (size_t)ImportanceCfg<false, DK>::LDS_RING;
+    // wavefronts per workgroup: the 256-row bf16 kernel of 16-head groups runs with eight (the other head classes need
+    // more than the 128 registers that four wavefronts per SIMD leave each)
+    static constexpr int waves(int hgm, int rw) { return (BF16 && hgm == 16 && rw == 4) ? 8 : 4; }
     template <int HGM, int RW>
     static const void* one() {
-        if constexpr (BF16) return (const void*)k_importance32<DK, HGM, RW>;
+        if constexpr (BF16) return (const void*)k_importance32<DK, HGM, RW, waves(HGM, RW)>;
         else return (const void*)k_importance<false, DK, HGM, RW>;
     }
     static const void* fn(int hgm, int rw) {
@@ -493,7 +496,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         if (tm.begin(SSV_K_IMPORTANCE)) return -1;
         using IK = ImportanceKernels<BF16, DK>;
         const auto imp_kernel = reinterpret_cast<void (*)(ImportanceArgs)>(const_cast<void*>(IK::fn(lo.H_g == 16 ? 16 : (lo.H_g >= 4 ? 4 : 1), lo.imp_rw)));
-        for (int r = 0; r < reps; ++r) SSV_LAUNCH(SSV_K_IMPORTANCE, imp_kernel, grid_i, IK::LDS, ia);
+        for (int r = 0; r < reps; ++r) SSV_LAUNCH_T(SSV_K_IMPORTANCE, imp_kernel, grid_i, 64 * IK::waves(lo.H_g == 16 ? 16 : (lo.H_g >= 4 ? 4 : 1), lo.imp_rw), IK::LDS, ia);
         if (hipGetLastError() != hipSuccess || tm.end(SSV_K_IMPORTANCE)) return -1;
 
         sa.colsum = colsum; sa.sel_out = sel_idx; sa.nc_pitch = lo.nc_pitch; sa.l_sel = p->l_sel; sa.n_init = p->n_init;
