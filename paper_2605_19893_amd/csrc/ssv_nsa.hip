@@ -43,6 +43,7 @@ constexpr size_t kMaxStreamLds = 80 * 1024;  // two workgroups per CU
 constexpr int kScan32Wgs = 256;              // the matrix-core scan: one workgroup per CU
 constexpr int kScan32MinRows = 192;          // SSV_SCAN_AUTO: rows per (sequence, KV head) from which it is used ...
 constexpr int kScan32MinTileSteps = 1024;    // ... when the launch has at least this many tile steps (four per CU)
+constexpr int kScan32PairCost = 4;           // its balanced split: what a segment costs a workgroup besides its tiles, in tiles
 constexpr int kScan32MinTilesMultiRound = 8; // its launches of several rounds: slices of a short sequence hold at least this many tiles
 constexpr size_t kMaxLds = 160 * 1024;
 
@@ -50,6 +51,8 @@ struct Layout {
     ssv_nsa_plan plan;
     int H_g, es;
     bool one_launch, unfused, scan32;
+    bool scan_balanced;          // matrix-core scan: equal ranges over the batch's tiles instead of even slices per group
+    int scan_ranges, scan_range_min;
     int imp_C, imp_n_qg, n_imp_chunks, imp_rw;   // importance pass: routed queries per workgroup, such workgroups per sequence, slices, blocks of 64 rows per workgroup
     int nc_pitch, max_blocks, bitmap_words, max_sched;
     size_t lds_stream, lds_k, lds_vt;
@@ -225,9 +228,25 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // (caps: the combine kernel's per-row slice loops; unfused: every branch is merged by thread groups that own rows)
     const int cap_c = unfused ? kCombineRowsMaxSlots : kMaxSlotsPerBranch, cap_ws = unfused ? kCombineRowsMaxSlots : 32;
     pl.n_cmp_chunks = std::min(std::max(1, ceil_div(ntc, per_c)), cap_c);
+    // The matrix-core scan of a batch of mixed lengths (the caller's average is below the maximum): one range of the
+    // batch's tile sequence per workgroup, about total / 256 tiles each; the lengths are read on the device, the
+    // average only sizes the slots: a pair of the longest sequence is cut by at most ceil(ntc / range) + 1 ranges, and
+    // the kernel never takes ranges shorter than scan_range_min (in tiles plus the fixed cost per pair), which keeps every
+    // pair within the slots there are.
+    lo->scan_balanced = false;
+    lo->scan_ranges = lo->scan_range_min = 0;
+    if (lo->scan32 && ntc_avg < ntc && p->B <= kScan32MaxBalancedB && (int64_t)p->B * p->H_kv * (ntc + kScan32PairCost) < (1ll << 30)) {
+        lo->scan_balanced = true;
+        lo->scan_ranges = std::max(1, kScan32Wgs / pl.n_qg_scan);
+        const int cost = ntc + kScan32PairCost;                      // of a pair of the longest sequence
+        const int range_est = std::max(1, ceil_div(p->B * p->H_kv * (ntc_avg + kScan32PairCost), lo->scan_ranges));
+        pl.n_cmp_chunks = std::min(std::max(2, ceil_div(cost, range_est) + 1), cap_c);
+        lo->scan_range_min = ceil_div(cost, pl.n_cmp_chunks - 1);
+        per_c = std::max(range_est, lo->scan_range_min);
+    }
     pl.n_win_splits = std::min(std::max(1, ceil_div(ntw, per_w)), cap_ws);
     pl.n_slc_splits = std::min(std::max(1, ceil_div(nts, per_s)), cap_ws);
-    pl.tiles_per_chunk = ceil_div(ntc, pl.n_cmp_chunks);
+    pl.tiles_per_chunk = lo->scan_balanced ? per_c : ceil_div(ntc, pl.n_cmp_chunks);
     pl.n_slots = pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits;
 
     lo->H_g = H_g;
@@ -419,7 +438,9 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
             for (const void* fn : fns)
                 if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStreamLds) != hipSuccess) return SSV_ELAUNCH;
             if constexpr (BF16) {
-                if (hipFuncSetAttribute((const void*)k_scan32<DK, DV>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                if (hipFuncSetAttribute((const void*)k_scan32<DK, DV, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)Scan32Cfg<DK, DV>::LDS) != hipSuccess ||
+                    hipFuncSetAttribute((const void*)k_scan32<DK, DV, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                         (int)Scan32Cfg<DK, DV>::LDS) != hipSuccess)
                     return SSV_ELAUNCH;
             }
@@ -466,14 +487,20 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
             ca.B = p->B; ca.T = p->T; ca.H = p->H; ca.H_kv = p->H_kv; ca.H_g = lo.H_g; ca.C = pl.C_scan; ca.n_qg = pl.n_qg_scan;
             ca.l = p->l; ca.d = p->d; ca.max_seq_len = p->max_seq_len; ca.max_n_cmp = p->max_n_cmp; ca.scale_log2 = scale_log2;
             ca.n_chunks = pl.n_cmp_chunks;
-            ca.n_wg = p->B * p->H_kv * pl.n_qg_scan * pl.n_cmp_chunks;
+            ca.n_ranges = lo.scan_ranges;
+            ca.range_min = lo.scan_range_min;
+            ca.pair_cost = kScan32PairCost;
+            ca.n_wg = lo.scan_balanced ? lo.scan_ranges * pl.n_qg_scan : p->B * p->H_kv * pl.n_qg_scan * pl.n_cmp_chunks;
             ca.min_tiles = ca.n_wg > kScan32Wgs ? kScan32MinTilesMultiRound : 1;
             ca.rows_total = lo.rows_total;
             for (int j = 0; j < 3; ++j) { ca.kc_s[j] = sa.kc_s[j]; ca.vc_s[j] = sa.vc_s[j]; ca.q_s[j] = lo.q_s[j]; }
             if (pl.C_scan * lo.H_g > Scan32Cfg<DK, DV>::ROWS) return -1;      // (cannot happen: make_layout bounds C_scan)
             const int grid = ceil_div(ca.n_wg, 8) * 8;
             if (tm.begin(SSV_K_STREAM_A)) return -1;
-            for (int r = 0; r < reps; ++r) SSV_LAUNCH_T(SSV_K_STREAM_A, (k_scan32<DK, DV>), grid, kScan32Threads, (Scan32Cfg<DK, DV>::LDS), ca);
+            for (int r = 0; r < reps; ++r) {
+                if (lo.scan_balanced) SSV_LAUNCH_T(SSV_K_STREAM_A, (k_scan32<DK, DV, true>), grid, kScan32Threads, (Scan32Cfg<DK, DV>::LDS), ca);
+                else SSV_LAUNCH_T(SSV_K_STREAM_A, (k_scan32<DK, DV, false>), grid, kScan32Threads, (Scan32Cfg<DK, DV>::LDS), ca);
+            }
             return (hipGetLastError() == hipSuccess && !tm.end(SSV_K_STREAM_A)) ? 0 : -1;
         } else {
             return -1;
@@ -774,3 +801,4 @@ const char* ssv_nsa_kernel_name(int idx) {
 int ssv_nsa_version(void) { return 2; }
 
 }  // extern "C"
+

@@ -18,7 +18,7 @@ def _to_device(arr: np.ndarray, dtype: str, device) -> torch.Tensor:
 
 class DeviceCase:
     def __init__(self, case, device="cuda:0", mode=B.SSV_REFRESH, group_size=0, scale=0.0, exec=B.SSV_EXEC_FUSED,
-                 topn_home=B.SSV_TOPN_AUTO, max_slice_tiles=0, imp_rows=0, strided_q_out=False, scan_kernel=B.SSV_SCAN_AUTO):
+                 topn_home=B.SSV_TOPN_AUTO, max_slice_tiles=0, imp_rows=0, strided_q_out=False, scan_kernel=B.SSV_SCAN_AUTO, avg_seq_len=None):
         if not torch.cuda.is_available():
             raise RuntimeError("DeviceCase needs a GPU: the NSA verification path has no CPU fallback")
         B.load_library()
@@ -58,7 +58,7 @@ class DeviceCase:
             l_sel=nsa.l_sel, n_sel=nsa.n_sel, w=nsa.w, n_init=nsa.n_init, n_local=nsa.n_local,
             dtype=B.SSV_BF16 if dt == "bf16" else B.SSV_F32, mode=mode, group_size=group_size, scale=scale,
             max_seq_len=int(case.seq_lens.max()), max_n_cmp=int(case.n_cmp.max()),
-            avg_seq_len=int(case.seq_lens.mean()),
+            avg_seq_len=int(case.seq_lens.mean()) if avg_seq_len is None else avg_seq_len,
             k_stride=self.k.stride()[:3], v_stride=self.v.stride()[:3],
             kc_stride=self.k_cmp.stride()[:3], vc_stride=self.v_cmp.stride()[:3], q_stride=q_stride, out_stride=out_stride,
             exec=exec, topn_home=topn_home, max_slice_tiles=max_slice_tiles, imp_rows=imp_rows, scan_kernel=scan_kernel)

@@ -526,6 +526,12 @@ def test_matrix_core_scan(dev_mod, oracle):
         dev_s, _, out_s, sel_s = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_STREAM)
         assert dev_s.plan.scan_matrix == 0
         assert np.array_equal(sel_s, sel), case.name            # the routing sees the same statistics up to rounding
+        if len(set(case.seq_lens.tolist())) > 1:
+            # sequences of different lengths took the balanced split (ranges over the whole batch); without the hint
+            # of the average length the same batch takes even slices per group: the same selections, outputs to tolerance
+            dev_e, _, out_e, sel_e = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_MATRIX, avg_seq_len=0)
+            assert dev_e.plan.scan_matrix == 1
+            assert np.array_equal(sel_e, sel), case.name
     run_shared(dev_mod, oracle, cases[0], 2, scan_kernel=B.SSV_SCAN_MATRIX)
     run_shared(dev_mod, oracle, cases[1], 3, scan_kernel=B.SSV_SCAN_MATRIX)
     # explicit scan grouping: 5 queries (80 rows) per workgroup of the scan, 2 per workgroup of the other branches
@@ -535,3 +541,33 @@ def test_matrix_core_scan(dev_mod, oracle):
     dev.run()
     out, sel = dev.results()
     check(cases[0], compare(cases[0], oracle, oracle.nsa_verify(cases[0]), out, sel))
+
+
+def test_matrix_core_scan_balanced_split(dev_mod, oracle):
+    """The matrix-core scan's split for batches of mixed lengths: the tiles of all (sequence, KV head) pairs laid end to
+    end and cut into equal ranges, a workgroup finishing one pair's state and starting the next.  Batches whose lengths
+    span two orders of magnitude, sequences without queries, without compressed rows and shorter than one tile between
+    long ones, an odd batch size, three query groups walking the same ranges (a tree of 40 nodes), ranges much longer
+    than the short sequences (a workgroup crosses several pairs) and much shorter than the long ones (a pair is cut into
+    many slices), against the oracle in refresh and reuse mode."""
+    from paper_2605_19893_amd import binding as B
+    tree = si.tree_parents((4, 3, 2), "bfs")
+    cases = [
+        si.make_case("bal_chain16", "bf16", 7, 16, 64, 4, 192, 128, si.STD_NSA, [300, 26000, 40, 5200, 900, 13000, 2100], 701, rho=0.6,
+                     n_query=[16, 16, 5, 0, 16, 9, 16], poison_pad=True),
+        si.make_case("bal_tree40", "bf16", 3, len(tree), 32, 2, 192, 128, si.STD_NSA, [1500, 21000, 6400], 703, rho=0.6, parents=tree),
+        si.make_case("bal_many_short", "bf16", 12, 16, 32, 2, 128, 128, si.STD_NSA,
+                     [260, 700, 330, 18000, 512, 96, 1300, 450, 15, 2000, 640, 800], 705, rho=0.4),
+        si.make_case("bal_hg4", "bf16", 3, 64, 32, 8, 64, 64, si.STD_NSA, [9000, 400, 3100], 707, rho=0.3, n_query=[64, 40, 64]),
+    ]
+    for case in cases:
+        dev, ref, out, sel = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_MATRIX)
+        assert dev.plan.scan_matrix == 1 and dev.plan.n_cmp_chunks >= 2
+        run_reuse(dev_mod, oracle, case, sel, dev=dev)
+        # the hint only sizes the slots: far below the true average (more slots than ranges cut), far above it (few slots:
+        # the kernel lengthens its ranges so that no pair needs more, and a range crosses several short pairs), equal
+        # to the maximum (even slices per group)
+        mx = int(case.seq_lens.max())
+        for hint in (mx // 16 + 1, int(mx * 0.9), mx):
+            dev_h, _, out_h, sel_h = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_MATRIX, avg_seq_len=hint)
+            assert np.array_equal(sel_h, sel), (case.name, hint)
