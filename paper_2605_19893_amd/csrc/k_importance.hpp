@@ -45,6 +45,8 @@ struct ImportanceArgs {
     float scale_log2;
     int n_cmp_chunks;          // slices of the compressed scan (partial statistics to merge)
     int n_imp_chunks;          // slices of this kernel's own pass over k_cmp
+    const int32_t* work_table; // k_importance32: (sequence, slice, slices) per item, written by the balanced scan of the
+                               // same call (k_scan32.hpp); null: every sequence is cut into n_imp_chunks slices
     int n_wg;
     int nc_pitch;
     int64_t rows_total;
@@ -479,9 +481,23 @@ k_importance32(const ImportanceArgs a) {
     const int wg = (blockIdx.x & 7) * (n_pad >> 3) + (blockIdx.x >> 3);
     if (wg >= a.n_wg) return;
     const int qg = wg % a.n_qg;
-    const int chunk = (wg / a.n_qg) % a.n_imp_chunks;
-    const int bg = wg / (a.n_qg * a.n_imp_chunks);
-    const int b = bg / a.H_kv, g = bg % a.H_kv;
+    int chunk, n_chunks, b, g;
+    if (a.work_table) {
+        // a batch of mixed lengths: item = (sequence, slice), then KV head, then query group
+        const int item = wg / (a.n_qg * a.H_kv);
+        if (item >= a.work_table[0]) return;
+        const int4 e = reinterpret_cast<const int4*>(a.work_table + 4)[item];
+        b = min(max(e.x, 0), a.B - 1);
+        chunk = e.y;
+        n_chunks = e.z;
+        g = (wg / a.n_qg) % a.H_kv;
+    } else {
+        chunk = (wg / a.n_qg) % a.n_imp_chunks;
+        n_chunks = a.n_imp_chunks;
+        const int bg = wg / (a.n_qg * a.n_imp_chunks);
+        b = bg / a.H_kv;
+        g = bg % a.H_kv;
+    }
 
     // A operands: row n of every row tile of this wavefront, all contraction steps.  When every query is routed the
     // rows are known before the sequence's metadata, and their loads overlap its latency (queries past the
@@ -522,7 +538,7 @@ k_importance32(const ImportanceArgs a) {
     for (int j = 0; j < nq_grp; ++j) cm = max(cm, s_cmax[s_qi[j]]);
     const int ntiles = (cm + kTile - 1) / kTile;
     int t0, t1;
-    even_slice(ntiles, a.n_imp_chunks, 1, chunk, t0, t1);
+    even_slice(ntiles, n_chunks, 1, chunk, t0, t1);
     if (t0 >= t1) return;       // (uniform; cm > 0 from here on, so the sequence has compressed rows)
 
     // Tiles of 64 compressed rows, rows past the last one repeating it (their probabilities are masked by the

@@ -53,12 +53,13 @@ struct Layout {
     bool one_launch, unfused, scan32;
     bool scan_balanced;          // matrix-core scan: equal ranges over the batch's tiles instead of even slices per group
     int scan_ranges, scan_range_min;
+    int imp_items_max;           // > 0: the importance pass takes its slices from the work table the balanced scan writes
     int imp_C, imp_n_qg, n_imp_chunks, imp_rw;   // importance pass: routed queries per workgroup, such workgroups per sequence, slices, blocks of 64 rows per workgroup
     int nc_pitch, max_blocks, bitmap_words, max_sched;
     size_t lds_stream, lds_k, lds_vt;
     int64_t rows_total;
     int64_t q_s[3], out_s[3];            // bytes
-    size_t off_stats, off_acc, off_colsum, off_branch, branch_bytes, total;
+    size_t off_stats, off_acc, off_colsum, off_branch, off_imp_table, branch_bytes, total;
 };
 
 // LDS tile sizes of the streaming kernel for a shape (they equal StreamCfg<...>::LDS_K / LDS_VT)
@@ -280,6 +281,13 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     }
     const int imp_units = p->B * p->H_kv * lo->imp_n_qg;
     lo->n_imp_chunks = std::max(1, std::min(ntc, std::max(1, kImportanceWgs / imp_units)));
+    // a refresh call behind the balanced scan: slices per sequence in proportion to its length, from the work table the
+    // scan writes (one round of about equally long workgroups; needs room for two items per sequence at least)
+    lo->imp_items_max = 0;
+    if (lo->scan_balanced && p->mode != SSV_REUSE) {
+        const int items = kImportanceWgs / (p->H_kv * lo->imp_n_qg);
+        if (items >= 2 * p->B) lo->imp_items_max = items;
+    }
     lo->es = es;
     lo->nc_pitch = (int)align_up((size_t)std::max(1, p->max_n_cmp), kTile);
     lo->max_blocks = max_blocks;
@@ -315,6 +323,8 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     lo->off_branch = off;
     lo->branch_bytes = align_up((size_t)lo->rows_total * p->d_v * es, 256);
     if (unfused) off += 3 * lo->branch_bytes;    // the three branch outputs, [rows, d_v] in the storage type
+    lo->off_imp_table = off;
+    if (lo->imp_items_max) off = align_up(off + imp_table_bytes(lo->imp_items_max), 256);
     lo->total = off;
     pl.workspace_bytes = (int64_t)off;
     return SSV_OK;
@@ -490,6 +500,8 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
             ca.n_ranges = lo.scan_ranges;
             ca.range_min = lo.scan_range_min;
             ca.pair_cost = kScan32PairCost;
+            ca.imp_items_max = lo.imp_items_max;
+            ca.imp_table = lo.imp_items_max ? reinterpret_cast<int32_t*>(ws + lo.off_imp_table) : nullptr;
             ca.n_wg = lo.scan_balanced ? lo.scan_ranges * pl.n_qg_scan : p->B * p->H_kv * pl.n_qg_scan * pl.n_cmp_chunks;
             ca.min_tiles = ca.n_wg > kScan32Wgs ? kScan32MinTilesMultiRound : 1;
             ca.rows_total = lo.rows_total;
@@ -518,6 +530,10 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
         ia.l = p->l; ia.d = p->d; ia.max_seq_len = p->max_seq_len; ia.max_n_cmp = p->max_n_cmp; ia.scale_log2 = scale_log2;
         ia.n_cmp_chunks = pl.n_cmp_chunks; ia.n_imp_chunks = lo.n_imp_chunks;
         ia.n_wg = p->B * p->H_kv * lo.imp_n_qg * lo.n_imp_chunks; ia.nc_pitch = lo.nc_pitch; ia.rows_total = lo.rows_total;
+        if (lo.imp_items_max) {
+            ia.work_table = reinterpret_cast<const int32_t*>(ws + lo.off_imp_table);
+            ia.n_wg = lo.imp_items_max * p->H_kv * lo.imp_n_qg;
+        }
         for (int j = 0; j < 3; ++j) { ia.kc_s[j] = sa.kc_s[j]; ia.q_s[j] = lo.q_s[j]; }
         const int grid_i = ceil_div(ia.n_wg, 8) * 8;
         if (tm.begin(SSV_K_IMPORTANCE)) return -1;

@@ -547,7 +547,7 @@ def test_matrix_core_scan_balanced_split(dev_mod, oracle):
     """The matrix-core scan's split for batches of mixed lengths: the tiles of all (sequence, KV head) pairs laid end to
     end and cut into equal ranges, a workgroup finishing one pair's state and starting the next.  Batches whose lengths
     span two orders of magnitude, sequences without queries, without compressed rows and shorter than one tile between
-    long ones, an odd batch size, three query groups walking the same ranges (a tree of 40 nodes), ranges much longer
+    long ones, a batch without any query, an odd batch size, three query groups walking the same ranges (a tree of 40 nodes), ranges much longer
     than the short sequences (a workgroup crosses several pairs) and much shorter than the long ones (a pair is cut into
     many slices), against the oracle in refresh and reuse mode."""
     from paper_2605_19893_amd import binding as B
@@ -559,11 +559,15 @@ def test_matrix_core_scan_balanced_split(dev_mod, oracle):
         si.make_case("bal_many_short", "bf16", 12, 16, 32, 2, 128, 128, si.STD_NSA,
                      [260, 700, 330, 18000, 512, 96, 1300, 450, 15, 2000, 640, 800], 705, rho=0.4),
         si.make_case("bal_hg4", "bf16", 3, 64, 32, 8, 64, 64, si.STD_NSA, [9000, 400, 3100], 707, rho=0.3, n_query=[64, 40, 64]),
+        si.make_case("bal_no_queries", "bf16", 2, 16, 32, 2, 192, 128, si.STD_NSA, [3000, 500], 709, rho=0.3, n_query=[0, 0]),
     ]
     for case in cases:
         dev, ref, out, sel = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_MATRIX)
         assert dev.plan.scan_matrix == 1 and dev.plan.n_cmp_chunks >= 2
         run_reuse(dev_mod, oracle, case, sel, dev=dev)
+        # the importance pass took its slices from the work table the scan wrote; with 256 rows per workgroup too
+        dev_w, _, out_w, sel_w = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_MATRIX, imp_rows=256)
+        assert np.array_equal(sel_w, sel), case.name
         # the hint only sizes the slots: far below the true average (more slots than ranges cut), far above it (few slots:
         # the kernel lengthens its ranges so that no pair needs more, and a range crosses several short pairs), equal
         # to the maximum (even slices per group)
