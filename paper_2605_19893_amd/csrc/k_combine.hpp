@@ -3,13 +3,14 @@
 // input dtype (round-to-nearest-even for bf16).
 //   o_branch = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) Z_s,   out = g_cmp o_cmp + g_slc o_slc + g_win o_win
 //
-// Two layouts.  k_combine_rows (few slices per row, many rows): a group of d_v/4 threads owns one output row (four
+// Three kernels.  k_combine_rows (few slices per row, many rows): a group of d_v/4 threads owns one output row (four
 // columns per thread), eight or sixteen rows per workgroup, no cross-thread reduction: every thread of the group
 // first folds the (m, Z) pairs of each branch's slices into the branch maximum and total (the loads of a group hit
-// the same addresses), then accumulates gate * 2^(m - M) / Z_total * partial accumulator over the slices, four
-// independent loads in flight.  k_combine_slices (many slices per row): one workgroup per output row; wavefronts
-// 0..2 each take one branch with one lane per slice (wave-wide max and sum), then all 256 threads accumulate
-// weight * partial accumulator, 256 / (d_v/4) slices in parallel, and a small LDS reduction produces the row.
+// the same addresses), then accumulates gate * 2^(m - M) / Z_total * partial accumulator over the slices;
+// k_combine_stream is its form for large calls (below).  k_combine_slices (many slices per row): one workgroup per
+// output row; wavefronts 0..2 each take one branch with one lane per slice (wave-wide max and sum), then all 256
+// threads accumulate weight * partial accumulator, 256 / (d_v/4) slices in parallel, and a small LDS reduction
+// produces the row.
 #pragma once
 #include "device_common.hpp"
 
@@ -40,10 +41,8 @@ constexpr int kMaxSlotsTotal = kMaxSlotsPerBranch + 32 + 32;
 
 constexpr int kCombineRowsMaxSlots = 16;   // slices per row up to which a thread group owns a row (k_combine_rows)
 
-// EAGER: every load is issued at once (one memory round trip: small, latency-bound calls); otherwise the statistics
-// come first and only the accumulators of slices that contributed are fetched (large calls are bound by the bytes
-// of the partial states, and a short sequence of a mixed batch leaves most of its slices empty).
-template <bool BF16, int DV, bool EAGER>
+// Every load is issued at once (one memory round trip: these calls are small and bound by latency).
+template <bool BF16, int DV>
 __global__ void __launch_bounds__(kThreads) k_combine_rows(const CombineArgs a) {
     constexpr int TPR = DV / 4;                 // threads across one row, 4 columns each
     constexpr int RPW = kThreads / TPR;         // rows per workgroup
@@ -63,9 +62,8 @@ __global__ void __launch_bounds__(kThreads) k_combine_rows(const CombineArgs a) 
     const int n_read = one_branch ? (a.br_lo == 0 ? cnt3[0] : (a.br_lo == 1 ? cnt3[1] : cnt3[2]))
                                   : a.n_cmp_chunks + a.n_win_splits + a.n_slc_splits;
 
-    // Everything this thread needs is fetched in one round of independent loads (EAGER: slices that contributed
-    // nothing never wrote their accumulator; whatever is read there is discarded by its zero weight), so the kernel
-    // costs one memory round trip, or two, instead of one per batch of slices.
+    // Everything this thread needs is fetched in one round of independent loads (slices that contributed nothing never
+    // wrote their accumulator; whatever is read there is discarded by its zero weight).
     float2 st[MS];
     f32x4 v[MS];
 #pragma unroll
@@ -75,14 +73,8 @@ __global__ void __launch_bounds__(kThreads) k_combine_rows(const CombineArgs a) 
         if (s < n_read) {              // uniform
             const int64_t pr = (int64_t)(base + s) * a.rows_total + row;
             st[s] = *reinterpret_cast<const float2*>(a.part_stats + pr * 2);
-            if constexpr (EAGER) v[s] = *reinterpret_cast<const f32x4*>(a.part_acc + pr * DV + c * 4);
+            v[s] = *reinterpret_cast<const f32x4*>(a.part_acc + pr * DV + c * 4);
         }
-    }
-    if constexpr (!EAGER) {
-#pragma unroll
-        for (int s = 0; s < MS; ++s)
-            if (s < n_read && st[s].y > 0.f)
-                v[s] = *reinterpret_cast<const f32x4*>(a.part_acc + ((int64_t)(base + s) * a.rows_total + row) * DV + c * 4);
     }
     const float g3[3] = {a.gates[row * 3 + 0], a.gates[row * 3 + 1], a.gates[row * 3 + 2]};
     const int Tq = a.n_query ? min(max(a.n_query[b], 0), a.T) : a.T;
@@ -116,6 +108,103 @@ __global__ void __launch_bounds__(kThreads) k_combine_rows(const CombineArgs a) 
         *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.out) + out_row_offset(a, row) + c * 8) = *reinterpret_cast<u32x2*>(h);
     } else {
         *reinterpret_cast<f32x4*>(reinterpret_cast<char*>(a.out) + out_row_offset(a, row) + c * 16) = acc;
+    }
+}
+
+// Large calls (partial states beyond the last-level cache): persistent workgroups over batches of rows.  Sixteen lanes
+// per row turn the (m, Z) pairs of the row's slices into one weight per slice, gate * 2^(m - M_branch) / Z_branch, through
+// lane exchanges; the weights go to LDS, and a group of d_v/4 threads per row then fetches only the accumulators with a
+// non-zero weight (a short sequence of a mixed batch leaves most of its slices empty) and sums them in slot order.  The
+// statistics of the next batch are fetched before the accumulators of the current one are summed, and become
+// weights after it: one memory round trip per batch instead of two, and no start-up per batch.
+template <bool BF16, int DV>
+__global__ void __launch_bounds__(kThreads) k_combine_stream(const CombineArgs a) {
+    constexpr int TPR = DV / 4;                 // threads across one row, 4 columns each
+    constexpr int RPW = kThreads / TPR;         // rows per batch
+    constexpr int MS = kCombineRowsMaxSlots;
+    static_assert(RPW * MS <= kThreads && MS == 16, "one lane per (row, slice) of a batch; 16-lane exchanges");
+    __shared__ float s_w[2][RPW][MS];
+    const int tid = threadIdx.x;
+    const int n_read = a.n_cmp_chunks + a.n_win_splits + a.n_slc_splits;
+    const int64_t n_batches = (a.rows_total + RPW - 1) / RPW;
+    // weight lanes: row wr of the batch, slice ws; its branch in gate order (compressed, selected, window)
+    const int wr = tid / MS, ws = tid % MS;
+    const bool wlane = tid < RPW * MS && ws < n_read;
+    const int wbr = ws < a.n_cmp_chunks ? 0 : (ws < a.n_cmp_chunks + a.n_win_splits ? 2 : 1);
+    struct Fetched { float2 st; float gate; bool live; };
+    auto fetch = [&](int64_t batch) {
+        Fetched f{make_float2(0.f, 0.f), 0.f, false};
+        const int64_t row = batch * RPW + wr;
+        if (wlane && batch < n_batches && row < a.rows_total) {
+            const int i = (int)((row / a.H) % a.T);
+            const int b = (int)(row / ((int64_t)a.H * a.T));
+            const int Tq = a.n_query ? min(max(a.n_query[b], 0), a.T) : a.T;
+            f.st = *reinterpret_cast<const float2*>(a.part_stats + ((int64_t)ws * a.rows_total + row) * 2);
+            f.gate = a.gates[row * 3 + wbr];
+            f.live = i < Tq;
+        }
+        return f;
+    };
+    auto weight = [&](const Fetched& f) {       // (all 64 lanes of a wavefront take part in the exchanges)
+        const bool valid = f.live && f.st.y > 0.f;
+        float w = 0.f;
+#pragma unroll
+        for (int br = 0; br < 3; ++br) {
+            const bool mine = valid && wbr == br;
+            float M = mine ? f.st.x : -INFINITY;
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+            const float e = mine ? fast_exp2(f.st.x - M) : 0.f;
+            float Zt = e * f.st.y;
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) Zt += __shfl_xor(Zt, off);
+            if (mine) w = f.gate * e / Zt;
+        }
+        return w;
+    };
+
+    int64_t batch = blockIdx.x;
+    if (batch >= n_batches) return;
+    if (tid < RPW * MS) s_w[0][wr][ws] = weight(fetch(batch));
+    __syncthreads();
+    const int r = tid / TPR, c = tid % TPR;
+    for (int buf = 0; batch < n_batches; batch += gridDim.x, buf ^= 1) {
+        const Fetched nxt = fetch(batch + gridDim.x);
+        __builtin_amdgcn_sched_barrier(0);      // the statistics of the next batch are on their way before anything below
+        const int64_t row = batch * RPW + r;
+        if (row < a.rows_total) {
+            // eight slices at a time: their loads in flight together (registers for all sixteen would cost a wavefront
+            // per SIMD)
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            const float* src = a.part_acc + row * DV + c * 4;
+            const int64_t slot_stride = a.rows_total * DV;
+#pragma unroll
+            for (int h = 0; h < MS; h += 8) {
+                if (h >= n_read) break;
+                float w[8];
+                f32x4 v[8];
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    w[s] = h + s < n_read ? s_w[buf][r][h + s] : 0.f;
+                    v[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (w[s] != 0.f) v[s] = *reinterpret_cast<const f32x4*>(src + (h + s) * slot_stride);
+                }
+#pragma unroll
+                for (int s = 0; s < 8; ++s)
+                    if (w[s] != 0.f) acc += w[s] * v[s];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (BF16) {
+                __bf16 h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) h[e] = (__bf16)acc[e];
+                *reinterpret_cast<u32x2*>(reinterpret_cast<char*>(a.out) + out_row_offset(a, row) + c * 8) = *reinterpret_cast<u32x2*>(h);
+            } else {
+                *reinterpret_cast<f32x4*>(reinterpret_cast<char*>(a.out) + out_row_offset(a, row) + c * 16) = acc;
+            }
+        }
+        if (tid < RPW * MS) s_w[buf ^ 1][wr][ws] = weight(nxt);
+        __syncthreads();
     }
 }
 

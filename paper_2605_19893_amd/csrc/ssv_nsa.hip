@@ -46,6 +46,7 @@ constexpr int kScan32MinTileSteps = 1024;    // ... when the launch has at least
 constexpr int kScan32PairCost = 4;           // its balanced split: what a segment costs a workgroup besides its tiles, in tiles
 constexpr int kScan32MinTilesMultiRound = 8; // its launches of several rounds: slices of a short sequence hold at least this many tiles
 constexpr size_t kMaxLds = 160 * 1024;
+constexpr int kCombineStreamWgs = 1024;       // resident workgroups of the streaming combine (four per CU)
 
 struct Layout {
     ssv_nsa_plan plan;
@@ -586,7 +587,7 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
             ba.out_s[0] = (int64_t)p->T * p->H * DV * es; ba.out_s[1] = (int64_t)p->H * DV * es; ba.out_s[2] = (int64_t)DV * es;
             ba.br_lo = br; ba.br_hi = br + 1; ba.use_gates = 0;
             if (tm.begin(K)) return -1;
-            for (int r = 0; r < reps; ++r) SSV_LAUNCH(K, (k_combine_rows<BF16, DV, true>), grid_rows, 0, ba);
+            for (int r = 0; r < reps; ++r) SSV_LAUNCH(K, (k_combine_rows<BF16, DV>), grid_rows, 0, ba);
             return (hipGetLastError() == hipSuccess && !tm.end(K)) ? 0 : -1;
         };
         if (launch_stream(SSV_K_STREAM_A, kRolesCmp, 0, pl.n_cmp_chunks, 1, p->T) || branch_out(SSV_K_OUT_CMP, 0)) return SSV_ELAUNCH;
@@ -618,12 +619,15 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     // few slices per row: thread groups own rows; many slices: one workgroup per row, slices in parallel
     // (13..16 slices: thread groups only where there are rows enough to fill the chip with them)
     const bool by_rows = pl.n_slots <= 12 || (pl.n_slots <= kCombineRowsMaxSlots && lo.rows_total >= 4096);
-    // partial states beyond the last-level cache: fetch statistics first, then only the accumulators that count
-    const bool eager = (int64_t)pl.n_slots * lo.rows_total * (DV + 2) * 4 <= (int64_t)64 << 20;
+    // partial states of tens of megabytes: the streaming form (statistics first, then only the accumulators that count)
+    const bool eager = (int64_t)pl.n_slots * lo.rows_total * (DV + 2) * 4 <= (int64_t)40 << 20;
+    // the streaming combine: persistent workgroups, every one the same number of batches of rows
+    const int n_batches = grid_rows, rounds = ceil_div(n_batches, kCombineStreamWgs);
+    const int grid_stream = ceil_div(n_batches, rounds);
     if (tm.begin(SSV_K_COMBINE)) return SSV_ELAUNCH;
     for (int r = 0; r < reps; ++r) {
-        if (by_rows && eager) SSV_LAUNCH(SSV_K_COMBINE, (k_combine_rows<BF16, DV, true>), grid_rows, 0, ca);
-        else if (by_rows) SSV_LAUNCH(SSV_K_COMBINE, (k_combine_rows<BF16, DV, false>), grid_rows, 0, ca);
+        if (by_rows && eager) SSV_LAUNCH(SSV_K_COMBINE, (k_combine_rows<BF16, DV>), grid_rows, 0, ca);
+        else if (by_rows) SSV_LAUNCH(SSV_K_COMBINE, (k_combine_stream<BF16, DV>), grid_stream, 0, ca);
         else SSV_LAUNCH(SSV_K_COMBINE, (k_combine_slices<BF16, DV>), (int)lo.rows_total, 0, ca);
     }
     if (hipGetLastError() != hipSuccess || tm.end(SSV_K_COMBINE)) return SSV_ELAUNCH;
