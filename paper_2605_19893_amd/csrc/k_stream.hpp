@@ -30,6 +30,7 @@ struct StreamArgs {
     float scale_log2;
     int n_cmp_chunks, n_win_splits, n_slc_splits, min_tiles;
     int slot_lo, slot_cnt;   // partial-state slots computed by this launch
+    int joint;               // <WIN|SLC> launch: > 0 = parts per group over window tiles and schedule entries together (below)
     int n_wg;                // real workgroups (the grid is padded to a multiple of 8)
     int max_sched, bitmap_words;
     int64_t rows_total;
@@ -85,6 +86,13 @@ __device__ __forceinline__ void even_slice(int n, int parts, int min_items, int 
 // launches <CMP|WIN> and then <SLC>, the reuse path launches all three at once, the unfused execution launches
 // each branch on its own, and <WIN|SLC> follows the matrix-core scan of the compressed cache (k_scan32.hpp); code of
 // absent roles is compiled out.
+//
+// Joint slicing (the <WIN|SLC> launch, joint = P > 0): the window tiles of a group and the entries of its merged schedule
+// form one list, window first, cut into P even parts; a workgroup takes one part, which may end the window and begin
+// the schedule.  It writes one state per branch: part j owns window slot j and selected slot j (slots
+// [n_cmp_chunks, + P) and [n_cmp_chunks + P, + P)); the state of a branch its part does not touch is marked empty.
+// Separate slices per branch leave the window's workgroup (9 tiles at w = 512) idle while the schedule's
+// (up to 32 tiles each) run on.
 constexpr int kRolesCmp = 1, kRolesWin = 2, kRolesCmpWin = 3, kRolesSlc = 4, kRolesWinSlc = 6, kRolesAll = 7;
 
 // Two workgroups per CU (the LDS of the full-size shapes allows no more), stated to the compiler as exactly two
@@ -123,13 +131,15 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
     const int bg = wg / (a.n_qg * a.slot_cnt);
     const int b = bg / a.H_kv, g = bg % a.H_kv;
 
+    const bool joint = ROLES == kRolesWinSlc && a.joint > 0;    // (uniform for the launch)
     int role, part;
-    if (slot < a.n_cmp_chunks) { role = ROLE_CMP; part = slot; }
+    if (joint) { role = ROLE_SLC; part = slot - a.slot_lo; }     // (the role of the first segment is set below)
+    else if (slot < a.n_cmp_chunks) { role = ROLE_CMP; part = slot; }
     else if (slot < a.n_cmp_chunks + a.n_win_splits) { role = ROLE_WIN; part = slot - a.n_cmp_chunks; }
     else { role = ROLE_SLC; part = slot - a.n_cmp_chunks - a.n_win_splits; }
     const bool r_cmp = (ROLES & 1) && role == ROLE_CMP;
-    const bool r_win = (ROLES & 2) && role == ROLE_WIN;
-    const bool r_slc = (ROLES & 4) && role == ROLE_SLC;
+    bool r_win = (ROLES & 2) && role == ROLE_WIN;
+    bool r_slc = (ROLES & 4) && role == ROLE_SLC;      // joint: true up to the schedule's construction, then per segment
 
     // ---- query fragments (B operand of S^T = K Q^T), kept in registers for the whole slice.  Their addresses need
     //      nothing from the sequence's metadata, so the loads go first and overlap the latency of everything below
@@ -202,6 +212,7 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
 
     // ---- tile range of this workgroup
     int t0 = 0, t1 = 0;           // CMP / WIN: tile indices; SLC: schedule entries
+    int jw0 = 0, jw1 = 0, js0 = 0, js1 = 0;      // joint slicing: both ranges
     if (nq_grp > 0) {
         if (r_cmp) {
             int cm = 0;
@@ -258,7 +269,20 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
             }
             __syncthreads();
             const int len = s_scalar[0];
-            even_slice(len, a.n_slc_splits, a.min_tiles, part, t0, t1);
+            if (!joint) even_slice(len, a.n_slc_splits, a.min_tiles, part, t0, t1);
+            else {
+                // this part of [window tiles | schedule entries]: its window tiles [jw0, jw1), its entries [js0, js1)
+                int dmin = 1 << 30;
+                for (int j = 0; j < nq_grp; ++j) dmin = min(dmin, s_depth[qg * a.C + j]);
+                const int wlo = max(0, L + dmin - a.w + 1) / kTile;
+                const int nw = (n_slots_kv + kTile - 1) / kTile - wlo;
+                int lo, hi;
+                even_slice(nw + len, a.joint, a.min_tiles, part, lo, hi);
+                jw0 = wlo + min(lo, nw);
+                jw1 = wlo + min(hi, nw);
+                js0 = max(lo, nw) - nw;
+                js1 = max(hi, nw) - nw;
+            }
         }
     }
 
@@ -281,13 +305,6 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
 
     f32x4 acc[NRT][MT];
     float mrun[NRT], zrun[NRT];
-#pragma unroll
-    for (int t = 0; t < NRT; ++t) {
-        mrun[t] = -INFINITY;
-        zrun[t] = 0.f;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[t][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
 
     const char* kbase;
     const char* vbase;
@@ -326,10 +343,7 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
     };
     kdir.init((uint32_t)krow, tid);
 #pragma unroll
-    for (int j = 0; j < AHEAD; ++j) {
-        vregs[j].init((uint32_t)vrow, tid);
-        if (t0 + j < t1) issue_tile(t0 + j, vregs[j]);
-    }
+    for (int j = 0; j < AHEAD; ++j) vregs[j].init((uint32_t)vrow, tid);
     // this lane's two base offsets into a K tile (row n of a 16-key tile, granule G of an even / odd 64-byte chunk)
     const int k_rb_e = DirectRowTile<Cfg::KROW>::read_base(n, G, 0), k_rb_o = DirectRowTile<Cfg::KROW>::read_base(n, G, 1);
     // wave-wide bounds for the "every key of the tile is valid for every row" fast path (rows that do not
@@ -542,25 +556,47 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
             }
         }
     };
-    for (int it = t0; it < t1; it += AHEAD) {
+    // One segment; joint slicing: the part's window tiles, then its schedule entries, a state for each.
+    int out_slot = slot;
+    for (int seg = 0; seg < (joint ? 2 : 1); ++seg) {
+        if (joint) {
+            r_win = seg == 0;
+            r_slc = seg == 1;
+            t0 = seg == 0 ? jw0 : js0;
+            t1 = seg == 0 ? jw1 : js1;
+            out_slot = a.n_cmp_chunks + seg * a.joint + part;
+            if (seg) __syncthreads();     // every wave has finished reading the window's last tile
+        }
+#pragma unroll
+        for (int t = 0; t < NRT; ++t) {
+            mrun[t] = -INFINITY;
+            zrun[t] = 0.f;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[t][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
 #pragma unroll
         for (int j = 0; j < AHEAD; ++j)
-            if (it + j < t1) tile_step(it + j, vregs[j]);
-    }
-
-    // ---- partial state of this slice: (m, Z) per row and the un-normalised accumulator
+            if (t0 + j < t1) issue_tile(t0 + j, vregs[j]);
+        for (int it = t0; it < t1; it += AHEAD) {
 #pragma unroll
-    for (int t = 0; t < NRT; ++t) {
-        if (!rvalid[t]) continue;
-        const int64_t pr = (int64_t)slot * a.rows_total + grow[t];
-        if (G == 0) {
-            a.part_stats[pr * 2 + 0] = mrun[t] * a.scale_log2;   // statistics leave the kernel in the log2 domain
-            a.part_stats[pr * 2 + 1] = zrun[t];
+            for (int j = 0; j < AHEAD; ++j)
+                if (it + j < t1) tile_step(it + j, vregs[j]);
         }
-        if (zrun[t] > 0.f) {
+
+        // ---- partial state of this slice: (m, Z) per row and the un-normalised accumulator
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                *reinterpret_cast<f32x4*>(a.part_acc + pr * DV + 16 * mt + 4 * G) = acc[t][mt];
+        for (int t = 0; t < NRT; ++t) {
+            if (!rvalid[t]) continue;
+            const int64_t pr = (int64_t)out_slot * a.rows_total + grow[t];
+            if (G == 0) {
+                a.part_stats[pr * 2 + 0] = mrun[t] * a.scale_log2;   // statistics leave the kernel in the log2 domain
+                a.part_stats[pr * 2 + 1] = zrun[t];
+            }
+            if (zrun[t] > 0.f) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    *reinterpret_cast<f32x4*>(a.part_acc + pr * DV + 16 * mt + 4 * G) = acc[t][mt];
+            }
         }
     }
 }

@@ -54,6 +54,7 @@ struct Layout {
     bool one_launch, unfused, scan32;
     bool scan_balanced;          // matrix-core scan: equal ranges over the batch's tiles instead of even slices per group
     int scan_ranges, scan_range_min;
+    int joint_parts;             // > 0: the <WIN|SLC> launch cuts window tiles and schedule entries of a group together
     int imp_items_max;           // > 0: the importance pass takes its slices from the work table the balanced scan writes
     int imp_C, imp_n_qg, n_imp_chunks, imp_rw;   // importance pass: routed queries per workgroup, such workgroups per sequence, slices, blocks of 64 rows per workgroup
     int nc_pitch, max_blocks, bitmap_words, max_sched;
@@ -217,8 +218,8 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
         // when that takes several rounds; window and selected blocks share the second launch
         const int spu = std::max(1, kScan32Wgs / units_scan);
         per_c = std::min(std::max(1, ceil_div(ntc_avg, spu)), long_slice);
-        const int tiles_b[2] = {ntw, nts};
-        per_w = per_s = tiles_per_slice(tiles_b, 2, units);
+        const int tiles_b = ntw + nts;      // (cut as one list: a part may end the window and begin the schedule)
+        per_w = per_s = tiles_per_slice(&tiles_b, 1, units);
     } else if (lo->one_launch) {
         const int tiles[3] = {ntc_avg, ntw, nts};
         per_c = per_w = per_s = tiles_per_slice(tiles, 3, units);
@@ -248,6 +249,23 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     }
     pl.n_win_splits = std::min(std::max(1, ceil_div(ntw, per_w)), cap_ws);
     pl.n_slc_splits = std::min(std::max(1, ceil_div(nts, per_s)), cap_ws);
+    lo->joint_parts = 0;
+    if (lo->scan32) {
+        // One round of resident workgroups: the parts of a group are cut over window tiles and schedule entries together,
+        // and every part owns a window slot and a selected slot (the one its tiles do not reach stays empty); measured
+        // 3 us faster at a 40-node tree over 128K tokens, where the window's own workgroup would sit idle for half the
+        // launch.  Several rounds fill such gaps by themselves (32 mixed-length sequences: 2 us slower): separate slices.
+        const int parts = std::min(std::max(1, ceil_div(ntw + nts, per_s)), kCombineRowsMaxSlots / 2);
+        if (units * parts <= kResidentWgs) {
+            lo->joint_parts = parts;
+            pl.n_win_splits = pl.n_slc_splits = parts;
+        } else {
+            const int tiles_b[2] = {ntw, nts};
+            per_w = per_s = tiles_per_slice(tiles_b, 2, units);
+            pl.n_win_splits = std::min(std::max(1, ceil_div(ntw, per_w)), cap_ws);
+            pl.n_slc_splits = std::min(std::max(1, ceil_div(nts, per_s)), cap_ws);
+        }
+    }
     pl.tiles_per_chunk = lo->scan_balanced ? per_c : ceil_div(ntc, pl.n_cmp_chunks);
     pl.n_slots = pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits;
 
@@ -305,7 +323,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // separate launch once the chip is full.
     const bool refresh = p->mode != SSV_REUSE;
     const bool fits = fused_topn_lds_bytes(max_blocks, pl.C, p->n_sel) <= lo->lds_k + lo->lds_vt;
-    const int n_wg_b = units * (pl.n_slc_splits + (lo->scan32 ? pl.n_win_splits : 0));
+    const int n_wg_b = units * (lo->joint_parts ? lo->joint_parts : pl.n_slc_splits + (lo->scan32 ? pl.n_win_splits : 0));
     pl.topn_in_slc = refresh && !unfused && fits &&
                      (p->topn_home == SSV_TOPN_IN_SLC || (p->topn_home == SSV_TOPN_AUTO && n_wg_b <= (pl.C <= 4 ? 2 : 1) * kTopnInSlcMaxWgs));
     pl.n_imp_chunks = refresh ? lo->n_imp_chunks : 0;
@@ -608,7 +626,10 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     if (lo.scan32) {
         if (launch_scan32()) return SSV_ELAUNCH;
         if (p->mode != SSV_REUSE && launch_routing()) return SSV_ELAUNCH;
-        if (launch_stream(SSV_K_STREAM_B, kRolesWinSlc, pl.n_cmp_chunks, pl.n_win_splits + pl.n_slc_splits, pl.C, pl.n_qg)) return SSV_ELAUNCH;
+        sa.joint = lo.joint_parts;
+        if (launch_stream(SSV_K_STREAM_B, kRolesWinSlc, pl.n_cmp_chunks, lo.joint_parts ? lo.joint_parts : pl.n_win_splits + pl.n_slc_splits, pl.C,
+                          pl.n_qg))
+            return SSV_ELAUNCH;
     } else if (lo.one_launch) {
         if (launch_stream(SSV_K_STREAM_A, kRolesAll, 0, pl.n_slots, pl.C, pl.n_qg)) return SSV_ELAUNCH;
     } else {

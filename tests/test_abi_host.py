@@ -132,6 +132,10 @@ def test_plan_fills_the_chip_and_respects_limits():
             # one round of one workgroup per CU, or several rounds of slices of at most 32 tiles
             assert 128 < wgs <= 256 or (wgs > 256 and pl.tiles_per_chunk <= 32), (name, wgs)
             assert pl.n_launches == (5 if name == "cfg4" else 4)
+            # behind the matrix-core scan the window shares the selected-branch launch: in one round of workgroups the
+            # parts of a group are cut over window tiles and schedule entries together (a slot of either branch per
+            # part), in several rounds each branch has slices of its own
+            assert (pl.n_win_splits, pl.n_slc_splits) == {"cfg3": (3, 3), "cfg4": (1, 2)}[name]
         else:
             wgs = units * (pl.n_cmp_chunks + pl.n_win_splits)
             # either one resident round (at most 2 workgroups per CU) or several rounds of slices of at most 32 tiles
