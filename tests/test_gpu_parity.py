@@ -575,3 +575,19 @@ def test_matrix_core_scan_balanced_split(dev_mod, oracle):
         for hint in (mx // 16 + 1, int(mx * 0.9), mx):
             dev_h, _, out_h, sel_h = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_MATRIX, avg_seq_len=hint)
             assert np.array_equal(sel_h, sel), (case.name, hint)
+
+
+def test_matrix_core_scan_large_batches(dev_mod, oracle):
+    """Batches beyond what the balanced split's tables take: 300 sequences (more than half the importance pass's work
+    table holds: that pass cuts every sequence the same way) and 1100 sequences (more than the scan's prefix array
+    holds: even slices per sequence), mixed lengths, against the oracle."""
+    from paper_2605_19893_amd import binding as B
+    rng = np.random.default_rng(907)
+    for nb in (300, 1100):
+        lens = rng.integers(20, 700, size=nb).tolist()
+        lens[3] = 5000
+        case = si.make_case(f"mscan_b{nb}", "bf16", nb, 3, 4, 2, 64, 64, si.STD_NSA, lens, 909 + nb, rho=0.3,
+                            n_query=rng.integers(0, 4, size=nb).tolist())
+        dev, ref, out, sel = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_MATRIX)
+        assert dev.plan.scan_matrix == 1
+        run_reuse(dev_mod, oracle, case, sel, dev=dev)
