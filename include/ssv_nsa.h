@@ -74,6 +74,9 @@ extern "C" {
 #define SSV_SCAN_STREAM 1     /* the streaming kernel (64 or 128 rows per workgroup, two workgroups per CU) */
 #define SSV_SCAN_MATRIX 2     /* the matrix-core scan (bf16 only: 256 rows per workgroup, one workgroup per CU; the window
                                  branch then runs in the selected-branch launch) */
+#define SSV_SCAN_STREAM_TABLE 3 /* the streaming kernel with its slices taken from a work table built on the device from
+                                 the lengths (what SSV_SCAN_AUTO and SSV_SCAN_STREAM do for long scans of mixed-length
+                                 batches), whenever the batch and the launch allow it (SSV_EXEC_FUSED only) */
 
 /* kernels of one call, in launch order (indices into kernel_ms of ssv_nsa_verify_timed) */
 #define SSV_K_STREAM_A  0     /* refresh: compressed scan + window;  reuse: compressed + window (+ selected, unless
@@ -132,8 +135,9 @@ typedef struct ssv_nsa_params {
     int32_t imp_rows;     /* rows (routed queries x heads of a group) per workgroup in the importance pass of a refresh
                              call: 64, 128 or 256; 0 = automatic (more than 64 where a KV head has that many rows and
                              the pass runs for several tiles per workgroup); never changes the result */
-    int32_t scan_kernel;  /* SSV_SCAN_AUTO, SSV_SCAN_STREAM or SSV_SCAN_MATRIX (SSV_EXEC_FUSED, SSV_BF16 only; with it
-                             scan_group_size may reach 256 / H_g); never changes the result beyond rounding */
+    int32_t scan_kernel;  /* SSV_SCAN_AUTO, SSV_SCAN_STREAM, SSV_SCAN_STREAM_TABLE or SSV_SCAN_MATRIX (SSV_EXEC_FUSED,
+                             SSV_BF16 only; with it scan_group_size may reach 256 / H_g); never changes the result
+                             beyond rounding */
 } ssv_nsa_params;
 
 /* How one call is cut into workgroups (host-side planning; filled by ssv_nsa_plan). */

@@ -24,7 +24,7 @@ SSV_NUM_KERNELS = 9
 SSV_T_EVENT_PAIR, SSV_NUM_TIMINGS = 9, 10
 SSV_EXEC_FUSED, SSV_EXEC_UNFUSED = 0, 1
 SSV_TOPN_AUTO, SSV_TOPN_SEPARATE, SSV_TOPN_IN_SLC = 0, 1, 2
-SSV_SCAN_AUTO, SSV_SCAN_STREAM, SSV_SCAN_MATRIX = 0, 1, 2
+SSV_SCAN_AUTO, SSV_SCAN_STREAM, SSV_SCAN_MATRIX, SSV_SCAN_STREAM_TABLE = 0, 1, 2, 3
 
 EXPORTS = ("ssv_nsa_verify", "ssv_nsa_verify_static", "ssv_nsa_verify_timed", "ssv_nsa_plan_query", "ssv_nsa_workspace_bytes",
            "ssv_nsa_supported", "ssv_nsa_strerror", "ssv_nsa_kernel_name", "ssv_nsa_version", "ssv_nsa_compress",

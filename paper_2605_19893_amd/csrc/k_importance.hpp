@@ -29,6 +29,7 @@
 // of a ring slot against its readers.
 #pragma once
 #include "k_stream.hpp"
+#include "work_table.hpp"
 
 namespace ssv {
 
@@ -45,8 +46,8 @@ struct ImportanceArgs {
     float scale_log2;
     int n_cmp_chunks;          // slices of the compressed scan (partial statistics to merge)
     int n_imp_chunks;          // slices of this kernel's own pass over k_cmp
-    const int32_t* work_table; // k_importance32: (sequence, slice, slices) per item, written by the balanced scan of the
-                               // same call (k_scan32.hpp); null: every sequence is cut into n_imp_chunks slices
+    const int32_t* work_table; // k_importance32: (sequence, slice, slices) per item (work_table.hpp), built earlier in the
+                               // same call; null: every sequence is cut into n_imp_chunks slices
     int n_wg;
     int nc_pitch;
     int64_t rows_total;
@@ -484,12 +485,7 @@ k_importance32(const ImportanceArgs a) {
     int chunk, n_chunks, b, g;
     if (a.work_table) {
         // a batch of mixed lengths: item = (sequence, slice), then KV head, then query group
-        const int item = wg / (a.n_qg * a.H_kv);
-        if (item >= a.work_table[0]) return;
-        const int4 e = reinterpret_cast<const int4*>(a.work_table + 4)[item];
-        b = min(max(e.x, 0), a.B - 1);
-        chunk = e.y;
-        n_chunks = e.z;
+        if (!work_table_item(a.work_table, wg / (a.n_qg * a.H_kv), a.B, b, chunk, n_chunks)) return;
         g = (wg / a.n_qg) % a.H_kv;
     } else {
         chunk = (wg / a.n_qg) % a.n_imp_chunks;

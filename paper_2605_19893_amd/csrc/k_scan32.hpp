@@ -27,6 +27,7 @@
 // Output: one partial softmax state per row and slice, in the format of the streaming kernel (k_stream.hpp).
 #pragma once
 #include "k_stream.hpp"
+#include "work_table.hpp"
 
 namespace ssv {
 
@@ -45,7 +46,7 @@ struct Scan32Args {
     int n_ranges, range_min;      // balanced: ranges (n_wg = n_ranges * n_qg); shortest range that keeps every
                                   // (sequence, KV head) pair within n_chunks slices
     int pair_cost;                // balanced: what a segment costs besides its tiles, in tiles
-    int32_t* imp_table;           // balanced, refresh calls: work table of the importance pass (below), or null
+    int32_t* imp_table;           // balanced, refresh calls: work table of the importance pass (work_table.hpp), or null
     int imp_items_max;            // its capacity in items (at least twice the batch size)
     int64_t rows_total;
     int64_t kc_s[3], vc_s[3];     // strides in bytes: sequence, KV head, row
@@ -69,14 +70,6 @@ struct Scan32Cfg {
 };
 
 constexpr float kScan32RaiseLog2 = 8.f;   // the reference maximum is raised when a tile's maximum exceeds it by more (log2 units)
-
-// Work table of the importance pass for a batch of mixed lengths, written by one workgroup of the balanced scan (it has
-// the batch's tile counts in LDS anyway; the importance pass is the next launch of the stream).  Sequence b with n_b
-// tiles gets k_b = ceil(n_b / p) slices, p = total tiles / (imp_items_max - sequences), so that the slices of all
-// sequences number at most imp_items_max: one round of equally long workgroups there too.  Layout (int32): [0] = number of items, [4 + 4 i ..] =
-// (sequence, slice, slices of that sequence, 0) of item i, items in sequence order.
-constexpr int kImpTableHeader = 4;
-__host__ __device__ inline size_t imp_table_bytes(int items_max) { return (size_t)(kImpTableHeader + 4 * items_max) * sizeof(int32_t); }
 
 // BAL: the balanced split (the even split's instantiation has no segment loop)
 template <int DK, int DV, bool BAL>
@@ -166,47 +159,8 @@ __global__ void __launch_bounds__(kScan32Threads, 1) __attribute__((amdgpu_waves
 
         // (written by the last range that has work, the one most likely to have time; by the first if the batch has none)
         if (a.imp_table && range_id == max(W - 1, 0) / range_len && qg == 0) {
-            auto block_sum = [&](int v) {
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-                __syncthreads();        // s_wsum is free
-                if (lane == 0) s_wsum[wave] = v;
-                __syncthreads();
-                int t = 0;
-                for (int w = 0; w < kScan32Threads / 64; ++w) t += s_wsum[w];
-                return t;
-            };
-            const int t0b = n0 > 0 ? n0 - pc : 0, t1b = n1 > 0 ? n1 - pc : 0;       // tiles of this thread's two sequences
-            const int Wb = block_sum(t0b + t1b), active = block_sum((n0 > 0) + (n1 > 0));
-            // k_b = ceil(n_b D / Wb) with D = imp_items_max - active: slices of at most Wb / D tiles, and
-            // sum_b k_b <= D + active = imp_items_max (integers: the bound is exact)
-            const int D = max(1, a.imp_items_max - active);
-            auto slices = [&](int tiles) { return tiles > 0 ? (int)(((int64_t)tiles * D + Wb - 1) / Wb) : 0; };
-            const int k0 = min(slices(t0b), a.imp_items_max), k1 = min(slices(t1b), a.imp_items_max);
-            int inc = k0 + k1;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int up = __shfl_up(inc, off);
-                if (lane >= off) inc += up;
-            }
-            __syncthreads();
-            if (lane == 63) s_wsum[wave] = inc;
-            __syncthreads();
-            int start = inc - (k0 + k1), total = 0;
-            for (int w = 0; w < kScan32Threads / 64; ++w) {
-                if (w < wave) start += s_wsum[w];
-                total += s_wsum[w];
-            }
-            // (the total stays within the capacity whenever the batch has fewer sequences than there are items: the host
-            // asks for twice as many; the bound below only guards the table)
-            for (int i = 0; i < k0 + k1; ++i) {
-                const int item = start + i;
-                if (item >= a.imp_items_max) break;
-                const int second = i >= k0;
-                reinterpret_cast<int4*>(a.imp_table + kImpTableHeader)[item] =
-                    make_int4(2 * tid + second, second ? i - k0 : i, second ? k1 : k0, 0);
-            }
-            if (tid == 0) a.imp_table[0] = min(total, a.imp_items_max);
+            const int tiles2[2] = {n0 > 0 ? n0 - pc : 0, n1 > 0 ? n1 - pc : 0};     // tiles of this thread's two sequences
+            block_build_work_table<kScan32Threads, 2>(tiles2, a.imp_items_max, 1 << 30, a.imp_table, s_wsum, tid);
         }
         if (x >= W) return;                           // (uniform) fewer ranges than workgroups
     }

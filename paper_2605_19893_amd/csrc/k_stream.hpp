@@ -17,6 +17,7 @@
 #pragma once
 #include "device_common.hpp"
 #include "k_topn.hpp"
+#include "work_table.hpp"
 
 namespace ssv {
 
@@ -30,6 +31,8 @@ struct StreamArgs {
     float scale_log2;
     int n_cmp_chunks, n_win_splits, n_slc_splits, min_tiles;
     int slot_lo, slot_cnt;   // partial-state slots computed by this launch
+    const int32_t* cmp_table; // launches with the compressed scan: its work table (below), or null
+    int cmp_items_max;       // capacity of that table in items
     int joint;               // <WIN|SLC> launch: > 0 = parts per group over window tiles and schedule entries together (below)
     int n_wg;                // real workgroups (the grid is padded to a multiple of 8)
     int max_sched, bitmap_words;
@@ -87,6 +90,13 @@ __device__ __forceinline__ void even_slice(int n, int parts, int min_items, int 
 // each branch on its own, and <WIN|SLC> follows the matrix-core scan of the compressed cache (k_scan32.hpp); code of
 // absent roles is compiled out.
 //
+// Work table of the compressed scan (cmp_table, batches of mixed lengths; work_table.hpp): the scan's workgroups come
+// first in the launch, cmp_items_max * H_kv * n_qg of them, and take (sequence, slice, slices) from the table: slices per
+// sequence in proportion to its length, all of about the same length.  Slice j of a sequence owns compressed slot j;
+// the last slice marks the slots beyond the sequence's slices as empty.  The workgroups of the other branches follow,
+// cut as always.  Workgroup ids go round-robin over the XCDs here (the groups of one slice stay together): the slices
+// are equally long, so an equal count per XCD is what balances them.
+//
 // Joint slicing (the <WIN|SLC> launch, joint = P > 0): the window tiles of a group and the entries of its merged schedule
 // form one list, window first, cut into P even parts; a workgroup takes one part, which may end the window and begin
 // the schedule.  It writes one state per branch: part j owns window slot j and selected slot j (slots
@@ -124,12 +134,37 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
     // contiguous range of logical work items; the query groups of one (sequence, head, slice), which
     // read the same tiles, are adjacent in logical order and therefore share an L2.
     const int n_pad = gridDim.x;
-    const int wg = (blockIdx.x & 7) * (n_pad >> 3) + (blockIdx.x >> 3);
-    if (wg >= a.n_wg) return;
-    const int qg = wg % a.n_qg;
-    const int slot = a.slot_lo + (wg / a.n_qg) % a.slot_cnt;
-    const int bg = wg / (a.n_qg * a.slot_cnt);
-    const int b = bg / a.H_kv, g = bg % a.H_kv;
+    int wg, qg, slot, b, g;
+    int cmp_parts = 0;            // work table: slices of this sequence's compressed rows (0: the launch-wide count)
+    bool from_table = false;
+    if constexpr (ROLES & 1) from_table = a.cmp_table != nullptr;     // (uniform for the launch)
+    if (from_table) {
+        // the n_qg groups of a slice stay adjacent on one XCD, consecutive slices go to consecutive XCDs
+        const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
+        wg = ((j / a.n_qg) * 8 + x) * a.n_qg + j % a.n_qg;
+        if (wg >= a.n_wg) return;
+        qg = wg % a.n_qg;
+        const int n_tab = a.cmp_items_max * a.H_kv * a.n_qg;
+        if (wg < n_tab) {
+            g = (wg / a.n_qg) % a.H_kv;
+            if (!work_table_item(a.cmp_table, wg / (a.n_qg * a.H_kv), a.B, b, slot, cmp_parts)) return;
+            slot = min(max(slot, 0), a.n_cmp_chunks - 1);
+        } else {
+            const int rest = a.slot_cnt - a.n_cmp_chunks, w2 = wg - n_tab;      // the other branches' slots of this launch
+            slot = a.slot_lo + a.n_cmp_chunks + (w2 / a.n_qg) % rest;
+            const int bg = w2 / (a.n_qg * rest);
+            b = bg / a.H_kv;
+            g = bg % a.H_kv;
+        }
+    } else {
+        wg = (blockIdx.x & 7) * (n_pad >> 3) + (blockIdx.x >> 3);
+        if (wg >= a.n_wg) return;
+        qg = wg % a.n_qg;
+        slot = a.slot_lo + (wg / a.n_qg) % a.slot_cnt;
+        const int bg = wg / (a.n_qg * a.slot_cnt);
+        b = bg / a.H_kv;
+        g = bg % a.H_kv;
+    }
 
     const bool joint = ROLES == kRolesWinSlc && a.joint > 0;    // (uniform for the launch)
     int role, part;
@@ -218,7 +253,7 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
             int cm = 0;
             for (int j = 0; j < nq_grp; ++j) cm = max(cm, s_cmax[qg * a.C + j]);
             const int ntiles = (cm + kTile - 1) / kTile;
-            even_slice(ntiles, a.n_cmp_chunks, a.min_tiles, part, t0, t1);
+            even_slice(ntiles, cmp_parts ? cmp_parts : a.n_cmp_chunks, a.min_tiles, part, t0, t1);
         } else if (r_win) {
             int dmin = 1 << 30;
             for (int j = 0; j < nq_grp; ++j) dmin = min(dmin, s_depth[qg * a.C + j]);
@@ -591,6 +626,11 @@ __global__ void __launch_bounds__(kThreads, 2) __attribute__((amdgpu_waves_per_e
             if (G == 0) {
                 a.part_stats[pr * 2 + 0] = mrun[t] * a.scale_log2;   // statistics leave the kernel in the log2 domain
                 a.part_stats[pr * 2 + 1] = zrun[t];
+                // work table: the sequence's last slice marks the compressed slots beyond its slices as empty
+                if (r_cmp && cmp_parts && part == cmp_parts - 1) {
+                    for (int sl = cmp_parts; sl < a.n_cmp_chunks; ++sl)
+                        *reinterpret_cast<float2*>(a.part_stats + ((int64_t)sl * a.rows_total + grow[t]) * 2) = make_float2(0.f, 0.f);
+                }
             }
             if (zrun[t] > 0.f) {
 #pragma unroll

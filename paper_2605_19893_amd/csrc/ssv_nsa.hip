@@ -15,6 +15,7 @@
 #include "k_stream.hpp"
 #include "k_topn.hpp"
 #include "planner.hpp"
+#include "work_table.hpp"
 
 // Scratch of ssv_nsa_verify_static: one copy per GPU inside the library's device image.  In host code this name is
 // only a handle for hipGetSymbolAddress; the device address it resolves to is what kernels and copies are given.
@@ -43,6 +44,7 @@ constexpr size_t kMaxStreamLds = 80 * 1024;  // two workgroups per CU
 constexpr int kScan32Wgs = 256;              // the matrix-core scan: one workgroup per CU
 constexpr int kScan32MinRows = 192;          // SSV_SCAN_AUTO: rows per (sequence, KV head) from which it is used ...
 constexpr int kScan32MinTileSteps = 1024;    // ... when the launch has at least this many tile steps (four per CU)
+constexpr int kTableMinTileSteps = 4096;     // the streaming scan of a mixed-length batch: tile steps from which a work table pays for its launch
 constexpr int kScan32PairCost = 4;           // its balanced split: what a segment costs a workgroup besides its tiles, in tiles
 constexpr int kScan32MinTilesMultiRound = 8; // its launches of several rounds: slices of a short sequence hold at least this many tiles
 constexpr size_t kMaxLds = 160 * 1024;
@@ -54,6 +56,8 @@ struct Layout {
     bool one_launch, unfused, scan32;
     bool scan_balanced;          // matrix-core scan: equal ranges over the batch's tiles instead of even slices per group
     int scan_ranges, scan_range_min;
+    int cmp_items_max;           // > 0: the streaming kernel's compressed scan takes its slices from a work table (k_work_table)
+    bool table_kernel;           // the call starts with k_work_table
     int joint_parts;             // > 0: the <WIN|SLC> launch cuts window tiles and schedule entries of a group together
     int imp_items_max;           // > 0: the importance pass takes its slices from the work table the balanced scan writes
     int imp_C, imp_n_qg, n_imp_chunks, imp_rw;   // importance pass: routed queries per workgroup, such workgroups per sequence, slices, blocks of 64 rows per workgroup
@@ -61,7 +65,7 @@ struct Layout {
     size_t lds_stream, lds_k, lds_vt;
     int64_t rows_total;
     int64_t q_s[3], out_s[3];            // bytes
-    size_t off_stats, off_acc, off_colsum, off_branch, off_imp_table, branch_bytes, total;
+    size_t off_stats, off_acc, off_colsum, off_branch, off_imp_table, off_cmp_table, branch_bytes, total;
 };
 
 // LDS tile sizes of the streaming kernel for a shape (they equal StreamCfg<...>::LDS_K / LDS_VT)
@@ -85,9 +89,10 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     if (p->topn_home != SSV_TOPN_AUTO && p->topn_home != SSV_TOPN_SEPARATE && p->topn_home != SSV_TOPN_IN_SLC) return SSV_EINVAL;
     if (p->max_slice_tiles != 0 && (p->max_slice_tiles < 2 || p->max_slice_tiles > 64)) return SSV_EINVAL;
     if (p->imp_rows != 0 && p->imp_rows != 64 && p->imp_rows != 128 && p->imp_rows != 256) return SSV_EINVAL;
-    if (p->scan_kernel != SSV_SCAN_AUTO && p->scan_kernel != SSV_SCAN_STREAM && p->scan_kernel != SSV_SCAN_MATRIX) return SSV_EINVAL;
+    if (p->scan_kernel < SSV_SCAN_AUTO || p->scan_kernel > SSV_SCAN_STREAM_TABLE) return SSV_EINVAL;
     const bool unfused = p->exec == SSV_EXEC_UNFUSED;
     if (p->scan_kernel == SSV_SCAN_MATRIX && (unfused || p->dtype != SSV_BF16)) return SSV_EINVAL;
+    if (p->scan_kernel == SSV_SCAN_STREAM_TABLE && unfused) return SSV_EINVAL;
     if (unfused && (p->mode == SSV_REFRESH_SHARED || p->group_size > 1 || p->scan_group_size > 1)) return SSV_EINVAL;
     const int H_g = p->H / p->H_kv;
     if (p->T > SSV_MAX_T) return SSV_EUNSUPPORTED;
@@ -266,6 +271,24 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
             pl.n_slc_splits = std::min(std::max(1, ceil_div(nts, per_s)), cap_ws);
         }
     }
+    // The streaming kernel's compressed scan of a batch of mixed lengths: slices per sequence in proportion to its length,
+    // from a work table that a one-workgroup kernel builds from the device-resident lengths at the start of the call
+    // (work_table.hpp).  One round: the resident workgroups that the launch's other branches leave, at least two items
+    // per sequence; the slots per row bound the slices of the longest sequence (sized from the average, enforced by the
+    // table).  Only where the scan is long enough for the extra launch (about 4 us) to pay.
+    lo->cmp_items_max = 0;
+    const bool force_table = p->scan_kernel == SSV_SCAN_STREAM_TABLE;
+    if (!unfused && !lo->scan32 && p->B <= kWorkTableMaxB &&
+        (force_table || (ntc_avg < ntc && (int64_t)units_scan * ntc_avg >= kTableMinTileSteps))) {
+        const int others = units_scan * (pl.n_win_splits + (lo->one_launch ? pl.n_slc_splits : 0));
+        const int items = (kResidentWgs - others) / (p->H_kv * pl.n_qg_scan);
+        if (items >= 2 * p->B) {
+            lo->cmp_items_max = items;
+            const int64_t total_est = (int64_t)p->B * ntc_avg;
+            pl.n_cmp_chunks = (int)std::min<int64_t>(cap_c, std::max<int64_t>(1, ((int64_t)ntc * (items - p->B) + total_est - 1) / total_est + 1));
+            per_c = ceil_div(ntc, pl.n_cmp_chunks);
+        }
+    }
     pl.tiles_per_chunk = lo->scan_balanced ? per_c : ceil_div(ntc, pl.n_cmp_chunks);
     pl.n_slots = pl.n_cmp_chunks + pl.n_win_splits + pl.n_slc_splits;
 
@@ -300,13 +323,15 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     }
     const int imp_units = p->B * p->H_kv * lo->imp_n_qg;
     lo->n_imp_chunks = std::max(1, std::min(ntc, std::max(1, kImportanceWgs / imp_units)));
-    // a refresh call behind the balanced scan: slices per sequence in proportion to its length, from the work table the
-    // scan writes (one round of about equally long workgroups; needs room for two items per sequence at least)
+    // a refresh call of a mixed-length batch: slices per sequence in proportion to its length, from the work table that
+    // the balanced scan or the table kernel writes (one round of about equally long workgroups; needs room for two
+    // items per sequence at least; the 32x32x16 kernel only)
     lo->imp_items_max = 0;
-    if (lo->scan_balanced && p->mode != SSV_REUSE) {
+    if ((lo->scan_balanced || (lo->cmp_items_max && p->dtype == SSV_BF16)) && p->mode != SSV_REUSE) {
         const int items = kImportanceWgs / (p->H_kv * lo->imp_n_qg);
         if (items >= 2 * p->B) lo->imp_items_max = items;
     }
+    lo->table_kernel = lo->cmp_items_max > 0;      // (it builds the importance pass's table too)
     lo->es = es;
     lo->nc_pitch = (int)align_up((size_t)std::max(1, p->max_n_cmp), kTile);
     lo->max_blocks = max_blocks;
@@ -329,7 +354,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     pl.n_imp_chunks = refresh ? lo->n_imp_chunks : 0;
     pl.imp_rows = refresh ? 64 * lo->imp_rw : 0;
     if (unfused) pl.n_launches = refresh ? 9 : 7;
-    else pl.n_launches = (lo->one_launch ? 1 : 2) + (refresh ? 1 + !pl.topn_in_slc : 0) + 1;
+    else pl.n_launches = (lo->one_launch ? 1 : 2) + (refresh ? 1 + !pl.topn_in_slc : 0) + 1 + (lo->table_kernel ? 1 : 0);
     pl.scan_matrix = lo->scan32;
     lo->rows_total = (int64_t)p->B * p->T * p->H;
     size_t off = 0;
@@ -343,7 +368,9 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     lo->branch_bytes = align_up((size_t)lo->rows_total * p->d_v * es, 256);
     if (unfused) off += 3 * lo->branch_bytes;    // the three branch outputs, [rows, d_v] in the storage type
     lo->off_imp_table = off;
-    if (lo->imp_items_max) off = align_up(off + imp_table_bytes(lo->imp_items_max), 256);
+    if (lo->imp_items_max) off = align_up(off + work_table_bytes(lo->imp_items_max), 256);
+    lo->off_cmp_table = off;
+    if (lo->cmp_items_max) off = align_up(off + work_table_bytes(lo->cmp_items_max), 256);
     lo->total = off;
     pl.workspace_bytes = (int64_t)off;
     return SSV_OK;
@@ -482,11 +509,25 @@ int launch_all(const void* q, const void* k, const void* v, const void* kc, cons
     auto launch_stream = [&](int K, int roles, int slot_lo, int slot_cnt, int C, int n_qg) -> int {
         sa.C = C; sa.n_qg = n_qg;
         sa.slot_lo = slot_lo; sa.slot_cnt = slot_cnt; sa.n_wg = p->B * p->H_kv * n_qg * slot_cnt;
+        // the compressed scan from its work table: its workgroups first, then those of the launch's other branches
+        const bool tabled = lo.cmp_items_max > 0 && (roles & 1);
+        sa.cmp_table = tabled ? reinterpret_cast<const int32_t*>(ws + lo.off_cmp_table) : nullptr;
+        sa.cmp_items_max = lo.cmp_items_max;
+        if (tabled) sa.n_wg = (lo.cmp_items_max + p->B * (slot_cnt - pl.n_cmp_chunks)) * p->H_kv * n_qg;
         // A launch of several rounds of workgroups gains nothing from cutting a short sequence into slices of one
         // or two tiles: every slice pays the start-up of a workgroup and leaves a partial state to merge.
         sa.min_tiles = sa.n_wg > kResidentWgs ? kMinTilesMultiRound : 1;
-        const int grid = ceil_div(sa.n_wg, 8) * 8;
+        const int grid = tabled ? ceil_div(sa.n_wg, 8 * n_qg) * 8 * n_qg : ceil_div(sa.n_wg, 8) * 8;
         if (tm.begin(K)) return -1;
+        if (tabled) {
+            WorkTableArgs wa{};
+            wa.n_cmp = n_cmp; wa.n_query = n_query; wa.B = p->B; wa.T = p->T; wa.max_n_cmp = p->max_n_cmp;
+            wa.scan_table = reinterpret_cast<int32_t*>(ws + lo.off_cmp_table);
+            wa.scan_items_max = lo.cmp_items_max; wa.scan_slices_cap = pl.n_cmp_chunks;
+            wa.imp_table = lo.imp_items_max ? reinterpret_cast<int32_t*>(ws + lo.off_imp_table) : nullptr;
+            wa.imp_items_max = lo.imp_items_max;
+            hipLaunchKernelGGL(k_work_table, dim3(1), dim3(kThreads), 0, stream, wa);
+        }
         for (int r = 0; r < reps; ++r) {
 #define SSV_LAUNCH_STREAM(NRT_, ROLES_) SSV_LAUNCH(K, (k_stream<BF16, DK, DV, NRT_, ROLES_>), grid, lds_stream, sa)
             if (C * lo.H_g > 64) {

@@ -163,12 +163,21 @@ def test_plan_fills_the_chip_and_respects_limits():
     assert (pl.C, pl.n_qg, pl.C_scan, pl.n_qg_scan, pl.scan_matrix) == (4, 3, 12, 1, 1)
     pl = B.ssv_nsa_plan_query(std_params(B=32, T=12, max_seq_len=131072, max_n_cmp=8191, scan_kernel=B.SSV_SCAN_STREAM))
     assert (pl.C, pl.n_qg, pl.C_scan, pl.n_qg_scan, pl.scan_matrix) == (4, 3, 6, 2, 0)
+    # a long streaming scan of a mixed-length batch (the mean well below the maximum) starts with the work-table kernel:
+    # one launch more, slots sized for the longest sequence's share of one round; a uniform batch does not
+    mixed = std_params(B=32, T=8, max_seq_len=131072, max_n_cmp=8191, avg_seq_len=40000)
+    pl = B.ssv_nsa_plan_query(mixed)
+    pl_u = B.ssv_nsa_plan_query(std_params(B=32, T=8, max_seq_len=131072, max_n_cmp=8191))
+    assert pl.scan_matrix == 0 and pl_u.scan_matrix == 0 and pl.n_launches == pl_u.n_launches + 1
+    assert 2 <= pl.n_cmp_chunks <= 16 and pl.workspace_bytes == B.ssv_nsa_workspace_bytes(mixed)
+    pl = B.ssv_nsa_plan_query(std_params(scan_kernel=B.SSV_SCAN_STREAM_TABLE))
+    assert pl.scan_matrix == 0 and pl.n_launches == 5
     # the matrix-core scan on request: any bf16 problem of the fused execution; its groups hold up to 256 rows
     pl = B.ssv_nsa_plan_query(std_params(scan_kernel=B.SSV_SCAN_MATRIX))
     assert (pl.scan_matrix, pl.C_scan, pl.n_qg_scan, pl.n_launches) == (1, 8, 1, 4)
     pl = B.ssv_nsa_plan_query(std_params(scan_kernel=B.SSV_SCAN_MATRIX, scan_group_size=3, mode=B.SSV_REUSE))
     assert (pl.scan_matrix, pl.C_scan, pl.n_qg_scan, pl.n_launches) == (1, 3, 3, 3)
-    for bad in (dict(scan_kernel=3), dict(scan_kernel=B.SSV_SCAN_MATRIX, exec=B.SSV_EXEC_UNFUSED),
+    for bad in (dict(scan_kernel=4), dict(scan_kernel=B.SSV_SCAN_STREAM_TABLE, exec=B.SSV_EXEC_UNFUSED), dict(scan_kernel=B.SSV_SCAN_MATRIX, exec=B.SSV_EXEC_UNFUSED),
                 dict(scan_kernel=B.SSV_SCAN_MATRIX, dtype=B.SSV_F32, d_k=64, d_v=64), dict(scan_kernel=B.SSV_SCAN_MATRIX, scan_group_size=17)):
         with pytest.raises(B.SsvError) as e:
             B.ssv_nsa_plan_query(std_params(**bad))

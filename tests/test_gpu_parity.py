@@ -591,3 +591,38 @@ def test_matrix_core_scan_large_batches(dev_mod, oracle):
         dev, ref, out, sel = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_MATRIX)
         assert dev.plan.scan_matrix == 1
         run_reuse(dev_mod, oracle, case, sel, dev=dev)
+
+
+def test_streaming_scan_work_table(dev_mod, oracle):
+    """The streaming kernel's compressed scan with its slices from the work table that a one-workgroup kernel builds
+    from the device-resident lengths (mixed-length batches): lengths over two orders of magnitude, sequences without
+    queries, without compressed rows and shorter than one tile, a tree, 128-row scan groups, fp32, refresh, reuse (all
+    branches in one launch) and the shared-index variant, against the oracle and against the even slices' selections."""
+    from paper_2605_19893_amd import binding as B
+    tree = si.tree_parents((3, 2), "bfs")
+    cases = [
+        si.make_case("tab_chain", "bf16", 7, 8, 64, 4, 192, 128, si.STD_NSA, [300, 26000, 40, 5200, 900, 13000, 2100], 901, rho=0.6,
+                     n_query=[8, 8, 5, 0, 8, 3, 8], poison_pad=True),
+        si.make_case("tab_tree", "bf16", 3, len(tree), 32, 2, 192, 128, si.STD_NSA, [1500, 21000, 6400], 903, rho=0.6, parents=tree),
+        si.make_case("tab_many", "bf16", 12, 4, 32, 2, 128, 128, si.STD_NSA, [260, 700, 330, 18000, 512, 96, 1300, 450, 15, 2000, 640, 800],
+                     905, rho=0.4),
+        si.make_case("tab_f32", "f32", 3, 4, 8, 2, 64, 64, si.STD_NSA, [3000, 200, 1200], 907, rho=0.5),
+        si.make_case("tab_none", "bf16", 2, 4, 32, 2, 192, 128, si.STD_NSA, [3000, 500], 909, rho=0.3, n_query=[0, 0]),
+    ]
+    for case in cases:
+        dev, ref, out, sel = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_STREAM_TABLE)
+        assert dev.plan.scan_matrix == 0
+        launches = dev.plan.n_launches
+        run_reuse(dev_mod, oracle, case, sel, dev=dev)
+        dev_e, _, out_e, sel_e = run_refresh(dev_mod, oracle, case, scan_kernel=B.SSV_SCAN_STREAM)
+        assert dev_e.plan.n_launches == launches - 1      # (the table kernel)
+        assert np.array_equal(sel_e, sel), case.name
+        # 128-row groups in the scan launch
+        dev_g = dev_mod.DeviceCase(case, scan_kernel=B.SSV_SCAN_STREAM_TABLE)
+        C = dev_g.plan.C
+        if 2 * C <= case.T:
+            dev_g.set_group_size(C, B.SSV_REFRESH, scan_group_size=2 * C)
+            dev_g.run()
+            out_g, sel_g = dev_g.results()
+            check(case, compare(case, oracle, ref, out_g, sel_g))
+    run_shared(dev_mod, oracle, cases[0], 2, scan_kernel=B.SSV_SCAN_STREAM_TABLE)
