@@ -573,6 +573,7 @@ LABELS = {
     "cfg2": "cfg2: B=16 L=65536 T=4 chain rho=0.7, 5% keys x4, H=64/4 d_k=192 d_v=128 l=32 d=16 l'=64 n=16 w=512",
     "cfg3": "cfg3: B=4 L=131072 T=40 tree (4,3,2) BFS order, same heads and NSA parameters",
     "cfg4": "cfg4: B=32 L log-uniform 4K..128K T=16 chain rho=0.7, same heads and NSA parameters",
+    "cfg4-t8": "cfg4-t8: the lengths of cfg4 with chains of 8 (128 rows per KV head: the streaming kernel scans, from its work table)",
 }
 
 
@@ -587,7 +588,8 @@ def main():
     ap.add_argument("--extras", action="store_true", help="warm-cache, graph-replay and back-to-back figures as well")
     ap.add_argument("--cold-only", action="store_true",
                     help="kept for the profiling commands: every launch of a trace runs on cold inputs (the default now)")
-    ap.add_argument("--only", default="", help="measure only this workload (cfg1, cfg2, cfg3 or cfg4; for profiling runs), "
+    ap.add_argument("--only", default="", help="measure only this workload (cfg1, cfg2, cfg3 or cfg4; for profiling runs; cfg4-t8: the lengths of cfg4 "
+                    "with chains of 8), "
                     "'shared': the shared-index study alone, at T = 8 and T = 32, or 'kernel-workload': the full grid of the "
                     "paper's isolated-kernel workload (32/8 heads of dimension 64, draft lengths 4 and 64, contexts 8K-64K), "
                     "or 'compress': the compressed-cache construction kernel")
@@ -641,6 +643,8 @@ def main():
         return
 
     makers = {"cfg1": lambda: si.config1(args.rho), "cfg2": si.config2, "cfg3": lambda: si.config3("bfs"), "cfg4": si.config4}
+    if args.only == "cfg4-t8":      # (not one of the named configurations: measured on request only)
+        makers["cfg4-t8"] = lambda: si.config4(T=8)
     headline = args.only if args.only in makers else "cfg2"
     order = [headline] if (args.only or args.no_extra) else [headline] + [t for t in makers if t != headline]
     results = {}
