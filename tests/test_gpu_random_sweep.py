@@ -68,3 +68,32 @@ def test_random_problem(seed, oracle):
     out3, sel3 = dev.results()
     check(case, compare(case, oracle, oracle.nsa_verify_shared(case, share), out3, sel3,
                         routed_by=oracle.group_representatives(case, share)))
+
+
+@pytest.mark.parametrize("seed", list(range(100, 116)))
+def test_random_problem_scan_variants(seed, oracle):
+    """The same random problems through the other homes of the compressed scan: the streaming kernel with its slices
+    from the work table, and (bf16) the matrix-core kernel, whose split is the balanced one whenever the lengths of the
+    batch differ in their tile counts; refresh, reuse and the shared-index variant."""
+    from paper_2605_19893_amd import SSV_REFRESH, SSV_REUSE, SSV_REFRESH_SHARED
+    from paper_2605_19893_amd import binding as B
+    from paper_2605_19893_amd.device_case import DeviceCase
+    case, _, _, share, fused = draw_case(seed)
+    kernels = [B.SSV_SCAN_STREAM_TABLE] + ([B.SSV_SCAN_MATRIX] if case.dtype == "bf16" else [])
+    ref = oracle.nsa_verify(case)
+    ref_shared = oracle.nsa_verify_shared(case, share)
+    for kern in kernels:
+        dev = DeviceCase(case, scan_kernel=kern, topn_home=B.SSV_TOPN_IN_SLC if fused else B.SSV_TOPN_SEPARATE)
+        print(f"[run] {case.name} scan_kernel={kern} B={case.B} T={case.T} H={case.H}/{case.H_kv} L={case.seq_lens.tolist()} "
+              f"nq={case.n_query.tolist()} tree={case.parents is not None} plan={dev.plan.as_dict()}", flush=True)
+        dev.run()
+        out, sel = dev.results()
+        check(case, compare(case, oracle, ref, out, sel))
+        dev.set_mode(SSV_REUSE)
+        dev.run()
+        out2, _ = dev.results()
+        check(case, compare(case, oracle, oracle.nsa_verify(case, sel_idx=sel), out2, sel, reuse_sel=sel))
+        dev.set_group_size(share, SSV_REFRESH_SHARED)
+        dev.run()
+        out3, sel3 = dev.results()
+        check(case, compare(case, oracle, ref_shared, out3, sel3, routed_by=oracle.group_representatives(case, share)))
