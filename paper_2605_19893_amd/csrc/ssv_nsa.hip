@@ -275,7 +275,7 @@ int make_layout(const ssv_nsa_params* p, Layout* lo) {
     // from a work table that a one-workgroup kernel builds from the device-resident lengths at the start of the call
     // (work_table.hpp).  One round: the resident workgroups that the launch's other branches leave, at least two items
     // per sequence; the slots per row bound the slices of the longest sequence (sized from the average, enforced by the
-    // table).  Only where the scan is long enough for the extra launch (about 4 us) to pay.
+    // table).  Only where the scan is long enough for the extra launch (5 to 7 us) to pay.
     lo->cmp_items_max = 0;
     const bool force_table = p->scan_kernel == SSV_SCAN_STREAM_TABLE;
     if (!unfused && !lo->scan32 && p->B <= kWorkTableMaxB &&
