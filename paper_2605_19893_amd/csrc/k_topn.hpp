@@ -15,7 +15,8 @@
 // the n_eff-th largest key overall (they are n_eff distinct keys), so every winner is >= the largest of
 // the four wavefronts' bounds; the (few) keys at or above it are compacted into a candidate list and
 // ranked by counting.  If the list overflows (massive ties), a
-// plain serial argmax over LDS takes over.
+// plain serial argmax over LDS takes over.  LDS keeps the importances as their 32-bit patterns (the index is the position;
+// keys are composed on the fly): 18 KB at 2048 blocks, eight workgroups per CU.
 #pragma once
 #include "device_common.hpp"
 
@@ -49,7 +50,7 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
 }
 
 __host__ __device__ inline size_t topn_lds_bytes(int max_blocks) {
-    return (size_t)max_blocks * 8 + kThreads * 8 + kMaxCand * 8 + 16 * 8 + kMaxNSel * 4 + kMaxT * 28 + 64;
+    return (((size_t)max_blocks * 4 + 15) & ~(size_t)15) + kThreads * 8 + kMaxCand * 8 + 16 * 8 + kMaxNSel * 4 + kMaxT * 28 + 64;
 }
 
 // ---- The same selection by ONE wavefront, for callers that have several queries to select for at once (the
@@ -259,10 +260,11 @@ __device__ __forceinline__ void wave_topn(const float* cs, int ncv, int J, int l
     }
 }
 
-__global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
+// (eight workgroups per CU: 64 registers)
+__global__ void __launch_bounds__(kThreads, 8) k_topn(const TopnArgs a) {
     extern __shared__ __align__(16) char smem[];
-    uint64_t* s_key = reinterpret_cast<uint64_t*>(smem);                  // [max_blocks]
-    uint64_t* s_best = s_key + a.max_blocks;                              // [256] per-thread best keys
+    uint32_t* s_bits = reinterpret_cast<uint32_t*>(smem);                 // [max_blocks] importance bit patterns (forced: +inf)
+    uint64_t* s_best = reinterpret_cast<uint64_t*>(smem + (((size_t)a.max_blocks * 4 + 15) & ~(size_t)15));   // [256] per-thread best keys
     uint64_t* s_cand = s_best + kThreads;                                 // [kMaxCand]
     uint64_t* s_red = s_cand + kMaxCand;                                  // [16]: threshold, counter, argmax scratch
     int* s_pick = reinterpret_cast<int*>(s_red + 16);                     // [kMaxNSel]
@@ -309,11 +311,45 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
     const int j_last_scored = J - max(a.n_local, 0);
     for (int j = max(j_last_scored + 1, 0); j <= J; ++j) {
         if ((j % kThreads) == tid) {          // the owner of block j
-            const uint64_t key = ((uint64_t)0x7F800000u << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
-            s_key[j] = key;
+            s_bits[j] = 0x7F800000u;
+            const uint64_t key = topn_key(0x7F800000u, j);
             best = key > best ? key : best;
         }
     }
+    if (a_ratio == 4 && b_ratio == 2) {
+        // the standard geometry: block j takes columns 4j-1 .. 4j+3 with weights 1 2 2 2 1; one 16-byte and one 4-byte
+        // load per block, four blocks per thread in flight (the same terms in the same order as the general form below;
+        // eight in flight would not fit the 64 registers that eight workgroups per CU leave)
+        constexpr int NF = 4;
+        for (int j0 = tid; j0 <= j_last_scored; j0 += kThreads * NF) {
+            f32x4 x[NF];
+            float xm[NF];
+#pragma unroll
+            for (int v = 0; v < NF; ++v) {
+                const int j = j0 + v * kThreads;
+                const int c0 = j <= j_last_scored ? 4 * j : 0;
+                // (a row holds nc_pitch columns, a multiple of 64: a block starting past it has no visible column)
+                x[v] = *reinterpret_cast<const f32x4*>(cs + (c0 < ncv ? c0 : 0));
+                xm[v] = cs[(c0 >= 1 && c0 - 1 < ncv) ? c0 - 1 : 0];
+            }
+#pragma unroll
+            for (int v = 0; v < NF; ++v) {
+                const int j = j0 + v * kThreads;
+                if (j > j_last_scored) continue;
+                const int c0 = 4 * j;
+                float imp = 0.f;
+                if (c0 >= 1 && c0 - 1 < ncv) imp += 1.f * xm[v];
+                if (c0 < ncv) imp += 2.f * x[v][0];
+                if (c0 + 1 < ncv) imp += 2.f * x[v][1];
+                if (c0 + 2 < ncv) imp += 2.f * x[v][2];
+                if (c0 + 3 < ncv) imp += 1.f * x[v][3];
+                const uint32_t bits = j < a.n_init ? 0x7F800000u : __float_as_uint(imp);
+                s_bits[j] = bits;
+                const uint64_t key = topn_key(bits, j);
+                best = key > best ? key : best;
+            }
+        }
+    } else
     for (int j0 = tid; j0 <= j_last_scored; j0 += kThreads * kBlocksPerBatch) {
         float imp[kBlocksPerBatch];
         if (n_terms <= kMaxImpTerms) {
@@ -353,8 +389,8 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
             if (j <= j_last_scored) {
                 const bool forced = j < a.n_init;
                 const uint32_t bits = forced ? 0x7F800000u : __float_as_uint(imp[v]);
-                const uint64_t key = ((uint64_t)bits << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
-                s_key[j] = key;
+                s_bits[j] = bits;
+                const uint64_t key = topn_key(bits, j);
                 best = key > best ? key : best;
             }
         }
@@ -376,7 +412,7 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
 #pragma unroll
     for (int k = 1; k < 4; ++k) thr = s_red[12 + k] > thr ? s_red[12 + k] : thr;
     for (int j = tid; j <= J; j += kThreads) {
-        const uint64_t key = s_key[j];
+        const uint64_t key = topn_key(s_bits[j], j);
         if (key >= thr) {
             const unsigned slot = atomicAdd(reinterpret_cast<unsigned*>(&s_red[1]), 1u);
             if (slot < kMaxCand) s_cand[slot] = key;
@@ -413,9 +449,13 @@ __global__ void __launch_bounds__(kThreads) k_topn(const TopnArgs a) {
             const int j_top = (int)(0xFFFFFFFFu - (uint32_t)top);
             if (tid == 0) s_pick[round] = j_top;
             if ((j_top % kThreads) == tid) {       // the owner retires the winner and rescans its blocks
-                s_key[j_top] = 0;
+                s_bits[j_top] = 0xFFFFFFFFu;       // retired (no importance has this pattern)
                 best = 0;
-                for (int j = tid; j <= J; j += kThreads) best = s_key[j] > best ? s_key[j] : best;
+                for (int j = tid; j <= J; j += kThreads) {
+                    const uint32_t bits = s_bits[j];
+                    const uint64_t key = topn_key(bits, j);
+                    if (bits != 0xFFFFFFFFu && key > best) best = key;
+                }
             }
         }
     }
