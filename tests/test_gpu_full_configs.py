@@ -86,3 +86,19 @@ def test_shared_index_variant_full_size(dev_mod, oracle, make, C):
     dev.run()
     out, sel = dev.results()
     check(case, compare(case, oracle, ref, out, sel, routed_by=routed_by))
+
+
+def test_config4_lengths_chains_of_8_work_table(dev_mod, oracle):
+    """The mixed lengths of configuration 4 with chains of 8 (128 rows per KV head: the streaming kernel scans): a
+    scan long enough for the automatic plan to start the call with the work-table kernel; every element and index
+    set, refresh and reuse, and the shared-index variant."""
+    from paper_2605_19893_amd import SSV_REFRESH_SHARED
+    case = si.config4(T=8)
+    dev, _, _, _ = _refresh_then_reuse(dev_mod, oracle, case)
+    assert dev.plan.scan_matrix == 0
+    ref = oracle.nsa_verify_shared(case, 4)
+    dev = dev_mod.DeviceCase(case, mode=SSV_REFRESH_SHARED, group_size=4)
+    assert dev.plan.n_launches == 5      # table kernel, scan + window, importance, selected branch (with the selection), combine
+    dev.run()
+    out, sel = dev.results()
+    check(case, compare(case, oracle, ref, out, sel, routed_by=oracle.group_representatives(case, 4)))
