@@ -81,7 +81,9 @@ class DeviceCase:
             need = max(need, B.ssv_nsa_workspace_bytes(self.params))
         if need > self.workspace_bytes:
             self.workspace_bytes = need
-            self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+            # (a byte pattern, not zeros: a call must not depend on what the scratch held before; 0x55.. reads as a large
+            # positive float, so a partial state that a call reads without having written it shows in the output)
+            self.workspace = torch.full((need,), 0x55, dtype=torch.uint8, device=self.device)
         self.set_mode(mode)
 
     def set_mode(self, mode: int) -> None:

@@ -378,15 +378,18 @@ def test_up_to_128_verifier_queries(dev_mod, oracle, shape):
         run_shared(dev_mod, oracle, case, 4)
 
 
-def test_calls_can_be_captured_in_a_hip_graph(dev_mod, oracle):
+@pytest.mark.parametrize("scan_kernel", [0, 2, 3])
+def test_calls_can_be_captured_in_a_hip_graph(dev_mod, oracle, scan_kernel):
     """A refresh call and a reuse call recorded into a HIP graph and replayed: the library allocates nothing,
     never synchronises and clears no memory with memset nodes, so every replay (with eager work and synchronisation
-    in between) must reproduce the eager result bit for bit."""
+    in between) must reproduce the eager result bit for bit.  The scratch is filled with a byte pattern between
+    replays: every slot, table and counter a call reads it has written itself.  With the automatic scan, the
+    matrix-core scan (its balanced split: the lengths differ) and the streaming scan from its work table."""
     import torch
     from paper_2605_19893_amd import SSV_REFRESH, SSV_REUSE
-    case = si.make_case("graph", "bf16", 2, 6, 32, 2, 192, 128, si.STD_NSA, [3001, 2222], 155, rho=0.5)
+    case = si.make_case("graph", "bf16", 3, 6, 32, 2, 192, 128, si.STD_NSA, [3001, 2222, 150], 155, rho=0.5, n_query=[6, 4, 6])
     ref = oracle.nsa_verify(case)
-    dev = dev_mod.DeviceCase(case)
+    dev = dev_mod.DeviceCase(case, scan_kernel=scan_kernel)
     dev.run()
     out_eager, sel_eager = dev.results()
     check(case, compare(case, oracle, ref, out_eager, sel_eager))
@@ -419,6 +422,7 @@ def test_calls_can_be_captured_in_a_hip_graph(dev_mod, oracle):
     torch.cuda.synchronize()
     for replay in range(2):
         dev.out.zero_()
+        dev.workspace.fill_(0x55)
         torch.cuda.synchronize()
         graph2.replay()
         out, _ = dev.results()
